@@ -1,0 +1,163 @@
+/*
+ * gbmw.h -- C ABI of the batched layer-wise strategy search for gfx950 (MI355X).
+ *
+ * The library solves, for a batch of B independent pipeline-stage searches
+ * (the planner calls the search once per stage, PP degree, batch size and
+ * partition: Algorithm 1 / Algorithm 2), the dynamic programme of Section
+ * 4.1.2, Eq. 3 of "Improving Automatic Parallel Training via Balanced Memory
+ * Workload Optimization":
+ *
+ *   C(l, e, s) = min_{s'} [ C(l-1, e - M(l,s), s') + R(l, s', s) ] + c(l, s)
+ *
+ * for EVERY forward-memory budget e = 0..E at once, where
+ *   c(l, s)      execution time of layer l under strategy s,
+ *   M(l, s)      forward memory O_f(l,s) + O_ms(l,s) of that choice, in budget
+ *                units (the amount Eq. 3 subtracts from E_fwd),
+ *   R(l, s', s)  cost of transforming layer l-1's output laid out for s' into
+ *                the layout s needs,
+ * and reads optimal plans back from the recorded argmins (Algorithm 3's S_min).
+ * Eq. 3 writes its state without the strategy index although R needs it; the
+ * state here carries it.  Layer 0 has no predecessor: C(0, e, s) = c(0, s) if
+ * e >= M(0, s).  Cells whose memory exceeds the budget are +infinity.
+ *
+ * Arithmetic: IEEE binary32; each transition is two separately rounded
+ * additions in the order (C_prev + R) + c; every minimum keeps the LOWEST index
+ * among equal candidates; a minimum over candidates that are all +infinity
+ * records index 0.  Results are bit-identical to a sequential evaluation in
+ * that order.
+ *
+ * All computation runs in HIP kernels on the current device; there is no CPU
+ * fallback.  Calls are not thread-safe with respect to one context.
+ */
+#ifndef GBMW_H
+#define GBMW_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gbmw_ctx gbmw_ctx; /* opaque; owned by the library */
+
+typedef enum {
+  GBMW_OK = 0,
+  GBMW_ERR_INVALID_ARG = 1, /* null pointer, size out of range, bad value in c/M/R */
+  GBMW_ERR_UNSUPPORTED = 2, /* request needs data the context did not keep */
+  GBMW_ERR_OOM = 3,         /* device or host allocation failed */
+  GBMW_ERR_DEVICE = 4       /* a HIP call failed; see gbmw_last_error() */
+} gbmw_status;
+
+enum { GBMW_PTR_HOST = 0, GBMW_PTR_DEVICE = 1 };
+
+enum {
+  GBMW_FLAG_KEEP_ALL_C = 1u,   /* keep every layer's fp32 table (default: last two) */
+  GBMW_FLAG_TIME_KERNELS = 2u  /* record a HIP event pair around every min-plus launch */
+};
+
+#define GBMW_MAX_S 256
+
+/*
+ * The problem statement.  L is always a host pointer.  c, M and R are all host
+ * pointers (ptr_space == GBMW_PTR_HOST; the library copies them to the device)
+ * or all device pointers (GBMW_PTR_DEVICE; used in place, must stay valid and
+ * unchanged until the solve has completed on `stream`).  Rows of instance b
+ * start at off_b = L[0] + ... + L[b-1]; sumL = L[0] + ... + L[B-1].
+ */
+typedef struct {
+  int32_t B;        /* number of instances, >= 1                               */
+  int32_t S;        /* strategies per layer, 1..GBMW_MAX_S (shared)            */
+  int32_t E;        /* forward budget in units, >= 0; tables have rows 0..E    */
+  const int32_t* L; /* [B] layers per instance, each >= 1                      */
+  const float* c;   /* [sumL][S]     c[off_b + l][s]  >= 0, +inf = forbidden   */
+  const int32_t* M; /* [sumL][S]     M[off_b + l][s]  >= 0                     */
+  const float* R;   /* [sumL][S][S]  R[off_b + l][s_prev][s] >= 0, +inf allowed;
+                       the l == 0 slab of every instance is ignored           */
+  int32_t ptr_space; /* GBMW_PTR_HOST or GBMW_PTR_DEVICE, for c, M and R       */
+  void* stream;      /* hipStream_t to enqueue on, or NULL for the null stream */
+} gbmw_problem;
+
+/*
+ * Fill the tables of all B instances (Eq. 3 for every l, e, s; then
+ * best(e) = min_s C(L_b - 1, e, s)).  Work is enqueued on p->stream and the call
+ * returns without waiting for it.
+ *
+ * *ctx is in/out: pass a pointer to NULL to get a new context; pass a context
+ * returned earlier to solve again into the same device buffers (they are
+ * re-allocated only if the new problem needs more room; a solve that reuses a
+ * context enqueues no allocation).  On error a new context is not created and a
+ * passed-in one stays valid but holds no solution.
+ *
+ * Host inputs are validated before anything is enqueued (GBMW_ERR_INVALID_ARG
+ * for NaN, negative or -inf in c/R, negative M, L < 1, sizes out of range).
+ * Device inputs are validated by a kernel; a violation makes the next
+ * gbmw_synchronize / gbmw_get_best / gbmw_backtrack / gbmw_export_tables on
+ * the context return GBMW_ERR_INVALID_ARG (the kernels never read or write out
+ * of bounds whatever the values are).
+ */
+gbmw_status gbmw_dp_solve_batched(const gbmw_problem* p, uint32_t flags, gbmw_ctx** ctx);
+
+/*
+ * Read plans back (Algorithm 3's strategy list, obtained by walking the argmin
+ * records from the last layer down).  Query i asks for instance q_instance[i]
+ * at budget q_e[i] (0 <= q_e <= E).  All five arrays are HOST pointers owned by
+ * the caller; the call waits for the solve and for its own kernel.
+ *   plan     [nq][Lmax] bytes, Lmax = max_b L_b; entries l >= L_b and every
+ *            entry of an infeasible query are 0xFF
+ *   cost     [nq] best(e_q) (+inf if infeasible)
+ *   mem_used [nq] sum_l M(l, s_l) of the plan (-1 if infeasible)
+ * An infeasible query is not an error.
+ */
+gbmw_status gbmw_backtrack(gbmw_ctx* ctx, int32_t nq, const int32_t* q_instance,
+                           const int32_t* q_e, uint8_t* plan, float* cost, int32_t* mem_used);
+
+/* Lmax of the last solve (row length of `plan` above); 0 if none. */
+int32_t gbmw_max_layers(const gbmw_ctx* ctx);
+
+/*
+ * best [B][E+1] fp32 and best_s [B][E+1] bytes (lowest-index argmin over s of
+ * the last layer; 0 where best is +inf), to HOST memory.  Either may be NULL.
+ * Waits for the solve.
+ */
+gbmw_status gbmw_get_best(gbmw_ctx* ctx, float* best, uint8_t* best_s);
+
+/*
+ * Copy the tables of layers [l0, l1) of one instance to HOST memory in the
+ * logical layout [l - l0][e][s] (s fastest, e = 0..E), whatever the device
+ * layout is.  C (fp32) and A (bytes) may each be NULL.  A[l][e'][s] is the
+ * predecessor strategy recorded for layer l (l >= 1) under s when e' units are
+ * left for layers < l (i.e. before layer l's own M is added); the l == 0 slab
+ * is returned as zeros.  Without GBMW_FLAG_KEEP_ALL_C only the last two layers
+ * of C exist: asking for others returns GBMW_ERR_UNSUPPORTED.  Waits for the
+ * solve.
+ */
+gbmw_status gbmw_export_tables(gbmw_ctx* ctx, int32_t instance, int32_t l0, int32_t l1,
+                               float* C, uint8_t* A);
+
+/* Wait for everything the context enqueued; reports deferred validation. */
+gbmw_status gbmw_synchronize(gbmw_ctx* ctx);
+
+/*
+ * Device time of the last solve, in milliseconds, from HIP events recorded on
+ * the solve's stream: total_ms spans the first kernel launch to the last
+ * kernel's completion; minplus_ms is the sum over the min-plus (Eq. 3 inner
+ * minimum, fused with the shift-add) launches and minplus_launches their count
+ * (both 0 unless the solve was given GBMW_FLAG_TIME_KERNELS).  Waits for the
+ * solve.  Any pointer may be NULL.
+ */
+gbmw_status gbmw_last_solve_ms(gbmw_ctx* ctx, float* total_ms, float* minplus_ms,
+                               int32_t* minplus_launches);
+
+/* Free the context and its device memory (waits first).  NULL is allowed. */
+void gbmw_destroy(gbmw_ctx* ctx);
+
+/* Message of the calling thread's most recent failure ("" if none). */
+const char* gbmw_last_error(void);
+
+/* Library / kernel variant description, e.g. for benchmark records. */
+const char* gbmw_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GBMW_H */

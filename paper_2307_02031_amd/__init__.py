@@ -1,0 +1,194 @@
+"""Python binding of libgbmw.so, the gfx950 library for the batched layer-wise
+strategy search (Section 4.1.2, Eq. 3 and Appendix A of the paper).
+
+The functions here have the names of the C entry points in include/gbmw.h and
+only marshal arguments: every step of the search runs in the library's HIP
+kernels.  There is no CPU fallback -- if the library has not been built
+(``python -m paper_2307_02031_amd.build``) importing this package raises.
+
+PyTorch is used for device memory and streams only: device-resident inputs are
+torch CUDA tensors whose ``data_ptr()`` is handed to the library, and work is
+enqueued on ``torch.cuda.current_stream()`` unless a stream is given.
+"""
+from __future__ import annotations
+
+import ctypes as ct
+import os
+
+import numpy as np
+import torch  # imported first so that the library binds to the same HIP runtime
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgbmw.so")
+
+GBMW_OK, GBMW_ERR_INVALID_ARG, GBMW_ERR_UNSUPPORTED, GBMW_ERR_OOM, GBMW_ERR_DEVICE = range(5)
+GBMW_PTR_HOST, GBMW_PTR_DEVICE = 0, 1
+GBMW_FLAG_KEEP_ALL_C = 1
+GBMW_FLAG_TIME_KERNELS = 2
+GBMW_MAX_S = 256
+
+EXPORTS = [
+    "gbmw_dp_solve_batched", "gbmw_backtrack", "gbmw_max_layers", "gbmw_get_best",
+    "gbmw_export_tables", "gbmw_synchronize", "gbmw_last_solve_ms", "gbmw_destroy",
+    "gbmw_last_error", "gbmw_version",
+]
+
+
+class gbmw_problem(ct.Structure):
+    _fields_ = [("B", ct.c_int32), ("S", ct.c_int32), ("E", ct.c_int32),
+                ("L", ct.c_void_p), ("c", ct.c_void_p), ("M", ct.c_void_p), ("R", ct.c_void_p),
+                ("ptr_space", ct.c_int32), ("stream", ct.c_void_p)]
+
+
+class GbmwError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"gbmw status {status}: {message}")
+        self.status = status
+
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2307_02031_amd.build` "
+                      "(there is no CPU fallback)")
+_lib = ct.CDLL(LIB_PATH)
+_lib.gbmw_dp_solve_batched.argtypes = [ct.POINTER(gbmw_problem), ct.c_uint32, ct.POINTER(ct.c_void_p)]
+_lib.gbmw_dp_solve_batched.restype = ct.c_int
+_lib.gbmw_backtrack.argtypes = [ct.c_void_p, ct.c_int32] + [ct.c_void_p] * 5
+_lib.gbmw_backtrack.restype = ct.c_int
+_lib.gbmw_max_layers.argtypes = [ct.c_void_p]
+_lib.gbmw_max_layers.restype = ct.c_int32
+_lib.gbmw_get_best.argtypes = [ct.c_void_p, ct.c_void_p, ct.c_void_p]
+_lib.gbmw_get_best.restype = ct.c_int
+_lib.gbmw_export_tables.argtypes = [ct.c_void_p, ct.c_int32, ct.c_int32, ct.c_int32, ct.c_void_p, ct.c_void_p]
+_lib.gbmw_export_tables.restype = ct.c_int
+_lib.gbmw_synchronize.argtypes = [ct.c_void_p]
+_lib.gbmw_synchronize.restype = ct.c_int
+_lib.gbmw_last_solve_ms.argtypes = [ct.c_void_p, ct.POINTER(ct.c_float), ct.POINTER(ct.c_float),
+                                    ct.POINTER(ct.c_int32)]
+_lib.gbmw_last_solve_ms.restype = ct.c_int
+_lib.gbmw_destroy.argtypes = [ct.c_void_p]
+_lib.gbmw_destroy.restype = None
+_lib.gbmw_last_error.restype = ct.c_char_p
+_lib.gbmw_version.restype = ct.c_char_p
+
+
+def gbmw_last_error() -> str:
+    return _lib.gbmw_last_error().decode()
+
+
+def gbmw_version() -> str:
+    return _lib.gbmw_version().decode()
+
+
+def _check(status: int):
+    if status != GBMW_OK:
+        raise GbmwError(status, gbmw_last_error())
+
+
+class Context:
+    """Owner of a gbmw_ctx*; keeps the arrays handed to the library alive."""
+
+    def __init__(self):
+        self.handle = ct.c_void_p(None)
+        self.B = self.S = self.E = 0
+        self.L = None
+        self._keep = ()
+
+    def __del__(self):
+        try:
+            gbmw_destroy(self)
+        except Exception:
+            pass
+
+
+def _ptr(a):
+    if isinstance(a, torch.Tensor):
+        return a.data_ptr()
+    return a.ctypes.data
+
+
+def gbmw_dp_solve_batched(L, c, M, R, S: int, E: int, flags: int = 0, ctx: Context | None = None,
+                          stream: int | None = None) -> Context:
+    """Enqueue the table fill for B = len(L) instances.
+
+    c [sumL][S] f32, M [sumL][S] i32, R [sumL][S][S] f32: either all numpy
+    arrays (host) or all torch CUDA tensors (device, used in place).  Returns
+    the context (a new one unless ``ctx`` is given)."""
+    L = np.ascontiguousarray(L, dtype=np.int32)
+    on_dev = isinstance(c, torch.Tensor)
+    if on_dev:
+        assert all(isinstance(x, torch.Tensor) and x.is_cuda and x.is_contiguous() for x in (c, M, R))
+        assert c.dtype == torch.float32 and M.dtype == torch.int32 and R.dtype == torch.float32
+    else:
+        c = np.ascontiguousarray(c, dtype=np.float32)
+        M = np.ascontiguousarray(M, dtype=np.int32)
+        R = np.ascontiguousarray(R, dtype=np.float32)
+    sumL = int(L.sum())
+    assert tuple(c.shape) == (sumL, S) and tuple(M.shape) == (sumL, S) and tuple(R.shape) == (sumL, S, S)
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else 0
+    p = gbmw_problem(len(L), S, E, L.ctypes.data, _ptr(c), _ptr(M), _ptr(R),
+                     GBMW_PTR_DEVICE if on_dev else GBMW_PTR_HOST, stream)
+    if ctx is None:
+        ctx = Context()
+    _check(_lib.gbmw_dp_solve_batched(ct.byref(p), flags, ct.byref(ctx.handle)))
+    ctx.B, ctx.S, ctx.E, ctx.L = len(L), S, E, L
+    ctx._keep = (L, c, M, R)
+    return ctx
+
+
+def gbmw_synchronize(ctx: Context) -> None:
+    _check(_lib.gbmw_synchronize(ctx.handle))
+
+
+def gbmw_max_layers(ctx: Context) -> int:
+    return int(_lib.gbmw_max_layers(ctx.handle))
+
+
+def gbmw_get_best(ctx: Context):
+    """best [B][E+1] float32, best_s [B][E+1] uint8 (host arrays)."""
+    best = np.empty((ctx.B, ctx.E + 1), np.float32)
+    best_s = np.empty((ctx.B, ctx.E + 1), np.uint8)
+    _check(_lib.gbmw_get_best(ctx.handle, best.ctypes.data, best_s.ctypes.data))
+    return best, best_s
+
+
+def gbmw_backtrack(ctx: Context, q_instance, q_e):
+    """plan [nq][Lmax] uint8 (0xFF padded), cost [nq] float32, mem_used [nq] int32."""
+    qi = np.ascontiguousarray(q_instance, dtype=np.int32)
+    qe = np.ascontiguousarray(q_e, dtype=np.int32)
+    assert qi.shape == qe.shape and qi.ndim == 1
+    nq, Lmax = len(qi), gbmw_max_layers(ctx)
+    plan = np.empty((nq, Lmax), np.uint8)
+    cost = np.empty(nq, np.float32)
+    mem = np.empty(nq, np.int32)
+    _check(_lib.gbmw_backtrack(ctx.handle, nq, qi.ctypes.data, qe.ctypes.data, plan.ctypes.data,
+                               cost.ctypes.data, mem.ctypes.data))
+    return plan, cost, mem
+
+
+def gbmw_export_tables(ctx: Context, instance: int, l0: int = 0, l1: int | None = None,
+                       want_C: bool = True, want_A: bool = True):
+    """C [l1-l0][E+1][S] float32 and A [l1-l0][E+1][S] uint8 (None if not wanted)."""
+    if l1 is None:
+        l1 = int(ctx.L[instance])
+    n = max(0, l1 - l0)
+    C = np.empty((n, ctx.E + 1, ctx.S), np.float32) if want_C else None
+    A = np.empty((n, ctx.E + 1, ctx.S), np.uint8) if want_A else None
+    _check(_lib.gbmw_export_tables(ctx.handle, instance, l0, l1,
+                                   C.ctypes.data if want_C else None,
+                                   A.ctypes.data if want_A else None))
+    return C, A
+
+
+def gbmw_last_solve_ms(ctx: Context):
+    """(total_ms, minplus_ms, minplus_launches) of the last solve."""
+    a, b, n = ct.c_float(), ct.c_float(), ct.c_int32()
+    _check(_lib.gbmw_last_solve_ms(ctx.handle, ct.byref(a), ct.byref(b), ct.byref(n)))
+    return a.value, b.value, n.value
+
+
+def gbmw_destroy(ctx: Context) -> None:
+    if ctx.handle:
+        _lib.gbmw_destroy(ctx.handle)
+        ctx.handle = ct.c_void_p(None)
+        ctx._keep = ()

@@ -1,0 +1,395 @@
+// C-ABI layer of the batched layer-wise strategy search: argument checking,
+// device buffers, the per-layer launch sequence, result read-back.  See
+// include/gbmw.h for the contract of every entry point.
+#include "../../include/gbmw.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <numeric>
+#include <vector>
+
+#include "gbmw_kernels.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+gbmw_status fail(gbmw_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+#define HIP_TRY(expr)                                                                       \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess) {                                                                 \
+      (void)hipGetLastError();                                                              \
+      return fail(e_ == hipErrorOutOfMemory ? GBMW_ERR_OOM : GBMW_ERR_DEVICE, "%s: %s",     \
+                  #expr, hipGetErrorString(e_));                                            \
+    }                                                                                       \
+  } while (0)
+
+struct DevBuf {
+  void* p = nullptr;
+  size_t cap = 0;
+  gbmw_status reserve(size_t bytes) {
+    if (bytes <= cap) return GBMW_OK;
+    if (p) { (void)hipFree(p); p = nullptr; cap = 0; }
+    if (bytes == 0) return GBMW_OK;
+    HIP_TRY(hipMalloc(&p, bytes));
+    cap = bytes;
+    return GBMW_OK;
+  }
+  void release() {
+    if (p) (void)hipFree(p);
+    p = nullptr;
+    cap = 0;
+  }
+};
+
+}  // namespace
+
+struct gbmw_ctx {
+  int device = 0;
+  hipStream_t stream = nullptr;
+  bool solved = false;
+  uint32_t flags = 0;
+  int B = 0, S = 0, SP = 0, E = 0, EP = 0, sumL = 0, Lmax = 0;
+  std::vector<int> L, off, perm, n_active;   // n_active[l] = #{b : L_b > l}
+  gbmw::Tables t{};
+  DevBuf d_L, d_off, d_perm, d_c, d_M, d_R, d_Rt, d_C, d_A, d_best, d_best_s, d_status, d_q,
+      d_stage;
+  hipEvent_t ev0 = nullptr, ev1 = nullptr;
+  std::vector<hipEvent_t> ev_layer;          // pairs around min-plus launches
+  int timed_launches = 0;
+};
+
+namespace {
+
+void free_ctx(gbmw_ctx* c) {
+  if (!c) return;
+  (void)hipSetDevice(c->device);
+  (void)hipStreamSynchronize(c->stream);
+  for (DevBuf* b : {&c->d_L, &c->d_off, &c->d_perm, &c->d_c, &c->d_M, &c->d_R, &c->d_Rt, &c->d_C,
+                    &c->d_A, &c->d_best, &c->d_best_s, &c->d_status, &c->d_q, &c->d_stage})
+    b->release();
+  if (c->ev0) (void)hipEventDestroy(c->ev0);
+  if (c->ev1) (void)hipEventDestroy(c->ev1);
+  for (hipEvent_t e : c->ev_layer) (void)hipEventDestroy(e);
+  delete c;
+}
+
+gbmw_status check_host_values(const gbmw_problem* p, const std::vector<int>& L,
+                              const std::vector<int>& off) {
+  const int S = p->S;
+  const size_t sumL = (size_t)off.back() + L.back();
+  for (size_t i = 0; i < sumL * S; ++i) {
+    if (!(p->c[i] >= 0.0f)) return fail(GBMW_ERR_INVALID_ARG, "c[%zu] is NaN or negative", i);
+    if (p->M[i] < 0) return fail(GBMW_ERR_INVALID_ARG, "M[%zu] is negative", i);
+  }
+  for (int b = 0; b < p->B; ++b)
+    for (size_t i = ((size_t)off[b] + 1) * S * S; i < ((size_t)off[b] + L[b]) * S * S; ++i)
+      if (!(p->R[i] >= 0.0f)) return fail(GBMW_ERR_INVALID_ARG, "R[%zu] is NaN or negative", i);
+  return GBMW_OK;
+}
+
+gbmw_status wait_and_check(gbmw_ctx* c) {
+  if (!c) return fail(GBMW_ERR_INVALID_ARG, "null context");
+  if (!c->solved) return fail(GBMW_ERR_INVALID_ARG, "context holds no solution");
+  HIP_TRY(hipSetDevice(c->device));
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  int status = 0;
+  HIP_TRY(hipMemcpy(&status, c->d_status.p, sizeof(int), hipMemcpyDeviceToHost));
+  if (status)
+    return fail(GBMW_ERR_INVALID_ARG, "device inputs rejected:%s%s%s",
+                (status & 1) ? " c has NaN/negative values;" : "",
+                (status & 2) ? " M has negative values;" : "",
+                (status & 4) ? " R has NaN/negative values;" : "");
+  return GBMW_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* gbmw_last_error(void) { return g_err; }
+
+const char* gbmw_version(void) {
+  return "gbmw 0.1 (gfx950; fused min-plus/argmin/shift-add; [s][e] tables)";
+}
+
+gbmw_status gbmw_dp_solve_batched(const gbmw_problem* p, uint32_t flags, gbmw_ctx** out) {
+  g_err[0] = 0;
+  if (!p || !out) return fail(GBMW_ERR_INVALID_ARG, "null problem or context pointer");
+  if (!p->L || !p->c || !p->M || !p->R) return fail(GBMW_ERR_INVALID_ARG, "null L/c/M/R");
+  if (p->B < 1 || p->B > 65535) return fail(GBMW_ERR_INVALID_ARG, "B=%d not in 1..65535", p->B);
+  if (p->S < 1 || p->S > GBMW_MAX_S) return fail(GBMW_ERR_INVALID_ARG, "S=%d not in 1..256", p->S);
+  if (p->E < 0 || p->E > (1 << 30)) return fail(GBMW_ERR_INVALID_ARG, "E=%d out of range", p->E);
+  if (p->ptr_space != GBMW_PTR_HOST && p->ptr_space != GBMW_PTR_DEVICE)
+    return fail(GBMW_ERR_INVALID_ARG, "ptr_space=%d", p->ptr_space);
+  if (flags & ~(uint32_t)(GBMW_FLAG_KEEP_ALL_C | GBMW_FLAG_TIME_KERNELS))
+    return fail(GBMW_ERR_INVALID_ARG, "unknown flag bits 0x%x", flags);
+
+  const int B = p->B, S = p->S, E = p->E;
+  std::vector<int> L(p->L, p->L + B), off(B), perm(B);
+  long long sum = 0;
+  int Lmax = 0;
+  for (int b = 0; b < B; ++b) {
+    if (L[b] < 1) return fail(GBMW_ERR_INVALID_ARG, "L[%d]=%d < 1", b, L[b]);
+    off[b] = (int)sum;
+    sum += L[b];
+    Lmax = std::max(Lmax, L[b]);
+    if (sum > (1 << 24)) return fail(GBMW_ERR_INVALID_ARG, "sum of L too large");
+  }
+  const int sumL = (int)sum;
+  if (p->ptr_space == GBMW_PTR_HOST) {
+    gbmw_status st = check_host_values(p, L, off);
+    if (st != GBMW_OK) return st;
+  }
+  std::iota(perm.begin(), perm.end(), 0);
+  std::stable_sort(perm.begin(), perm.end(), [&](int a, int b) { return L[a] > L[b]; });
+  std::vector<int> n_active(Lmax + 1, 0);
+  for (int l = 0; l <= Lmax; ++l)
+    n_active[l] = (int)std::count_if(L.begin(), L.end(), [&](int x) { return x > l; });
+
+  gbmw_ctx* c = *out;
+  const bool fresh = (c == nullptr);
+  if (fresh) {
+    c = new (std::nothrow) gbmw_ctx();
+    if (!c) return fail(GBMW_ERR_OOM, "host allocation failed");
+    if (hipGetDevice(&c->device) != hipSuccess) {
+      delete c;
+      return fail(GBMW_ERR_DEVICE, "no HIP device available");
+    }
+  }
+  c->solved = false;
+
+  auto bail = [&](gbmw_status st) {
+    if (fresh) free_ctx(c);
+    return st;
+  };
+#define TRY(expr)                       \
+  do {                                  \
+    gbmw_status s_ = (expr);            \
+    if (s_ != GBMW_OK) return bail(s_); \
+  } while (0)
+#define HIP_TRY_B(expr)                                                                        \
+  do {                                                                                         \
+    hipError_t e_ = (expr);                                                                    \
+    if (e_ != hipSuccess) {                                                                    \
+      (void)hipGetLastError();                                                                 \
+      return bail(fail(e_ == hipErrorOutOfMemory ? GBMW_ERR_OOM : GBMW_ERR_DEVICE, "%s: %s",   \
+                       #expr, hipGetErrorString(e_)));                                         \
+    }                                                                                          \
+  } while (0)
+
+  HIP_TRY_B(hipSetDevice(c->device));
+  hipStream_t st = (hipStream_t)p->stream;
+  c->stream = st;
+  c->flags = flags;
+  c->B = B; c->S = S; c->E = E; c->sumL = sumL; c->Lmax = Lmax;
+  c->SP = (S + 3) / 4 * 4;
+  c->EP = (E + 1 + 255) / 256 * 256;
+  c->L = L; c->off = off; c->perm = perm; c->n_active = n_active;
+  const int SP = c->SP, EP = c->EP;
+  const bool keep = (flags & GBMW_FLAG_KEEP_ALL_C) != 0;
+  const size_t slab = (size_t)S * EP;
+
+  TRY(c->d_L.reserve(sizeof(int) * B));
+  TRY(c->d_off.reserve(sizeof(int) * B));
+  TRY(c->d_perm.reserve(sizeof(int) * B));
+  TRY(c->d_status.reserve(sizeof(int)));
+  TRY(c->d_Rt.reserve(sizeof(float) * (size_t)sumL * SP * SP));
+  TRY(c->d_C.reserve(sizeof(float) * slab * (keep ? (size_t)sumL : (size_t)2 * B)));
+  TRY(c->d_A.reserve(slab * (size_t)sumL));
+  TRY(c->d_best.reserve(sizeof(float) * (size_t)B * EP));
+  TRY(c->d_best_s.reserve((size_t)B * EP));
+  if (!c->ev0) {
+    HIP_TRY_B(hipEventCreate(&c->ev0));
+    HIP_TRY_B(hipEventCreate(&c->ev1));
+  }
+
+  const float *dc, *dR;
+  const int* dM;
+  if (p->ptr_space == GBMW_PTR_HOST) {
+    TRY(c->d_c.reserve(sizeof(float) * (size_t)sumL * S));
+    TRY(c->d_M.reserve(sizeof(int) * (size_t)sumL * S));
+    TRY(c->d_R.reserve(sizeof(float) * (size_t)sumL * S * S));
+    HIP_TRY_B(hipMemcpyAsync(c->d_c.p, p->c, sizeof(float) * (size_t)sumL * S, hipMemcpyHostToDevice, st));
+    HIP_TRY_B(hipMemcpyAsync(c->d_M.p, p->M, sizeof(int) * (size_t)sumL * S, hipMemcpyHostToDevice, st));
+    HIP_TRY_B(hipMemcpyAsync(c->d_R.p, p->R, sizeof(float) * (size_t)sumL * S * S, hipMemcpyHostToDevice, st));
+    dc = (const float*)c->d_c.p; dM = (const int*)c->d_M.p; dR = (const float*)c->d_R.p;
+  } else {
+    dc = p->c; dM = p->M; dR = p->R;
+  }
+  // The small index arrays come from host vectors owned by the context, which
+  // outlive the copies.
+  HIP_TRY_B(hipMemcpyAsync(c->d_L.p, c->L.data(), sizeof(int) * B, hipMemcpyHostToDevice, st));
+  HIP_TRY_B(hipMemcpyAsync(c->d_off.p, c->off.data(), sizeof(int) * B, hipMemcpyHostToDevice, st));
+  HIP_TRY_B(hipMemcpyAsync(c->d_perm.p, c->perm.data(), sizeof(int) * B, hipMemcpyHostToDevice, st));
+
+  gbmw::Tables& t = c->t;
+  t.B = B; t.S = S; t.SP = SP; t.E = E; t.EP = EP; t.keep_all = keep ? 1 : 0;
+  t.L = (const int*)c->d_L.p; t.off = (const int*)c->d_off.p; t.perm = (const int*)c->d_perm.p;
+  t.c = dc; t.M = dM; t.Rt = (const float*)c->d_Rt.p;
+  t.Cbuf = (float*)c->d_C.p; t.A = (uint8_t*)c->d_A.p;
+  t.best = (float*)c->d_best.p; t.best_s = (uint8_t*)c->d_best_s.p;
+  t.status = (int*)c->d_status.p;
+
+  const bool timed = (flags & GBMW_FLAG_TIME_KERNELS) != 0;
+  c->timed_launches = 0;
+  if (timed) {
+    while ((int)c->ev_layer.size() < 2 * Lmax) {
+      hipEvent_t e;
+      HIP_TRY_B(hipEventCreate(&e));
+      c->ev_layer.push_back(e);
+    }
+  }
+
+  HIP_TRY_B(hipEventRecord(c->ev0, st));
+  gbmw::launch_prepare(t, dR, sumL, p->ptr_space == GBMW_PTR_DEVICE, st);
+  gbmw::launch_init_layer0(t, st);
+  for (int l = 1; l < Lmax; ++l) {
+    if (timed) HIP_TRY_B(hipEventRecord(c->ev_layer[2 * c->timed_launches], st));
+    gbmw::launch_minplus(t, l, n_active[l], st);
+    if (timed) {
+      HIP_TRY_B(hipEventRecord(c->ev_layer[2 * c->timed_launches + 1], st));
+      ++c->timed_launches;
+    }
+  }
+  gbmw::launch_final(t, st);
+  HIP_TRY_B(hipEventRecord(c->ev1, st));
+  HIP_TRY_B(hipGetLastError());
+#undef TRY
+#undef HIP_TRY_B
+  c->solved = true;
+  *out = c;
+  return GBMW_OK;
+}
+
+gbmw_status gbmw_synchronize(gbmw_ctx* ctx) {
+  g_err[0] = 0;
+  return wait_and_check(ctx);
+}
+
+int32_t gbmw_max_layers(const gbmw_ctx* ctx) { return (ctx && ctx->solved) ? ctx->Lmax : 0; }
+
+gbmw_status gbmw_get_best(gbmw_ctx* c, float* best, uint8_t* best_s) {
+  g_err[0] = 0;
+  gbmw_status st = wait_and_check(c);
+  if (st != GBMW_OK) return st;
+  const size_t w = (size_t)c->E + 1;
+  if (best)
+    HIP_TRY(hipMemcpy2D(best, w * sizeof(float), c->d_best.p, (size_t)c->EP * sizeof(float),
+                        w * sizeof(float), c->B, hipMemcpyDeviceToHost));
+  if (best_s)
+    HIP_TRY(hipMemcpy2D(best_s, w, c->d_best_s.p, (size_t)c->EP, w, c->B, hipMemcpyDeviceToHost));
+  return GBMW_OK;
+}
+
+gbmw_status gbmw_backtrack(gbmw_ctx* c, int32_t nq, const int32_t* q_instance, const int32_t* q_e,
+                           uint8_t* plan, float* cost, int32_t* mem_used) {
+  g_err[0] = 0;
+  gbmw_status st = wait_and_check(c);
+  if (st != GBMW_OK) return st;
+  if (nq < 0) return fail(GBMW_ERR_INVALID_ARG, "nq=%d", nq);
+  if (nq == 0) return GBMW_OK;
+  if (!q_instance || !q_e || !plan || !cost || !mem_used)
+    return fail(GBMW_ERR_INVALID_ARG, "null query or output pointer");
+  for (int i = 0; i < nq; ++i) {
+    if (q_instance[i] < 0 || q_instance[i] >= c->B)
+      return fail(GBMW_ERR_INVALID_ARG, "q_instance[%d]=%d not in 0..%d", i, q_instance[i], c->B - 1);
+    if (q_e[i] < 0 || q_e[i] > c->E)
+      return fail(GBMW_ERR_INVALID_ARG, "q_e[%d]=%d not in 0..%d", i, q_e[i], c->E);
+  }
+  const size_t n = (size_t)nq, Lm = (size_t)c->Lmax;
+  // one device block: q_inst | q_e | cost | mem | plan
+  const size_t bytes = n * (4 * sizeof(int)) + n * Lm;
+  st = c->d_q.reserve(bytes);
+  if (st != GBMW_OK) return st;
+  int* d_qi = (int*)c->d_q.p;
+  int* d_qe = d_qi + n;
+  float* d_cost = (float*)(d_qe + n);
+  int* d_mem = (int*)(d_cost + n);
+  uint8_t* d_plan = (uint8_t*)(d_mem + n);
+  HIP_TRY(hipMemcpyAsync(d_qi, q_instance, n * sizeof(int), hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(hipMemcpyAsync(d_qe, q_e, n * sizeof(int), hipMemcpyHostToDevice, c->stream));
+  gbmw::launch_backtrack(c->t, nq, d_qi, d_qe, c->Lmax, d_plan, d_cost, d_mem, c->stream);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipMemcpyAsync(cost, d_cost, n * sizeof(float), hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(hipMemcpyAsync(mem_used, d_mem, n * sizeof(int), hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(hipMemcpyAsync(plan, d_plan, n * Lm, hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  return GBMW_OK;
+}
+
+gbmw_status gbmw_export_tables(gbmw_ctx* c, int32_t inst, int32_t l0, int32_t l1, float* C,
+                               uint8_t* A) {
+  g_err[0] = 0;
+  gbmw_status st = wait_and_check(c);
+  if (st != GBMW_OK) return st;
+  if (inst < 0 || inst >= c->B) return fail(GBMW_ERR_INVALID_ARG, "instance=%d", inst);
+  const int Lb = c->L[inst];
+  if (l0 < 0 || l1 > Lb || l0 > l1) return fail(GBMW_ERR_INVALID_ARG, "layers [%d,%d) of %d", l0, l1, Lb);
+  if (l0 == l1) return GBMW_OK;
+  const bool keep = (c->flags & GBMW_FLAG_KEEP_ALL_C) != 0;
+  if (C && !keep && l0 < Lb - 2)
+    return fail(GBMW_ERR_UNSUPPORTED, "only the last two layers of C were kept (asked for layer %d of %d)", l0, Lb);
+  const size_t rows = (size_t)c->E + 1, S = (size_t)c->S, slab = S * c->EP;
+  const int row0 = c->off[inst];
+  // one layer at a time through a staging buffer of [E+1][S] floats
+  st = c->d_stage.reserve(rows * S * sizeof(float));
+  if (st != GBMW_OK) return st;
+  for (int l = l0; l < l1; ++l) {
+    if (C) {
+      const float* src = keep ? (const float*)c->d_C.p + (size_t)(row0 + l) * slab
+                              : (const float*)c->d_C.p + ((size_t)(l & 1) * c->B + inst) * slab;
+      gbmw::launch_export_f32(src, (float*)c->d_stage.p, 1, c->S, c->E, c->EP, c->stream);
+      HIP_TRY(hipGetLastError());
+      HIP_TRY(hipMemcpyAsync(C + (size_t)(l - l0) * rows * S, c->d_stage.p, rows * S * sizeof(float),
+                             hipMemcpyDeviceToHost, c->stream));
+      HIP_TRY(hipStreamSynchronize(c->stream));
+    }
+    if (A) {
+      uint8_t* dst = A + (size_t)(l - l0) * rows * S;
+      if (l == 0) {
+        memset(dst, 0, rows * S);
+      } else {
+        gbmw::launch_export_u8((const uint8_t*)c->d_A.p + (size_t)(row0 + l) * slab,
+                               (uint8_t*)c->d_stage.p, 1, c->S, c->E, c->EP, c->stream);
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(hipMemcpyAsync(dst, c->d_stage.p, rows * S, hipMemcpyDeviceToHost, c->stream));
+        HIP_TRY(hipStreamSynchronize(c->stream));
+      }
+    }
+  }
+  return GBMW_OK;
+}
+
+gbmw_status gbmw_last_solve_ms(gbmw_ctx* c, float* total_ms, float* minplus_ms,
+                               int32_t* minplus_launches) {
+  g_err[0] = 0;
+  gbmw_status st = wait_and_check(c);
+  if (st != GBMW_OK) return st;
+  if (total_ms) HIP_TRY(hipEventElapsedTime(total_ms, c->ev0, c->ev1));
+  float sum = 0.0f;
+  for (int i = 0; i < c->timed_launches; ++i) {
+    float ms = 0.0f;
+    HIP_TRY(hipEventElapsedTime(&ms, c->ev_layer[2 * i], c->ev_layer[2 * i + 1]));
+    sum += ms;
+  }
+  if (minplus_ms) *minplus_ms = sum;
+  if (minplus_launches) *minplus_launches = c->timed_launches;
+  return GBMW_OK;
+}
+
+void gbmw_destroy(gbmw_ctx* ctx) { free_ctx(ctx); }
+
+}  // extern "C"

@@ -1,0 +1,54 @@
+// Internal launch interface between the C-ABI layer (gbmw_api.hip) and the
+// gfx950 kernels (gbmw_kernels.hip).  Not installed; not part of the ABI.
+//
+// Device data layout ("SoA by strategy", budget axis contiguous):
+//   C table of one (instance, layer):  float  [S][EP]   C[s*EP + e]
+//   A table of one (instance, layer):  uint8  [S][EP]   A[s*EP + e']
+//   EP = (E + 1) rounded up to a multiple of 256 (row stride in elements)
+//   Rt: transposed, padded transformation cost  float [sumL][SP][SP],
+//       Rt[row][s][s'] = R[row][s'][s], zero in the padding; SP = S rounded up
+//       to a multiple of 4.  A wave's 64 lanes hold 64 consecutive budgets e
+//       of one strategy, so every table access is a coalesced 256-byte
+//       segment and every R / c / M operand is wave-uniform.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gbmw {
+
+struct Tables {
+  int B, S, SP, E, EP;
+  int keep_all;        // 1: Call[row][S][EP] for every layer row; 0: rolling pair
+  const int* L;        // [B]   device
+  const int* off;      // [B]   device, first row of each instance
+  const int* perm;     // [B]   device, instances ordered by L descending
+  const float* c;      // [sumL][S]
+  const int* M;        // [sumL][S]
+  const float* Rt;     // [sumL][SP][SP]
+  float* Cbuf;         // keep_all ? [sumL][S][EP] : [2][B][S][EP]
+  uint8_t* A;          // [sumL][S][EP]
+  float* best;         // [B][EP]
+  uint8_t* best_s;     // [B][EP]
+  int* status;         // device word; bit 0: bad c, bit 1: bad M, bit 2: bad R
+};
+
+// R -> Rt (transpose + pad) and validation of device-resident inputs.
+void launch_prepare(const Tables& t, const float* R, int sumL, bool validate, hipStream_t st);
+// C(0, e, s) for every instance.
+void launch_init_layer0(const Tables& t, hipStream_t st);
+// One layer l >= 1 for the first n_active instances of perm (those with L_b > l):
+// min-plus product with argmin, fused with the shift by M(l,s), the + c(l,s)
+// and the +inf prefix.
+void launch_minplus(const Tables& t, int l, int n_active, hipStream_t st);
+// best(e), best_s(e) over the last layer of every instance.
+void launch_final(const Tables& t, hipStream_t st);
+// Plans for nq queries (all pointers device).
+void launch_backtrack(const Tables& t, int nq, const int* q_inst, const int* q_e, int Lmax,
+                      uint8_t* plan, float* cost, int* mem_used, hipStream_t st);
+// [S][EP] -> [E+1][S] for rows [row0, row0+n) of C (fp32; base pointer given) or A (bytes).
+void launch_export_f32(const float* src, float* dst, int n, int S, int E, int EP, hipStream_t st);
+void launch_export_u8(const uint8_t* src, uint8_t* dst, int n, int S, int E, int EP, hipStream_t st);
+
+const char* minplus_variant(int S);
+
+}  // namespace gbmw

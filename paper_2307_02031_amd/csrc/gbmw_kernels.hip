@@ -1,0 +1,349 @@
+// gfx950 kernels of the batched layer-wise strategy search (Section 4.1.2,
+// Eq. 3; Appendix A, Algorithm 3 of the paper).  See gbmw_kernels.h for the
+// device layout.  (min,+) is not a multiply-accumulate, so the matrix cores
+// are not used: the work is fp32 VALU adds and mins with wave-uniform R
+// operands, streamed along the budget axis.
+#include "gbmw_kernels.h"
+
+#include <math.h>
+
+namespace gbmw {
+
+#define GBMW_AS4 __attribute__((address_space(4)))
+typedef const GBMW_AS4 float* cf32_t;   // uniform, read-only -> scalar loads
+typedef const GBMW_AS4 int* ci32_t;
+
+template <typename T>
+__device__ __forceinline__ const GBMW_AS4 T* as_const(const T* p) {
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Wold-style-cast"
+  return (const GBMW_AS4 T*)(p);
+#pragma clang diagnostic pop
+}
+
+__device__ __forceinline__ float* c_table(const Tables& t, int inst, int row, int l) {
+  const size_t slab = (size_t)t.S * t.EP;
+  return t.keep_all ? t.Cbuf + (size_t)row * slab
+                    : t.Cbuf + ((size_t)(l & 1) * t.B + inst) * slab;
+}
+
+// ---------------------------------------------------------------------------
+// prepare: Rt[row][s][s'] = R[row][s'][s] (zero padding) + input validation
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_prepare(Tables t, const float* __restrict__ R, int sumL,
+                                                 int validate, float* __restrict__ Rt) {
+  const int SP = t.SP, S = t.S;
+  const size_t n = (size_t)sumL * SP * SP;
+  int bad = 0;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+       i += (size_t)gridDim.x * blockDim.x) {
+    const int sp = (int)(i % SP);
+    const int s = (int)((i / SP) % SP);
+    const size_t row = i / ((size_t)SP * SP);
+    float v = 0.0f;
+    if (s < S && sp < S) {
+      v = R[(row * S + sp) * S + s];
+    }
+    Rt[i] = v;
+  }
+  if (validate) {
+    const size_t m = (size_t)sumL * S;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < m;
+         i += (size_t)gridDim.x * blockDim.x) {
+      if (!(t.c[i] >= 0.0f)) bad |= 1;
+      if (t.M[i] < 0) bad |= 2;
+    }
+    if (bad) atomicOr(t.status, bad);
+  }
+}
+
+// R is validated per instance because the l == 0 slab is ignored by contract
+// and may hold anything.
+__global__ __launch_bounds__(256) void k_validate_R(Tables t, const float* __restrict__ R) {
+  const int inst = blockIdx.y;
+  const int S = t.S;
+  const int Lb = t.L[inst];
+  const size_t base = ((size_t)t.off[inst] + 1) * S * S;   // skip layer 0
+  const size_t n = (size_t)(Lb - 1) * S * S;
+  int bad = 0;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+       i += (size_t)gridDim.x * blockDim.x)
+    if (!(R[base + i] >= 0.0f)) bad = 4;
+  if (bad) atomicOr(t.status, bad);
+}
+
+__global__ void k_clear_status(int* status) { *status = 0; }
+
+void launch_prepare(const Tables& t, const float* R, int sumL, bool validate, hipStream_t st) {
+  // a fill kernel rather than a memset node, so that the sequence can be captured
+  hipLaunchKernelGGL(k_clear_status, dim3(1), dim3(1), 0, st, t.status);
+  const size_t n = (size_t)sumL * t.SP * t.SP;
+  int blocks = (int)((n + 255) / 256);
+  if (blocks > 65536) blocks = 65536;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(k_prepare, dim3(blocks), dim3(256), 0, st, t, R, sumL, validate ? 1 : 0,
+                     const_cast<float*>(t.Rt));
+  if (validate) hipLaunchKernelGGL(k_validate_R, dim3(64, t.B), dim3(256), 0, st, t, R);
+}
+
+// ---------------------------------------------------------------------------
+// layer 0:  C(0, e, s) = e >= M(0, s) ? c(0, s) : +inf
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_init_layer0(Tables t) {
+  const int inst = blockIdx.z, s = blockIdx.y;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e > t.E) return;
+  const int row = t.off[inst];
+  const int m = t.M[(size_t)row * t.S + s];
+  const float cs = t.c[(size_t)row * t.S + s];
+  float* C0 = c_table(t, inst, row, 0);
+  C0[(size_t)s * t.EP + e] = (m >= 0 && e >= m) ? cs : INFINITY;
+}
+
+void launch_init_layer0(const Tables& t, hipStream_t st) {
+  hipLaunchKernelGGL(k_init_layer0, dim3((t.E + 256) / 256, t.S, t.B), dim3(256), 0, st, t);
+}
+
+// ---------------------------------------------------------------------------
+// min-plus + argmin + shift-add, register-blocked.
+//   wave: 64*K consecutive budgets e' of one instance; lane owns e' = e0 + 64*j.
+//   The SP values C_{l-1}[e'][0..SP) of each owned e' stay in VGPRs for the
+//   whole kernel; R_l[.][s] arrives as scalar operands, one row of Rt per
+//   output strategy s.
+// ---------------------------------------------------------------------------
+template <int SP, int K, int NW>
+__global__ __launch_bounds__(64 * NW) void k_minplus(Tables t, int l, int tiles) {
+  const int inst = t.perm[blockIdx.x / tiles];
+  const int tile = blockIdx.x % tiles;
+  const int S = t.S, E = t.E, EP = t.EP;
+  const int row = t.off[inst] + l;
+  const float* __restrict__ Cp = c_table(t, inst, row - 1, l - 1);
+  float* __restrict__ Cn = c_table(t, inst, row, l);
+  uint8_t* __restrict__ An = t.A + (size_t)row * S * EP;
+
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int e0 = (tile * NW + wave) * (64 * K) + lane;
+
+  float cp[K][SP];
+#pragma unroll
+  for (int sp = 0; sp < SP; ++sp) {
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+      const int e = e0 + 64 * j;
+      cp[j][sp] = (sp < S && e <= E) ? Cp[(size_t)sp * EP + e] : INFINITY;
+    }
+  }
+
+  cf32_t Rrow = as_const(t.Rt) + (size_t)row * SP * SP;
+  cf32_t crow = as_const(t.c) + (size_t)row * S;
+  ci32_t Mrow = as_const(t.M) + (size_t)row * S;
+
+  for (int s = 0; s < S; ++s) {
+    float r[SP];
+#pragma unroll
+    for (int sp = 0; sp < SP; ++sp) r[sp] = Rrow[s * SP + sp];
+
+    float tmin[K];
+    int arg[K];
+#pragma unroll
+    for (int j = 0; j < K; ++j) { tmin[j] = INFINITY; arg[j] = 0; }
+#pragma unroll
+    for (int sp = 0; sp < SP; ++sp) {
+#pragma unroll
+      for (int j = 0; j < K; ++j) {
+        const float x = cp[j][sp] + r[sp];
+        const bool lt = x < tmin[j];
+        tmin[j] = lt ? x : tmin[j];
+        arg[j] = lt ? sp : arg[j];
+      }
+    }
+
+    const int m = Mrow[s];
+    const float cs = crow[s];
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+      const int e = e0 + 64 * j;                       // pre-shift budget e'
+      if (e <= E) {
+        An[(size_t)s * EP + e] = (uint8_t)arg[j];
+        if (m >= 0 && m <= E - e) Cn[(size_t)s * EP + e + m] = tmin[j] + cs;
+        if (m < 0 || e < m) Cn[(size_t)s * EP + e] = INFINITY;
+      }
+    }
+  }
+}
+
+// Any S up to 256: the C_{l-1} tile of 64 budgets is staged in LDS as
+// [S][64]; wave w handles output strategies w, w+4, ...
+__global__ __launch_bounds__(256) void k_minplus_generic(Tables t, int l, int tiles) {
+  extern __shared__ float lds[];
+  const int inst = t.perm[blockIdx.x / tiles];
+  const int tile = blockIdx.x % tiles;
+  const int S = t.S, SP = t.SP, E = t.E, EP = t.EP;
+  const int row = t.off[inst] + l;
+  const float* __restrict__ Cp = c_table(t, inst, row - 1, l - 1);
+  float* __restrict__ Cn = c_table(t, inst, row, l);
+  uint8_t* __restrict__ An = t.A + (size_t)row * S * EP;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int e = tile * 64 + lane;
+
+  for (int sp = wave; sp < S; sp += 4)
+    lds[sp * 64 + lane] = (e <= E) ? Cp[(size_t)sp * EP + e] : INFINITY;
+  __syncthreads();
+
+  cf32_t Rrow = as_const(t.Rt) + (size_t)row * SP * SP;
+  for (int s = wave; s < S; s += 4) {
+    float tmin = INFINITY;
+    int arg = 0;
+    for (int sp = 0; sp < S; ++sp) {
+      const float x = lds[sp * 64 + lane] + Rrow[s * SP + sp];
+      if (x < tmin) { tmin = x; arg = sp; }
+    }
+    const int m = t.M[(size_t)row * S + s];
+    const float cs = t.c[(size_t)row * S + s];
+    if (e <= E) {
+      An[(size_t)s * EP + e] = (uint8_t)arg;
+      if (m >= 0 && m <= E - e) Cn[(size_t)s * EP + e + m] = tmin + cs;
+      if (m < 0 || e < m) Cn[(size_t)s * EP + e] = INFINITY;
+    }
+  }
+}
+
+template <int SP>
+struct Blocking {                       // budgets per lane for a given strategy count
+  static constexpr int K = (SP <= 24) ? 4 : 2;
+  static constexpr int NW = 4;
+};
+
+template <int SP>
+static void launch_minplus_sp(const Tables& t, int l, int n_active, hipStream_t st) {
+  constexpr int K = Blocking<SP>::K, NW = Blocking<SP>::NW;
+  const int tiles = (t.E + 1 + 64 * K * NW - 1) / (64 * K * NW);
+  hipLaunchKernelGGL((k_minplus<SP, K, NW>), dim3((unsigned)tiles * n_active), dim3(64 * NW), 0, st,
+                     t, l, tiles);
+}
+
+void launch_minplus(const Tables& t, int l, int n_active, hipStream_t st) {
+  if (n_active <= 0) return;
+  switch (t.SP) {
+#define GBMW_CASE(N) case N: launch_minplus_sp<N>(t, l, n_active, st); return;
+    GBMW_CASE(4) GBMW_CASE(8) GBMW_CASE(12) GBMW_CASE(16) GBMW_CASE(20) GBMW_CASE(24)
+    GBMW_CASE(28) GBMW_CASE(32) GBMW_CASE(36) GBMW_CASE(40) GBMW_CASE(44) GBMW_CASE(48)
+    GBMW_CASE(52) GBMW_CASE(56) GBMW_CASE(60) GBMW_CASE(64)
+#undef GBMW_CASE
+    default: break;
+  }
+  const int tiles = (t.E + 64) / 64;
+  hipLaunchKernelGGL(k_minplus_generic, dim3((unsigned)tiles * n_active), dim3(256),
+                     (size_t)t.S * 64 * sizeof(float), st, t, l, tiles);
+}
+
+const char* minplus_variant(int S) {
+  return S <= 64 ? "register-blocked, scalar R operands, in-loop argmin"
+                 : "generic LDS-staged (S > 64)";
+}
+
+// ---------------------------------------------------------------------------
+// final reduce: best(e) = min_s C(L_b - 1, e, s), lowest-index argmin
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_final(Tables t) {
+  const int inst = blockIdx.y;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e > t.E) return;
+  const int l = t.L[inst] - 1;
+  const float* __restrict__ C = c_table(t, inst, t.off[inst] + l, l);
+  float b = INFINITY;
+  int a = 0;
+  for (int s = 0; s < t.S; ++s) {
+    const float x = C[(size_t)s * t.EP + e];
+    if (x < b) { b = x; a = s; }
+  }
+  t.best[(size_t)inst * t.EP + e] = b;
+  t.best_s[(size_t)inst * t.EP + e] = (uint8_t)a;
+}
+
+void launch_final(const Tables& t, hipStream_t st) {
+  hipLaunchKernelGGL(k_final, dim3((t.E + 256) / 256, t.B), dim3(256), 0, st, t);
+}
+
+// ---------------------------------------------------------------------------
+// backtrack: one lane per query walks the argmin records from the last layer
+// down; each step is one dependent byte gather.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void k_backtrack(Tables t, int nq, const int* __restrict__ q_inst,
+                                                  const int* __restrict__ q_e, int Lmax,
+                                                  uint8_t* __restrict__ plan,
+                                                  float* __restrict__ cost,
+                                                  int* __restrict__ mem_used) {
+  const int q = blockIdx.x * 64 + threadIdx.x;
+  if (q >= nq) return;
+  const int inst = q_inst[q];
+  int e = q_e[q];
+  uint8_t* p = plan + (size_t)q * Lmax;
+  const int Lb = t.L[inst];
+  const float b = t.best[(size_t)inst * t.EP + e];
+  cost[q] = b;
+  if (b == INFINITY) {
+    for (int l = 0; l < Lmax; ++l) p[l] = 0xFF;
+    mem_used[q] = -1;
+    return;
+  }
+  for (int l = Lb; l < Lmax; ++l) p[l] = 0xFF;
+  int s = t.best_s[(size_t)inst * t.EP + e];
+  const int row0 = t.off[inst];
+  int mem = 0;
+  for (int l = Lb - 1; l >= 1; --l) {
+    p[l] = (uint8_t)s;
+    const int m = t.M[(size_t)(row0 + l) * t.S + s];
+    mem += m;
+    e -= m;                                            // budget left for layers < l
+    if (m < 0 || e < 0) { mem = -2; break; }           // only reachable with invalid inputs
+    s = t.A[((size_t)(row0 + l) * t.S + s) * t.EP + e];
+  }
+  if (mem != -2) {
+    p[0] = (uint8_t)s;
+    mem += t.M[(size_t)row0 * t.S + s];
+  }
+  mem_used[q] = mem;
+}
+
+void launch_backtrack(const Tables& t, int nq, const int* q_inst, const int* q_e, int Lmax,
+                      uint8_t* plan, float* cost, int* mem_used, hipStream_t st) {
+  if (nq <= 0) return;
+  hipLaunchKernelGGL(k_backtrack, dim3((nq + 63) / 64), dim3(64), 0, st, t, nq, q_inst, q_e, Lmax,
+                     plan, cost, mem_used);
+}
+
+// ---------------------------------------------------------------------------
+// export: device [n][S][EP] -> logical [n][E+1][S] through a 64x64 LDS tile
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void k_export(const T* __restrict__ src, T* __restrict__ dst, int S,
+                                                int E, int EP) {
+  __shared__ T tile[64][65];
+  const int n = blockIdx.z;
+  const int e0 = blockIdx.x * 64, s0 = blockIdx.y * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const T* in = src + (size_t)n * S * EP;
+  T* out = dst + (size_t)n * (E + 1) * S;
+  for (int i = ty; i < 64; i += 4) {
+    const int s = s0 + i, e = e0 + tx;
+    if (s < S && e <= E) tile[i][tx] = in[(size_t)s * EP + e];
+  }
+  __syncthreads();
+  for (int i = ty; i < 64; i += 4) {
+    const int e = e0 + i, s = s0 + tx;
+    if (s < S && e <= E) out[(size_t)e * S + s] = tile[tx][i];
+  }
+}
+
+void launch_export_f32(const float* src, float* dst, int n, int S, int E, int EP, hipStream_t st) {
+  hipLaunchKernelGGL(k_export<float>, dim3((E + 64) / 64, (S + 63) / 64, n), dim3(256), 0, st, src,
+                     dst, S, E, EP);
+}
+void launch_export_u8(const uint8_t* src, uint8_t* dst, int n, int S, int E, int EP,
+                      hipStream_t st) {
+  hipLaunchKernelGGL(k_export<uint8_t>, dim3((E + 64) / 64, (S + 63) / 64, n), dim3(256), 0, st,
+                     src, dst, S, E, EP);
+}
+
+}  // namespace gbmw

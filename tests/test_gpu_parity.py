@@ -1,0 +1,204 @@
+"""GPU library vs CPU oracle, bit for bit, through the C ABI (needs an MI355X)."""
+import numpy as np
+import pytest
+
+import gbmw_inputs as gi
+import oracle
+import pins
+from gpu_util import check_instance, check_plans_by_definition, solve_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def g():
+    import paper_2307_02031_amd as g
+    return g
+
+
+def _log(msg):
+    print(msg, flush=True)
+
+
+@pytest.mark.parametrize("k", [1, 2, 3])
+def test_single_configs_full_tables(g, k):
+    p = gi.make_config(k)
+    _log(f"config {k}: {p.name}")
+    ctx = solve_gpu(p, flags=g.GBMW_FLAG_KEEP_ALL_C)
+    q = None if k > 1 else list(range(p.E + 1))
+    check_instance(g, ctx, p, 0, full_C=True, q_es=q)
+    g.gbmw_destroy(ctx)
+
+
+def test_config1_against_brute_force(g):
+    """The GPU's best[e] against the enumeration of all 4^4 plans directly."""
+    p = gi.make_config(1)
+    ctx = solve_gpu(p)
+    best, _ = g.gbmw_get_best(ctx)
+    opt, argopt = pins.py_bruteforce(p.c, p.M, p.R, p.E)
+    pins.assert_same_f32(best[0], opt)
+    plan, cost, mem = g.gbmw_backtrack(ctx, np.zeros(p.E + 1, np.int32), np.arange(p.E + 1, dtype=np.int32))
+    for e in range(p.E + 1):
+        if np.isfinite(opt[e]):
+            assert tuple(int(x) for x in plan[e]) in argopt[e]
+
+
+SHAPES = [  # (S, E, list of L): ragged tails, tile boundaries, every kernel variant
+    (1, 300, [1, 5, 3]),
+    (2, 0, [3, 1]),
+    (3, 1, [2, 4]),
+    (4, 63, [4, 2, 6]),
+    (5, 64, [3]),
+    (7, 255, [5, 2]),
+    (8, 256, [2, 7]),
+    (13, 257, [4]),
+    (22, 1000, [6, 3, 9]),
+    (24, 1023, [3]),
+    (31, 2049, [4, 2]),
+    (44, 3000, [5, 8, 2]),
+    (45, 700, [3, 3]),
+    (64, 1500, [4, 6]),
+    (65, 500, [3, 2]),       # above 64: LDS-staged generic kernel
+    (100, 300, [3]),
+    (256, 130, [2, 3]),
+]
+
+
+@pytest.mark.parametrize("S,E,Ls", SHAPES, ids=[f"S{s}-E{e}" for s, e, _ in SHAPES])
+@pytest.mark.parametrize("device_inputs", [False, True], ids=["host", "device"])
+def test_ragged_batches_all_shapes(g, S, E, Ls, device_inputs):
+    _log(f"S={S} E={E} L={Ls} device_inputs={device_inputs}")
+    Mhi = max(2, E // 3 + 1)
+    parts = [gi.random_instance(1000 + 17 * S + i, L, S, E, M_rng=(0 if E == 0 else 1, Mhi),
+                                R_rng=(0.0, 4.0)) for i, L in enumerate(Ls)]
+    p = gi.stack(parts, f"S{S}E{E}")
+    ctx = solve_gpu(p, flags=g.GBMW_FLAG_KEEP_ALL_C, device_inputs=device_inputs)
+    for b in range(p.B):
+        check_instance(g, ctx, p, b, full_C=True, q_es=list(range(0, E + 1, max(1, E // 40))) + [E])
+    g.gbmw_destroy(ctx)
+
+
+def test_rolling_tables_keep_the_last_two_layers(g):
+    p = gi.stack([gi.random_instance(50 + i, L, 6, 400, M_rng=(1, 90)) for i, L in enumerate([5, 2, 8, 1])], "roll")
+    ctx = solve_gpu(p, flags=0)
+    for b in range(p.B):
+        check_instance(g, ctx, p, b, full_C=False)
+    with pytest.raises(g.GbmwError) as ei:
+        g.gbmw_export_tables(ctx, 2, 0, 8)
+    assert ei.value.status == g.GBMW_ERR_UNSUPPORTED
+    g.gbmw_destroy(ctx)
+
+
+def test_degenerate_inputs(g):
+    cases = []
+    # budget below every first-layer memory: everything infeasible
+    cases.append(gi.random_instance(304, 3, 3, 4, M_rng=(5, 9)))
+    # zero memory everywhere: e = 0 is feasible
+    cases.append(gi.random_instance(305, 3, 2, 7, M_rng=(0, 0)))
+    # memories larger than E and mixed
+    p = gi.random_instance(306, 4, 5, 100, M_rng=(1, 40))
+    p.M[1, 2] = 1000; p.M[2, :] = [0, 101, 100, 50, 2**31 - 1]
+    cases.append(p)
+    # +inf costs (forbidden strategy / transition)
+    p = gi.random_instance(307, 4, 3, 60, M_rng=(1, 12))
+    p.c[1, 2] = np.inf; p.R[2, 0, 1] = np.inf; p.R[3, :, 0] = np.inf
+    cases.append(p)
+    # duplicated columns: every minimum ties, lowest index must win
+    q = gi.random_instance(308, 5, 4, 200, M_rng=(1, 30))
+    cases.append(gi.Problem(1, 12, 200, q.L, np.tile(q.c, (1, 3)), np.tile(q.M, (1, 3)),
+                            np.tile(q.R, (1, 3, 3)), "dup"))
+    # all-equal costs and zero R: massive ties
+    q = gi.random_instance(309, 6, 9, 150, M_rng=(1, 20))
+    q.c[:] = 1.0; q.R[:] = 0.0
+    cases.append(q)
+    # subnormal and huge magnitudes
+    q = gi.random_instance(310, 5, 6, 120, M_rng=(1, 20))
+    q.c[:] = (q.c * np.float32(1e-42)).astype(np.float32)
+    q.R[:] = (q.R * np.float32(3e-43)).astype(np.float32)
+    assert (q.c > 0).all() and q.c.max() < 1.2e-38
+    cases.append(q)
+    q = gi.random_instance(311, 5, 6, 120, M_rng=(1, 20), c_rng=(1e37, 3e38), R_rng=(0.0, 3e38))
+    cases.append(q)
+    for p in cases:
+        _log(f"degenerate case {p.name}")
+        ctx = solve_gpu(p, flags=g.GBMW_FLAG_KEEP_ALL_C)
+        ref = check_instance(g, ctx, p, 0, full_C=True, q_es=list(range(p.E + 1)))
+        assert not np.isnan(ref.C).any()
+        g.gbmw_destroy(ctx)
+
+
+def test_context_reuse_and_errors(g):
+    import torch
+    a = gi.stack([gi.random_instance(70 + i, L, 10, 900, M_rng=(1, 200)) for i, L in enumerate([4, 6])], "a")
+    b = gi.stack([gi.random_instance(80 + i, L, 7, 300, M_rng=(1, 50)) for i, L in enumerate([3, 2, 5])], "b")
+    ctx = solve_gpu(a, flags=g.GBMW_FLAG_KEEP_ALL_C)
+    check_instance(g, ctx, a, 1, full_C=True)
+    ctx = solve_gpu(b, flags=g.GBMW_FLAG_KEEP_ALL_C | g.GBMW_FLAG_TIME_KERNELS, ctx=ctx)   # smaller: same buffers
+    for i in range(3):
+        check_instance(g, ctx, b, i, full_C=True)
+    total, mp, n = g.gbmw_last_solve_ms(ctx)
+    assert total > 0 and mp > 0 and n == 4 and mp <= total * 1.05
+    ctx = solve_gpu(a, flags=0, ctx=ctx)                                 # larger again
+    check_instance(g, ctx, a, 0, full_C=False)
+    # bad queries
+    with pytest.raises(g.GbmwError):
+        g.gbmw_backtrack(ctx, [2], [10])
+    with pytest.raises(g.GbmwError):
+        g.gbmw_backtrack(ctx, [0], [901])
+    plan, cost, mem = g.gbmw_backtrack(ctx, np.zeros(0, np.int32), np.zeros(0, np.int32))
+    assert plan.shape == (0, 6)
+    # device-resident inputs with a bad value: reported at synchronize
+    c = torch.from_numpy(b.c).cuda(); M = torch.from_numpy(b.M).cuda(); R = torch.from_numpy(b.R).cuda()
+    M[1, 1] = -5
+    ctx2 = g.gbmw_dp_solve_batched(b.L, c, M, R, b.S, b.E)
+    with pytest.raises(g.GbmwError) as ei:
+        g.gbmw_synchronize(ctx2)
+    assert ei.value.status == g.GBMW_ERR_INVALID_ARG and "M" in str(ei.value)
+    M[1, 1] = 5; R[3, 1, 2] = float("nan")        # row 3 = instance 1, layer 0: ignored slab
+    ctx2 = g.gbmw_dp_solve_batched(b.L, c, M, R, b.S, b.E, ctx=ctx2)
+    g.gbmw_synchronize(ctx2)
+    R[4, 1, 2] = float("nan")
+    ctx2 = g.gbmw_dp_solve_batched(b.L, c, M, R, b.S, b.E, ctx=ctx2)
+    with pytest.raises(g.GbmwError):
+        g.gbmw_get_best(ctx2)
+    g.gbmw_destroy(ctx2)
+    g.gbmw_destroy(ctx)
+
+
+def test_non_default_stream(g):
+    import torch
+    p = gi.random_instance(90, 6, 22, 2000, M_rng=(1, 300))
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        ctx = solve_gpu(p, flags=g.GBMW_FLAG_KEEP_ALL_C, device_inputs=True)
+    check_instance(g, ctx, p, 0, full_C=True)
+    g.gbmw_destroy(ctx)
+
+
+def test_config4_batched_full_size(g):
+    """All 64 instances in the launch configuration the benchmark times; full A,
+    last two layers of C, best, plans against the oracle for every instance."""
+    p = gi.make_config(4)
+    ctx = solve_gpu(p, flags=0, device_inputs=True)
+    best, best_s = g.gbmw_get_best(ctx)
+    for b in range(p.B):
+        _log(f"cfg4 instance {b} L={p.L[b]}")
+        check_instance(g, ctx, p, b, full_C=False, best=best, best_s=best_s)
+    g.gbmw_destroy(ctx)
+
+
+def test_config5_large_batched_full_size(g):
+    """B=16, L=96, S=64, E=65536 in one solve.  Two instances are compared with
+    the oracle cell by cell (A, last layers of C, best, plans); all sixteen are
+    checked through properties that hold at any size."""
+    p = gi.make_config(5)
+    ctx = solve_gpu(p, flags=0, device_inputs=True)
+    best, best_s = g.gbmw_get_best(ctx)
+    for b in (0, 11):
+        _log(f"cfg5 instance {b}: oracle comparison")
+        check_instance(g, ctx, p, b, full_C=False, best=best, best_s=best_s)
+    q = sorted(set(list(range(0, p.E + 1, 997)) + [p.E, p.E - 1, 12288, 12287]))
+    for b in range(p.B):
+        _log(f"cfg5 instance {b}: plan properties")
+        check_plans_by_definition(g, ctx, p, b, q, best)
+    g.gbmw_destroy(ctx)
