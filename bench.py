@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched layer-wise strategy search on one MI355X.
+
+A "step" is one complete solve of the workload through the C ABI: R transpose
+and input validation, layer-0 init, one fused min-plus/argmin/shift-add launch
+per layer, final reduce -- everything Eq. 3 needs for every budget e and every
+instance -- with the inputs already resident in HBM and a reused context (no
+allocation inside the timed region).
+
+Prints ONE JSON line.  metric = DP cell-updates/s with the nominal count
+sum_b L_b * E * S * S'; `value_executed` uses the count the kernels really
+perform, sum_b (L_b - 1) * (E + 1) * S * S' (layer 0 has no contraction), and
+that count is what the roofline fraction is based on.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# One plain (non-packed, non-FMA) fp32 VALU instruction retires 64 lanes per CU
+# per clock: 256 CU x 64 lanes x 2.4 GHz.  The published 157.3 TFLOP/s vector
+# figure is this x2 (packed) x2 (FMA counts as two), neither of which an
+# add/min mix can use.
+PEAK_PLAIN_FP32_TOPS = 256 * 64 * 2.4e9 / 1e12
+PEAK_PUBLISHED_FP32_TFLOPS = 157.3
+OPS_PER_UPDATE = 2          # one add + one min: the algorithmic minimum
+
+
+def solve_steps(g, torch, p, d, steps, warmup, flags=0):
+    ctx = None
+    for _ in range(max(1, warmup)):
+        ctx = g.gbmw_dp_solve_batched(p.L, d[0], d[1], d[2], p.S, p.E, flags=flags, ctx=ctx)
+    g.gbmw_synchronize(ctx)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        ctx = g.gbmw_dp_solve_batched(p.L, d[0], d[1], d[2], p.S, p.E, flags=flags, ctx=ctx)
+    g.gbmw_synchronize(ctx)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    return ctx, dt / steps
+
+
+def to_device(torch, p):
+    return (torch.from_numpy(p.c).cuda(), torch.from_numpy(p.M).cuda(), torch.from_numpy(p.R).cuda())
+
+
+def cpu_baseline(p, budget_s=12.0):
+    """The oracle as it stands, all host threads, on as many leading instances
+    of the workload as fit in about budget_s seconds."""
+    import oracle
+    threads = min(oracle.max_threads(), 16)
+    done_nominal = 0
+    done_exec = 0
+    t_used = 0.0
+    n = 0
+    for b in range(p.B):
+        o, Lb = int(p.offsets[b]), int(p.L[b])
+        t0 = time.perf_counter()
+        oracle.solve(p.c[o:o + Lb], p.M[o:o + Lb], p.R[o:o + Lb], p.E, keep_C=False, keep_A=True,
+                     nthreads=threads)
+        t_used += time.perf_counter() - t0
+        done_nominal += Lb * p.E * p.S * p.S
+        done_exec += (Lb - 1) * (p.E + 1) * p.S * p.S
+        n += 1
+        if t_used > budget_s:
+            break
+    return {"value": done_nominal / t_used, "unit": "cell-updates/s", "cores": threads,
+            "kind": "oracle", "value_executed": done_exec / t_used,
+            "sample": f"first {n} of {p.B} instances of the workload, {t_used:.1f} s of oracle time, "
+                      f"OpenMP over budget rows"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4, help="workload 1..5 (default: the batched config)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other configs")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; the search shards by instance with no "
+              "communication, but no multi-GPU figure is produced here.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import gbmw_inputs as gi
+    import paper_2307_02031_amd as g
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+
+    p = gi.make_config(args.config)
+    d = to_device(torch, p)
+    ctx, sec = solve_steps(g, torch, p, d, args.steps, args.warmup)
+    nominal, executed = p.nominal_updates(), p.executed_updates()
+
+    # the dominant kernel, timed live with HIP event pairs on the solve's stream
+    tctx = None
+    mp_ms = mp_n = tot_ms = 0.0
+    reps = max(3, min(args.steps, 10))
+    for _ in range(reps):
+        tctx = g.gbmw_dp_solve_batched(p.L, d[0], d[1], d[2], p.S, p.E, flags=g.GBMW_FLAG_TIME_KERNELS, ctx=tctx)
+        a, b, n = g.gbmw_last_solve_ms(tctx)
+        tot_ms += a; mp_ms += b; mp_n += n
+    g.gbmw_destroy(tctx)
+    launches_per_solve = mp_n / reps
+    avg_launch_ms = mp_ms / mp_n if mp_n else float("nan")
+    ops_per_launch = OPS_PER_UPDATE * executed / launches_per_solve if mp_n else 0.0
+    achieved = ops_per_launch / (avg_launch_ms * 1e-3) / 1e12 if mp_n else 0.0
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_cfg{args.config}.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get("hbm_bytes_per_launch")
+    roofline = {
+        "bound": "alu", "kernel": "k_minplus (fused min-plus + argmin + shift-add)",
+        "achieved": achieved, "peak": PEAK_PLAIN_FP32_TOPS, "unit": "TFLOP/s",
+        "frac": achieved / PEAK_PLAIN_FP32_TOPS, "traffic": traffic,
+        "ops_per_update": OPS_PER_UPDATE, "updates_per_launch": executed / launches_per_solve if mp_n else 0,
+        "avg_launch_ms": avg_launch_ms, "launches_per_solve": launches_per_solve,
+        "frac_of_published_fp32_vector_peak": achieved / PEAK_PUBLISHED_FP32_TFLOPS,
+        "algorithmic_bytes_per_launch": 9.0 * executed / p.S / launches_per_solve if mp_n else 0,
+        "hbm_GBps_algorithmic": (9.0 * executed / p.S / launches_per_solve) / (avg_launch_ms * 1e-3) / 1e9 if mp_n else 0,
+        "kernel_share_of_solve": mp_ms / tot_ms if tot_ms else None,
+    }
+
+    out = {
+        "metric": "DP cell-updates/s (B*L*E*S*S')", "value": nominal / sec, "unit": "cell-updates/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": p.name, "B": p.B, "S": p.S, "E": p.E, "sum_L": p.sumL,
+                   "nominal_updates": nominal, "executed_updates": executed,
+                   "library": g.gbmw_version()},
+        "value_executed": executed / sec,
+        "roofline": roofline,
+    }
+    g.gbmw_destroy(ctx)
+    del d
+
+    if not args.no_others:
+        others = {}
+        for k in (1, 2, 3, 5):
+            if k == args.config:
+                continue
+            q = gi.make_config(k)
+            dq = to_device(torch, q)
+            c2, s2 = solve_steps(g, torch, q, dq, 5 if k == 5 else 20, 2)
+            others[f"cfg{k}"] = {"ms_per_step": s2 * 1e3, "value": q.nominal_updates() / s2,
+                                 "value_executed": q.executed_updates() / s2}
+            g.gbmw_destroy(c2)
+            del dq
+        out["other_configs"] = others
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(p)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

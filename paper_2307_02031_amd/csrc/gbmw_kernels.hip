@@ -91,17 +91,16 @@ void launch_prepare(const Tables& t, const float* R, int sumL, bool validate, hi
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_init_layer0(Tables t) {
   const int inst = blockIdx.z, s = blockIdx.y;
-  const int e = blockIdx.x * 256 + threadIdx.x;
-  if (e > t.E) return;
+  const int e = blockIdx.x * 256 + threadIdx.x;           // EP is a multiple of 256
   const int row = t.off[inst];
   const int m = t.M[(size_t)row * t.S + s];
   const float cs = t.c[(size_t)row * t.S + s];
   float* C0 = c_table(t, inst, row, 0);
-  C0[(size_t)s * t.EP + e] = (m >= 0 && e >= m) ? cs : INFINITY;
+  C0[(size_t)s * t.EP + e] = (m >= 0 && e >= m && e <= t.E) ? cs : INFINITY;   // padding rows: +inf
 }
 
 void launch_init_layer0(const Tables& t, hipStream_t st) {
-  hipLaunchKernelGGL(k_init_layer0, dim3((t.E + 256) / 256, t.S, t.B), dim3(256), 0, st, t);
+  hipLaunchKernelGGL(k_init_layer0, dim3(t.EP / 256, t.S, t.B), dim3(256), 0, st, t);
 }
 
 // ---------------------------------------------------------------------------
@@ -109,66 +108,127 @@ void launch_init_layer0(const Tables& t, hipStream_t st) {
 //   wave: 64*K consecutive budgets e' of one instance; lane owns e' = e0 + 64*j.
 //   The SP values C_{l-1}[e'][0..SP) of each owned e' stay in VGPRs for the
 //   whole kernel; R_l[.][s] arrives as scalar operands, one row of Rt per
-//   output strategy s.
+//   output strategy s, fetched one iteration ahead.
+//
+//   Value pass: the SP candidates x = C + R are folded into chunk minima of CH
+//   candidates (3-input min), and the chunk minima into a running prefix
+//   minimum P[k] = min(P[k-1], chunk 2k-1, chunk 2k); T is the last prefix.
+//   One add and half a min per candidate, no compare in the chain.
+//   Argmin: P[k] == T is monotone in k, so the lowest-index minimiser lies in
+//   the first block k whose prefix equals T (re-comparing the stored x gives
+//   the same bits, so equality is exact).  The block tests are independent
+//   compares into wave masks; a block is re-scanned only when some lane of
+//   the wave first hits it, which for neighbouring budgets is usually one.
 // ---------------------------------------------------------------------------
-template <int SP, int K, int NW>
+__device__ __forceinline__ float fmin3(float a, float b, float c) {
+  return __builtin_fminf(__builtin_fminf(a, b), c);
+}
+
+template <int SP, int K, int NW, int CH>
 __global__ __launch_bounds__(64 * NW) void k_minplus(Tables t, int l, int tiles) {
+  constexpr int NC = (SP + CH - 1) / CH;                 // chunks (last may be short)
+  constexpr int NP = NC / 2 + 1;                         // prefix minima / blocks
   const int inst = t.perm[blockIdx.x / tiles];
   const int tile = blockIdx.x % tiles;
   const int S = t.S, E = t.E, EP = t.EP;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wbase = (tile * NW + wave) * (64 * K);
+  if (wbase > E) return;                                 // whole wave beyond the table
   const int row = t.off[inst] + l;
   const float* __restrict__ Cp = c_table(t, inst, row - 1, l - 1);
   float* __restrict__ Cn = c_table(t, inst, row, l);
   uint8_t* __restrict__ An = t.A + (size_t)row * S * EP;
+  const int e0 = wbase + lane;
 
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int e0 = (tile * NW + wave) * (64 * K) + lane;
-
+  // EP is a multiple of 64*K and wbase <= E < EP, so rows e0 + 64*j < EP are
+  // inside the allocation; rows in (E, EP) are padding whose results are
+  // never stored into the table proper.
   float cp[K][SP];
 #pragma unroll
   for (int sp = 0; sp < SP; ++sp) {
 #pragma unroll
-    for (int j = 0; j < K; ++j) {
-      const int e = e0 + 64 * j;
-      cp[j][sp] = (sp < S && e <= E) ? Cp[(size_t)sp * EP + e] : INFINITY;
-    }
+    for (int j = 0; j < K; ++j)
+      cp[j][sp] = (sp < SP - 3 || sp < S) ? Cp[(size_t)sp * EP + e0 + 64 * j] : INFINITY;
   }
 
   cf32_t Rrow = as_const(t.Rt) + (size_t)row * SP * SP;
   cf32_t crow = as_const(t.c) + (size_t)row * S;
   ci32_t Mrow = as_const(t.M) + (size_t)row * S;
 
+  float r[SP];
+#pragma unroll
+  for (int sp = 0; sp < SP; ++sp) r[sp] = Rrow[sp];
+  int m_raw = Mrow[0];
+  float cs = crow[0];
+
   for (int s = 0; s < S; ++s) {
-    float r[SP];
-#pragma unroll
-    for (int sp = 0; sp < SP; ++sp) r[sp] = Rrow[s * SP + sp];
+    const int m = m_raw < 0 ? 0x7fffffff : m_raw;        // invalid M: column infeasible
+    const float cs_cur = cs;
+    float rn[SP];
 
-    float tmin[K];
-    int arg[K];
-#pragma unroll
-    for (int j = 0; j < K; ++j) { tmin[j] = INFINITY; arg[j] = 0; }
-#pragma unroll
-    for (int sp = 0; sp < SP; ++sp) {
-#pragma unroll
-      for (int j = 0; j < K; ++j) {
-        const float x = cp[j][sp] + r[sp];
-        const bool lt = x < tmin[j];
-        tmin[j] = lt ? x : tmin[j];
-        arg[j] = lt ? sp : arg[j];
-      }
-    }
-
-    const int m = Mrow[s];
-    const float cs = crow[s];
 #pragma unroll
     for (int j = 0; j < K; ++j) {
-      const int e = e0 + 64 * j;                       // pre-shift budget e'
-      if (e <= E) {
-        An[(size_t)s * EP + e] = (uint8_t)arg[j];
-        if (m >= 0 && m <= E - e) Cn[(size_t)s * EP + e + m] = tmin[j] + cs;
-        if (m < 0 || e < m) Cn[(size_t)s * EP + e] = INFINITY;
+      // ---- value pass
+      float x[SP];
+#pragma unroll
+      for (int i = 0; i < SP; ++i) x[i] = cp[j][i] + r[i];
+      float cm[NC];
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        const int lo = c * CH, hi = (lo + CH < SP) ? lo + CH : SP;
+        float acc = x[lo];
+        int i = lo + 1;
+#pragma unroll
+        for (; i + 1 < hi; i += 2) acc = fmin3(acc, x[i], x[i + 1]);
+        if (i < hi) acc = __builtin_fminf(acc, x[i]);
+        cm[c] = acc;
       }
+      float P[NP];
+      P[0] = cm[0];
+#pragma unroll
+      for (int k = 1; k < NP; ++k)
+        P[k] = (2 * k < NC) ? fmin3(P[k - 1], cm[2 * k - 1], cm[2 * k])
+                            : __builtin_fminf(P[k - 1], cm[2 * k - 1]);
+      const float T = P[NP - 1];
+
+      if (j == K - 1) {                                  // R row is dead now: fetch the next
+        const int sn = (s + 1 < S) ? s + 1 : s;
+#pragma unroll
+        for (int sp = 0; sp < SP; ++sp) rn[sp] = Rrow[sn * SP + sp];
+        m_raw = Mrow[sn];
+        cs = crow[sn];
+      }
+
+      // ---- argmin: first block whose prefix minimum reaches T
+      int arg = 0;
+      bool prev = false;
+      unsigned long long prevm = 0;
+#pragma unroll
+      for (int k = 0; k < NP; ++k) {
+        const bool eq = (k == NP - 1) ? true : (P[k] == T);
+        const unsigned long long eqm = (k == NP - 1) ? ~0ull : __builtin_amdgcn_ballot_w64(eq);
+        if (__builtin_expect((eqm & ~prevm) != 0, 0)) {  // wave-uniform: a lane first hits block k
+          if (eq && !prev) {
+            const int clo = (k == 0) ? 0 : 2 * k - 1;    // chunks of block k
+            const int chi = (k == 0) ? 1 : ((2 * k + 1 < NC) ? 2 * k + 1 : NC);
+            const int lo = clo * CH, hi = (chi * CH < SP) ? chi * CH : SP;
+            int a = hi - 1;                              // implied when no earlier one matches
+#pragma unroll
+            for (int i = hi - 2; i >= lo; --i) a = (x[i] == T) ? i : a;
+            arg = a;
+          }
+        }
+        prev = eq;
+        prevm = eqm;
+      }
+
+      const int e = e0 + 64 * j;                         // pre-shift budget e'
+      An[(size_t)s * EP + e] = (uint8_t)arg;
+      if (m <= E - e) Cn[(size_t)s * EP + e + m] = T + cs_cur;
+      if (e < m || e > E) Cn[(size_t)s * EP + e] = INFINITY;
     }
+#pragma unroll
+    for (int sp = 0; sp < SP; ++sp) r[sp] = rn[sp];
   }
 }
 
@@ -212,13 +272,14 @@ template <int SP>
 struct Blocking {                       // budgets per lane for a given strategy count
   static constexpr int K = (SP <= 24) ? 4 : 2;
   static constexpr int NW = 4;
+  static constexpr int CH = 3;          // candidates per chunk minimum
 };
 
 template <int SP>
 static void launch_minplus_sp(const Tables& t, int l, int n_active, hipStream_t st) {
-  constexpr int K = Blocking<SP>::K, NW = Blocking<SP>::NW;
+  constexpr int K = Blocking<SP>::K, NW = Blocking<SP>::NW, CH = Blocking<SP>::CH;
   const int tiles = (t.E + 1 + 64 * K * NW - 1) / (64 * K * NW);
-  hipLaunchKernelGGL((k_minplus<SP, K, NW>), dim3((unsigned)tiles * n_active), dim3(64 * NW), 0, st,
+  hipLaunchKernelGGL((k_minplus<SP, K, NW, CH>), dim3((unsigned)tiles * n_active), dim3(64 * NW), 0, st,
                      t, l, tiles);
 }
 
@@ -238,7 +299,7 @@ void launch_minplus(const Tables& t, int l, int n_active, hipStream_t st) {
 }
 
 const char* minplus_variant(int S) {
-  return S <= 64 ? "register-blocked, scalar R operands, in-loop argmin"
+  return S <= 64 ? "register-blocked, prefetched scalar R operands, prefix-min value pass + on-demand argmin rescan"
                  : "generic LDS-staged (S > 64)";
 }
 
