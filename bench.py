@@ -83,6 +83,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4, help="workload 1..5 (default: the batched config)")
+    ap.add_argument("--streams", type=int, default=0, choices=[0, 1],
+                    help="1: keep every launch on one stream (GBMW_FLAG_ONE_STREAM), as the "
+                         "per-kernel roofline leg always does; 0: library default")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other configs")
     args = ap.parse_args()
@@ -102,7 +105,8 @@ def main():
 
     p = gi.make_config(args.config)
     d = to_device(torch, p)
-    ctx, sec = solve_steps(g, torch, p, d, args.steps, args.warmup)
+    base_flags = g.GBMW_FLAG_ONE_STREAM if args.streams == 1 else 0
+    ctx, sec = solve_steps(g, torch, p, d, args.steps, args.warmup, flags=base_flags)
     nominal, executed = p.nominal_updates(), p.executed_updates()
 
     # the dominant kernel, timed live with HIP event pairs on the solve's stream
@@ -142,6 +146,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": p.name, "B": p.B, "S": p.S, "E": p.E, "sum_L": p.sumL,
                    "nominal_updates": nominal, "executed_updates": executed,
+                   "streams": "one" if args.streams == 1 else "library default (instance groups)",
                    "library": g.gbmw_version()},
         "value_executed": executed / sec,
         "roofline": roofline,
@@ -156,7 +161,7 @@ def main():
                 continue
             q = gi.make_config(k)
             dq = to_device(torch, q)
-            c2, s2 = solve_steps(g, torch, q, dq, 5 if k == 5 else 20, 2)
+            c2, s2 = solve_steps(g, torch, q, dq, 5 if k == 5 else 20, 2, flags=base_flags)
             others[f"cfg{k}"] = {"ms_per_step": s2 * 1e3, "value": q.nominal_updates() / s2,
                                  "value_executed": q.executed_updates() / s2}
             g.gbmw_destroy(c2)

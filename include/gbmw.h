@@ -52,7 +52,14 @@ enum { GBMW_PTR_HOST = 0, GBMW_PTR_DEVICE = 1 };
 
 enum {
   GBMW_FLAG_KEEP_ALL_C = 1u,   /* keep every layer's fp32 table (default: last two) */
-  GBMW_FLAG_TIME_KERNELS = 2u  /* record a HIP event pair around every min-plus launch */
+  GBMW_FLAG_TIME_KERNELS = 2u, /* record a HIP event pair around every min-plus launch
+                                  (implies GBMW_FLAG_ONE_STREAM)                       */
+  GBMW_FLAG_ONE_STREAM = 4u    /* enqueue every kernel on p->stream itself.  Default: the
+                                  instances are split into groups whose per-layer
+                                  launches run on library-owned helper streams of default
+                                  priority that fork from and join back into p->stream
+                                  with events, so the call is still ordered on p->stream
+                                  as a whole                                             */
 };
 
 #define GBMW_MAX_S 256

@@ -25,6 +25,7 @@ GBMW_OK, GBMW_ERR_INVALID_ARG, GBMW_ERR_UNSUPPORTED, GBMW_ERR_OOM, GBMW_ERR_DEVI
 GBMW_PTR_HOST, GBMW_PTR_DEVICE = 0, 1
 GBMW_FLAG_KEEP_ALL_C = 1
 GBMW_FLAG_TIME_KERNELS = 2
+GBMW_FLAG_ONE_STREAM = 4
 GBMW_MAX_S = 256
 
 EXPORTS = [

@@ -18,6 +18,10 @@ namespace {
 
 thread_local char g_err[512] = "";
 
+// Instance groups per solve (each on its own stream).  Two is where the gain
+// from overlapping one group's ramp-down with the other's launch saturates.
+constexpr int kGroups = 2;
+
 gbmw_status fail(gbmw_status st, const char* fmt, ...) {
   va_list ap;
   va_start(ap, fmt);
@@ -62,11 +66,13 @@ struct gbmw_ctx {
   bool solved = false;
   uint32_t flags = 0;
   int B = 0, S = 0, SP = 0, E = 0, EP = 0, sumL = 0, Lmax = 0;
-  std::vector<int> L, off, perm, n_active;   // n_active[l] = #{b : L_b > l}
+  std::vector<int> L, off, perm;
   gbmw::Tables t{};
   DevBuf d_L, d_off, d_perm, d_c, d_M, d_R, d_Rt, d_C, d_A, d_best, d_best_s, d_status, d_q,
       d_stage;
-  hipEvent_t ev0 = nullptr, ev1 = nullptr;
+  hipEvent_t ev0 = nullptr, ev1 = nullptr, ev_fork = nullptr;
+  std::vector<hipStream_t> aux;              // extra streams for instance groups
+  std::vector<hipEvent_t> ev_join;
   std::vector<hipEvent_t> ev_layer;          // pairs around min-plus launches
   int timed_launches = 0;
 };
@@ -82,6 +88,9 @@ void free_ctx(gbmw_ctx* c) {
     b->release();
   if (c->ev0) (void)hipEventDestroy(c->ev0);
   if (c->ev1) (void)hipEventDestroy(c->ev1);
+  if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+  for (hipEvent_t e : c->ev_join) (void)hipEventDestroy(e);
+  for (hipStream_t a : c->aux) { (void)hipStreamSynchronize(a); (void)hipStreamDestroy(a); }
   for (hipEvent_t e : c->ev_layer) (void)hipEventDestroy(e);
   delete c;
 }
@@ -134,7 +143,7 @@ gbmw_status gbmw_dp_solve_batched(const gbmw_problem* p, uint32_t flags, gbmw_ct
   if (p->E < 0 || p->E > (1 << 30)) return fail(GBMW_ERR_INVALID_ARG, "E=%d out of range", p->E);
   if (p->ptr_space != GBMW_PTR_HOST && p->ptr_space != GBMW_PTR_DEVICE)
     return fail(GBMW_ERR_INVALID_ARG, "ptr_space=%d", p->ptr_space);
-  if (flags & ~(uint32_t)(GBMW_FLAG_KEEP_ALL_C | GBMW_FLAG_TIME_KERNELS))
+  if (flags & ~(uint32_t)(GBMW_FLAG_KEEP_ALL_C | GBMW_FLAG_TIME_KERNELS | GBMW_FLAG_ONE_STREAM))
     return fail(GBMW_ERR_INVALID_ARG, "unknown flag bits 0x%x", flags);
 
   const int B = p->B, S = p->S, E = p->E;
@@ -155,9 +164,26 @@ gbmw_status gbmw_dp_solve_batched(const gbmw_problem* p, uint32_t flags, gbmw_ct
   }
   std::iota(perm.begin(), perm.end(), 0);
   std::stable_sort(perm.begin(), perm.end(), [&](int a, int b) { return L[a] > L[b]; });
-  std::vector<int> n_active(Lmax + 1, 0);
-  for (int l = 0; l <= Lmax; ++l)
-    n_active[l] = (int)std::count_if(L.begin(), L.end(), [&](int x) { return x > l; });
+  // Instance groups: group g takes every G-th instance of the L-sorted order, so
+  // groups are balanced and, inside a group, the instances still active at
+  // layer l are a prefix.  Groups run on separate streams: layers of different
+  // instances are independent, so one group's launch fills the ramp-down of
+  // another's.
+  const bool timed = (flags & GBMW_FLAG_TIME_KERNELS) != 0;
+  int G = (timed || (flags & GBMW_FLAG_ONE_STREAM)) ? 1 : kGroups;
+  if (G > B) G = B;
+  std::vector<int> grouped, gfirst(G + 1, 0);
+  for (int g = 0; g < G; ++g) {
+    gfirst[g] = (int)grouped.size();
+    for (int i = g; i < B; i += G) grouped.push_back(perm[i]);
+  }
+  gfirst[G] = B;
+  perm = grouped;
+  auto active_in_group = [&](int g, int l) {
+    int n = 0;
+    for (int i = gfirst[g]; i < gfirst[g + 1]; ++i) n += (L[perm[i]] > l) ? 1 : 0;
+    return n;
+  };
 
   gbmw_ctx* c = *out;
   const bool fresh = (c == nullptr);
@@ -197,7 +223,7 @@ gbmw_status gbmw_dp_solve_batched(const gbmw_problem* p, uint32_t flags, gbmw_ct
   c->B = B; c->S = S; c->E = E; c->sumL = sumL; c->Lmax = Lmax;
   c->SP = (S + 3) / 4 * 4;
   c->EP = (E + 1 + 255) / 256 * 256;
-  c->L = L; c->off = off; c->perm = perm; c->n_active = n_active;
+  c->L = L; c->off = off; c->perm = perm;
   const int SP = c->SP, EP = c->EP;
   const bool keep = (flags & GBMW_FLAG_KEEP_ALL_C) != 0;
   const size_t slab = (size_t)S * EP;
@@ -206,7 +232,8 @@ gbmw_status gbmw_dp_solve_batched(const gbmw_problem* p, uint32_t flags, gbmw_ct
   TRY(c->d_off.reserve(sizeof(int) * B));
   TRY(c->d_perm.reserve(sizeof(int) * B));
   TRY(c->d_status.reserve(sizeof(int)));
-  TRY(c->d_Rt.reserve(sizeof(float) * (size_t)sumL * SP * SP));
+  const int RS = (SP + 2 + 3) / 4 * 4;
+  TRY(c->d_Rt.reserve(sizeof(float) * (size_t)sumL * S * RS));
   TRY(c->d_C.reserve(sizeof(float) * slab * (keep ? (size_t)sumL : (size_t)2 * B)));
   TRY(c->d_A.reserve(slab * (size_t)sumL));
   TRY(c->d_best.reserve(sizeof(float) * (size_t)B * EP));
@@ -236,14 +263,13 @@ gbmw_status gbmw_dp_solve_batched(const gbmw_problem* p, uint32_t flags, gbmw_ct
   HIP_TRY_B(hipMemcpyAsync(c->d_perm.p, c->perm.data(), sizeof(int) * B, hipMemcpyHostToDevice, st));
 
   gbmw::Tables& t = c->t;
-  t.B = B; t.S = S; t.SP = SP; t.E = E; t.EP = EP; t.keep_all = keep ? 1 : 0;
+  t.B = B; t.S = S; t.SP = SP; t.RS = RS; t.E = E; t.EP = EP; t.keep_all = keep ? 1 : 0;
   t.L = (const int*)c->d_L.p; t.off = (const int*)c->d_off.p; t.perm = (const int*)c->d_perm.p;
   t.c = dc; t.M = dM; t.Rt = (const float*)c->d_Rt.p;
   t.Cbuf = (float*)c->d_C.p; t.A = (uint8_t*)c->d_A.p;
   t.best = (float*)c->d_best.p; t.best_s = (uint8_t*)c->d_best_s.p;
   t.status = (int*)c->d_status.p;
 
-  const bool timed = (flags & GBMW_FLAG_TIME_KERNELS) != 0;
   c->timed_launches = 0;
   if (timed) {
     while ((int)c->ev_layer.size() < 2 * Lmax) {
@@ -253,15 +279,36 @@ gbmw_status gbmw_dp_solve_batched(const gbmw_problem* p, uint32_t flags, gbmw_ct
     }
   }
 
+  while ((int)c->aux.size() < G - 1) {
+    hipStream_t a;
+    HIP_TRY_B(hipStreamCreateWithFlags(&a, hipStreamNonBlocking));   // default priority
+    c->aux.push_back(a);
+    hipEvent_t e;
+    HIP_TRY_B(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    c->ev_join.push_back(e);
+  }
+  if (G > 1 && !c->ev_fork) HIP_TRY_B(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
+
   HIP_TRY_B(hipEventRecord(c->ev0, st));
   gbmw::launch_prepare(t, dR, sumL, p->ptr_space == GBMW_PTR_DEVICE, st);
   gbmw::launch_init_layer0(t, st);
-  for (int l = 1; l < Lmax; ++l) {
-    if (timed) HIP_TRY_B(hipEventRecord(c->ev_layer[2 * c->timed_launches], st));
-    gbmw::launch_minplus(t, l, n_active[l], st);
-    if (timed) {
-      HIP_TRY_B(hipEventRecord(c->ev_layer[2 * c->timed_launches + 1], st));
-      ++c->timed_launches;
+  if (G > 1) HIP_TRY_B(hipEventRecord(c->ev_fork, st));
+  for (int g = 0; g < G; ++g) {
+    hipStream_t sg = (g == 0) ? st : c->aux[g - 1];
+    if (g > 0) HIP_TRY_B(hipStreamWaitEvent(sg, c->ev_fork, 0));
+    for (int l = 1; l < Lmax; ++l) {
+      const int na = active_in_group(g, l);
+      if (na == 0) break;
+      if (timed) HIP_TRY_B(hipEventRecord(c->ev_layer[2 * c->timed_launches], sg));
+      gbmw::launch_minplus(t, l, gfirst[g], na, sg);
+      if (timed) {
+        HIP_TRY_B(hipEventRecord(c->ev_layer[2 * c->timed_launches + 1], sg));
+        ++c->timed_launches;
+      }
+    }
+    if (g > 0) {
+      HIP_TRY_B(hipEventRecord(c->ev_join[g - 1], sg));
+      HIP_TRY_B(hipStreamWaitEvent(st, c->ev_join[g - 1], 0));
     }
   }
   gbmw::launch_final(t, st);

@@ -5,11 +5,14 @@
 //   C table of one (instance, layer):  float  [S][EP]   C[s*EP + e]
 //   A table of one (instance, layer):  uint8  [S][EP]   A[s*EP + e']
 //   EP = (E + 1) rounded up to a multiple of 256 (row stride in elements)
-//   Rt: transposed, padded transformation cost  float [sumL][SP][SP],
-//       Rt[row][s][s'] = R[row][s'][s], zero in the padding; SP = S rounded up
-//       to a multiple of 4.  A wave's 64 lanes hold 64 consecutive budgets e
-//       of one strategy, so every table access is a coalesced 256-byte
-//       segment and every R / c / M operand is wave-uniform.
+//   Rt: transposed, padded transformation cost with the layer's own cost and
+//       memory riding along:  float [sumL][S][RS],  Rt[row][s][s'] = R[row][s'][s]
+//       for s' < S, zero for S <= s' < SP, Rt[row][s][SP] = c[row][s],
+//       Rt[row][s][SP+1] = bits of M[row][s]; SP = S rounded up to a multiple of 4,
+//       RS = SP + 2 rounded up to a multiple of 4 (rows are whole float4s).
+// A wave's 64 lanes hold 64 consecutive budgets e of one strategy, so every
+// table access is a coalesced 256-byte segment and every R / c / M operand is
+// wave-uniform.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -17,14 +20,14 @@
 namespace gbmw {
 
 struct Tables {
-  int B, S, SP, E, EP;
+  int B, S, SP, RS, E, EP;
   int keep_all;        // 1: Call[row][S][EP] for every layer row; 0: rolling pair
   const int* L;        // [B]   device
   const int* off;      // [B]   device, first row of each instance
   const int* perm;     // [B]   device, instances ordered by L descending
   const float* c;      // [sumL][S]
   const int* M;        // [sumL][S]
-  const float* Rt;     // [sumL][SP][SP]
+  const float* Rt;     // [sumL][S][RS]
   float* Cbuf;         // keep_all ? [sumL][S][EP] : [2][B][S][EP]
   uint8_t* A;          // [sumL][S][EP]
   float* best;         // [B][EP]
@@ -36,10 +39,10 @@ struct Tables {
 void launch_prepare(const Tables& t, const float* R, int sumL, bool validate, hipStream_t st);
 // C(0, e, s) for every instance.
 void launch_init_layer0(const Tables& t, hipStream_t st);
-// One layer l >= 1 for the first n_active instances of perm (those with L_b > l):
+// One layer l >= 1 for instances perm[first .. first + n_active):
 // min-plus product with argmin, fused with the shift by M(l,s), the + c(l,s)
 // and the +inf prefix.
-void launch_minplus(const Tables& t, int l, int n_active, hipStream_t st);
+void launch_minplus(const Tables& t, int l, int first, int n_active, hipStream_t st);
 // best(e), best_s(e) over the last layer of every instance.
 void launch_final(const Tables& t, hipStream_t st);
 // Plans for nq queries (all pointers device).

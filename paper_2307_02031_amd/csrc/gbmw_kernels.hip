@@ -28,33 +28,33 @@ __device__ __forceinline__ float* c_table(const Tables& t, int inst, int row, in
 }
 
 // ---------------------------------------------------------------------------
-// prepare: Rt[row][s][s'] = R[row][s'][s] (zero padding) + input validation
+// prepare: Rt[row][s][0..SP) = R[row][.][s] (zero padding), Rt[row][s][SP] = c,
+// Rt[row][s][SP+1] = bits of M; + input validation
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_prepare(Tables t, const float* __restrict__ R, int sumL,
                                                  int validate, float* __restrict__ Rt) {
-  const int SP = t.SP, S = t.S;
-  const size_t n = (size_t)sumL * SP * SP;
+  const int SP = t.SP, S = t.S, RS = t.RS;
+  const size_t n = (size_t)sumL * S * RS;
   int bad = 0;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
        i += (size_t)gridDim.x * blockDim.x) {
-    const int sp = (int)(i % SP);
-    const int s = (int)((i / SP) % SP);
-    const size_t row = i / ((size_t)SP * SP);
+    const int sp = (int)(i % RS);
+    const int s = (int)((i / RS) % S);
+    const size_t row = i / ((size_t)RS * S);
     float v = 0.0f;
-    if (s < S && sp < S) {
+    if (sp < S) {
       v = R[(row * S + sp) * S + s];
+    } else if (sp == SP) {
+      v = t.c[row * S + s];
+      if (validate && !(v >= 0.0f)) bad |= 1;
+    } else if (sp == SP + 1) {
+      const int m = t.M[row * S + s];
+      if (validate && m < 0) bad |= 2;
+      v = __int_as_float(m);
     }
     Rt[i] = v;
   }
-  if (validate) {
-    const size_t m = (size_t)sumL * S;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < m;
-         i += (size_t)gridDim.x * blockDim.x) {
-      if (!(t.c[i] >= 0.0f)) bad |= 1;
-      if (t.M[i] < 0) bad |= 2;
-    }
-    if (bad) atomicOr(t.status, bad);
-  }
+  if (validate && bad) atomicOr(t.status, bad);
 }
 
 // R is validated per instance because the l == 0 slab is ignored by contract
@@ -77,7 +77,7 @@ __global__ void k_clear_status(int* status) { *status = 0; }
 void launch_prepare(const Tables& t, const float* R, int sumL, bool validate, hipStream_t st) {
   // a fill kernel rather than a memset node, so that the sequence can be captured
   hipLaunchKernelGGL(k_clear_status, dim3(1), dim3(1), 0, st, t.status);
-  const size_t n = (size_t)sumL * t.SP * t.SP;
+  const size_t n = (size_t)sumL * t.S * t.RS;
   int blocks = (int)((n + 255) / 256);
   if (blocks > 65536) blocks = 65536;
   if (blocks < 1) blocks = 1;
@@ -107,8 +107,10 @@ void launch_init_layer0(const Tables& t, hipStream_t st) {
 // min-plus + argmin + shift-add, register-blocked.
 //   wave: 64*K consecutive budgets e' of one instance; lane owns e' = e0 + 64*j.
 //   The SP values C_{l-1}[e'][0..SP) of each owned e' stay in VGPRs for the
-//   whole kernel; R_l[.][s] arrives as scalar operands, one row of Rt per
-//   output strategy s, fetched one iteration ahead.
+//   whole kernel.  The layer's R tile (with c and M riding in each row) is
+//   staged once per workgroup in LDS; every output strategy s reads its row
+//   with wave-uniform 128-bit LDS reads (broadcast, conflict-free, returned in
+//   order so the reads pipeline ahead of the adds).
 //
 //   Value pass: the SP candidates x = C + R are folded into chunk minima of CH
 //   candidates (3-input min), and the chunk minima into a running prefix
@@ -125,16 +127,26 @@ __device__ __forceinline__ float fmin3(float a, float b, float c) {
 }
 
 template <int SP, int K, int NW, int CH>
-__global__ __launch_bounds__(64 * NW) void k_minplus(Tables t, int l, int tiles) {
+__global__ __launch_bounds__(64 * NW) void k_minplus(Tables t, int l, int tiles, int first) {
   constexpr int NC = (SP + CH - 1) / CH;                 // chunks (last may be short)
   constexpr int NP = NC / 2 + 1;                         // prefix minima / blocks
-  const int inst = t.perm[blockIdx.x / tiles];
+  constexpr int RS = (SP + 2 + 3) / 4 * 4;               // row: SP x R, c, M, padding
+  constexpr int RQ = RS / 4;
+  extern __shared__ float4 rt_lds[];                     // [S][RQ]
+
+  const int inst = t.perm[first + blockIdx.x / tiles];
   const int tile = blockIdx.x % tiles;
   const int S = t.S, E = t.E, EP = t.EP;
+  const int row = t.off[inst] + l;
+  {
+    const float4* __restrict__ src = reinterpret_cast<const float4*>(t.Rt + (size_t)row * S * RS);
+    for (int i = threadIdx.x; i < S * RQ; i += 64 * NW) rt_lds[i] = src[i];
+  }
+  __syncthreads();
+
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wbase = (tile * NW + wave) * (64 * K);
   if (wbase > E) return;                                 // whole wave beyond the table
-  const int row = t.off[inst] + l;
   const float* __restrict__ Cp = c_table(t, inst, row - 1, l - 1);
   float* __restrict__ Cn = c_table(t, inst, row, l);
   uint8_t* __restrict__ An = t.A + (size_t)row * S * EP;
@@ -151,20 +163,16 @@ __global__ __launch_bounds__(64 * NW) void k_minplus(Tables t, int l, int tiles)
       cp[j][sp] = (sp < SP - 3 || sp < S) ? Cp[(size_t)sp * EP + e0 + 64 * j] : INFINITY;
   }
 
-  cf32_t Rrow = as_const(t.Rt) + (size_t)row * SP * SP;
-  cf32_t crow = as_const(t.c) + (size_t)row * S;
-  ci32_t Mrow = as_const(t.M) + (size_t)row * S;
-
-  float r[SP];
-#pragma unroll
-  for (int sp = 0; sp < SP; ++sp) r[sp] = Rrow[sp];
-  int m_raw = Mrow[0];
-  float cs = crow[0];
-
   for (int s = 0; s < S; ++s) {
+    float r[RS];
+#pragma unroll
+    for (int q = 0; q < RQ; ++q) {
+      const float4 v = rt_lds[s * RQ + q];
+      r[4 * q] = v.x; r[4 * q + 1] = v.y; r[4 * q + 2] = v.z; r[4 * q + 3] = v.w;
+    }
+    const float cs = r[SP];
+    const int m_raw = __float_as_int(r[SP + 1]);
     const int m = m_raw < 0 ? 0x7fffffff : m_raw;        // invalid M: column infeasible
-    const float cs_cur = cs;
-    float rn[SP];
 
 #pragma unroll
     for (int j = 0; j < K; ++j) {
@@ -191,14 +199,6 @@ __global__ __launch_bounds__(64 * NW) void k_minplus(Tables t, int l, int tiles)
                             : __builtin_fminf(P[k - 1], cm[2 * k - 1]);
       const float T = P[NP - 1];
 
-      if (j == K - 1) {                                  // R row is dead now: fetch the next
-        const int sn = (s + 1 < S) ? s + 1 : s;
-#pragma unroll
-        for (int sp = 0; sp < SP; ++sp) rn[sp] = Rrow[sn * SP + sp];
-        m_raw = Mrow[sn];
-        cs = crow[sn];
-      }
-
       // ---- argmin: first block whose prefix minimum reaches T
       int arg = 0;
       bool prev = false;
@@ -224,21 +224,19 @@ __global__ __launch_bounds__(64 * NW) void k_minplus(Tables t, int l, int tiles)
 
       const int e = e0 + 64 * j;                         // pre-shift budget e'
       An[(size_t)s * EP + e] = (uint8_t)arg;
-      if (m <= E - e) Cn[(size_t)s * EP + e + m] = T + cs_cur;
+      if (m <= E - e) Cn[(size_t)s * EP + e + m] = T + cs;
       if (e < m || e > E) Cn[(size_t)s * EP + e] = INFINITY;
     }
-#pragma unroll
-    for (int sp = 0; sp < SP; ++sp) r[sp] = rn[sp];
   }
 }
 
 // Any S up to 256: the C_{l-1} tile of 64 budgets is staged in LDS as
 // [S][64]; wave w handles output strategies w, w+4, ...
-__global__ __launch_bounds__(256) void k_minplus_generic(Tables t, int l, int tiles) {
+__global__ __launch_bounds__(256) void k_minplus_generic(Tables t, int l, int tiles, int first) {
   extern __shared__ float lds[];
-  const int inst = t.perm[blockIdx.x / tiles];
+  const int inst = t.perm[first + blockIdx.x / tiles];
   const int tile = blockIdx.x % tiles;
-  const int S = t.S, SP = t.SP, E = t.E, EP = t.EP;
+  const int S = t.S, RS = t.RS, E = t.E, EP = t.EP;
   const int row = t.off[inst] + l;
   const float* __restrict__ Cp = c_table(t, inst, row - 1, l - 1);
   float* __restrict__ Cn = c_table(t, inst, row, l);
@@ -250,12 +248,12 @@ __global__ __launch_bounds__(256) void k_minplus_generic(Tables t, int l, int ti
     lds[sp * 64 + lane] = (e <= E) ? Cp[(size_t)sp * EP + e] : INFINITY;
   __syncthreads();
 
-  cf32_t Rrow = as_const(t.Rt) + (size_t)row * SP * SP;
+  cf32_t Rrow = as_const(t.Rt) + (size_t)row * S * RS;
   for (int s = wave; s < S; s += 4) {
     float tmin = INFINITY;
     int arg = 0;
     for (int sp = 0; sp < S; ++sp) {
-      const float x = lds[sp * 64 + lane] + Rrow[s * SP + sp];
+      const float x = lds[sp * 64 + lane] + Rrow[s * RS + sp];
       if (x < tmin) { tmin = x; arg = sp; }
     }
     const int m = t.M[(size_t)row * S + s];
@@ -270,23 +268,24 @@ __global__ __launch_bounds__(256) void k_minplus_generic(Tables t, int l, int ti
 
 template <int SP>
 struct Blocking {                       // budgets per lane for a given strategy count
-  static constexpr int K = (SP <= 24) ? 4 : 2;
+  static constexpr int K = 1;
   static constexpr int NW = 4;
   static constexpr int CH = 3;          // candidates per chunk minimum
 };
 
 template <int SP>
-static void launch_minplus_sp(const Tables& t, int l, int n_active, hipStream_t st) {
+static void launch_minplus_sp(const Tables& t, int l, int first, int n_active, hipStream_t st) {
   constexpr int K = Blocking<SP>::K, NW = Blocking<SP>::NW, CH = Blocking<SP>::CH;
   const int tiles = (t.E + 1 + 64 * K * NW - 1) / (64 * K * NW);
-  hipLaunchKernelGGL((k_minplus<SP, K, NW, CH>), dim3((unsigned)tiles * n_active), dim3(64 * NW), 0, st,
-                     t, l, tiles);
+  constexpr int RS = (SP + 2 + 3) / 4 * 4;
+  hipLaunchKernelGGL((k_minplus<SP, K, NW, CH>), dim3((unsigned)tiles * n_active), dim3(64 * NW),
+                     (size_t)t.S * RS * sizeof(float), st, t, l, tiles, first);
 }
 
-void launch_minplus(const Tables& t, int l, int n_active, hipStream_t st) {
+void launch_minplus(const Tables& t, int l, int first, int n_active, hipStream_t st) {
   if (n_active <= 0) return;
   switch (t.SP) {
-#define GBMW_CASE(N) case N: launch_minplus_sp<N>(t, l, n_active, st); return;
+#define GBMW_CASE(N) case N: launch_minplus_sp<N>(t, l, first, n_active, st); return;
     GBMW_CASE(4) GBMW_CASE(8) GBMW_CASE(12) GBMW_CASE(16) GBMW_CASE(20) GBMW_CASE(24)
     GBMW_CASE(28) GBMW_CASE(32) GBMW_CASE(36) GBMW_CASE(40) GBMW_CASE(44) GBMW_CASE(48)
     GBMW_CASE(52) GBMW_CASE(56) GBMW_CASE(60) GBMW_CASE(64)
@@ -295,11 +294,11 @@ void launch_minplus(const Tables& t, int l, int n_active, hipStream_t st) {
   }
   const int tiles = (t.E + 64) / 64;
   hipLaunchKernelGGL(k_minplus_generic, dim3((unsigned)tiles * n_active), dim3(256),
-                     (size_t)t.S * 64 * sizeof(float), st, t, l, tiles);
+                     (size_t)t.S * 64 * sizeof(float), st, t, l, tiles, first);
 }
 
 const char* minplus_variant(int S) {
-  return S <= 64 ? "register-blocked, prefetched scalar R operands, prefix-min value pass + on-demand argmin rescan"
+  return S <= 64 ? "register-blocked, LDS-staged R tile, prefix-min value pass + on-demand argmin rescan"
                  : "generic LDS-staged (S > 64)";
 }
 

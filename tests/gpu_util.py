@@ -12,6 +12,8 @@ import pins
 def solve_gpu(p: gi.Problem, flags: int = 0, device_inputs: bool = False, ctx=None):
     import torch
     import paper_2307_02031_amd as g
+    if not device_inputs:
+        flags |= g.GBMW_FLAG_ONE_STREAM      # host-input cases also cover the one-stream path
     if device_inputs:
         c = torch.from_numpy(p.c).cuda()
         M = torch.from_numpy(p.M).cuda()
