@@ -86,6 +86,9 @@ def main():
     ap.add_argument("--streams", type=int, default=0, choices=[0, 1],
                     help="1: keep every launch on one stream (GBMW_FLAG_ONE_STREAM), as the "
                          "per-kernel roofline leg always does; 0: library default")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="instead of the benchmark, run a plain 1 GiB device-to-device copy five times "
+                         "(a kernel of known traffic against which HBM byte counters are scaled)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other configs")
     args = ap.parse_args()
@@ -102,6 +105,17 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+
+    if args.copy_calibration:
+        n = 1 << 28                                   # 2^28 floats = 1 GiB read + 1 GiB written
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": True, "bytes_read_per_copy": 4 * n,
+                          "bytes_written_per_copy": 4 * n, "copies": 5}), flush=True)
+        return
 
     p = gi.make_config(args.config)
     d = to_device(torch, p)
@@ -122,11 +136,14 @@ def main():
     avg_launch_ms = mp_ms / mp_n if mp_n else float("nan")
     ops_per_launch = OPS_PER_UPDATE * executed / launches_per_solve if mp_n else 0.0
     achieved = ops_per_launch / (avg_launch_ms * 1e-3) / 1e12 if mp_n else 0.0
+    # HBM bytes per launch as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by
+    # a copy kernel of known size); the summary file states the commands.
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"traffic_cfg{args.config}.json")
+    tpath = os.path.join(ROOT, "profiles", f"k_minplus_cfg{args.config}_hbm_traffic.txt")
     if os.path.exists(tpath):
-        with open(tpath) as f:
-            traffic = json.load(f).get("hbm_bytes_per_launch")
+        for line in open(tpath):
+            if line.startswith("hbm_bytes_per_launch:"):
+                traffic = int(line.split(":")[1])
     roofline = {
         "bound": "alu", "kernel": "k_minplus (fused min-plus + argmin + shift-add)",
         "achieved": achieved, "peak": PEAK_PLAIN_FP32_TOPS, "unit": "TFLOP/s",
