@@ -291,7 +291,12 @@ gbmw_status gbmw_dp_solve_batched(const gbmw_problem* p, uint32_t flags, gbmw_ct
 
   HIP_TRY_B(hipEventRecord(c->ev0, st));
   gbmw::launch_prepare(t, dR, sumL, p->ptr_space == GBMW_PTR_DEVICE, st);
-  gbmw::launch_init_layer0(t, st);
+  {
+    // Layer 0 goes to memory only where something reads it from there.
+    const bool all = keep || !gbmw::layer0_in_registers(S);
+    const bool some = std::any_of(L.begin(), L.end(), [](int x) { return x <= 2; });
+    if (all || some) gbmw::launch_init_layer0(t, !all, st);
+  }
   if (G > 1) HIP_TRY_B(hipEventRecord(c->ev_fork, st));
   for (int g = 0; g < G; ++g) {
     hipStream_t sg = (g == 0) ? st : c->aux[g - 1];
@@ -306,12 +311,12 @@ gbmw_status gbmw_dp_solve_batched(const gbmw_problem* p, uint32_t flags, gbmw_ct
         ++c->timed_launches;
       }
     }
+    gbmw::launch_final(t, gfirst[g], gfirst[g + 1] - gfirst[g], sg);
     if (g > 0) {
       HIP_TRY_B(hipEventRecord(c->ev_join[g - 1], sg));
       HIP_TRY_B(hipStreamWaitEvent(st, c->ev_join[g - 1], 0));
     }
   }
-  gbmw::launch_final(t, st);
   HIP_TRY_B(hipEventRecord(c->ev1, st));
   HIP_TRY_B(hipGetLastError());
 #undef TRY

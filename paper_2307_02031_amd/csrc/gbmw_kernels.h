@@ -37,14 +37,17 @@ struct Tables {
 
 // R -> Rt (transpose + pad) and validation of device-resident inputs.
 void launch_prepare(const Tables& t, const float* R, int sumL, bool validate, hipStream_t st);
-// C(0, e, s) for every instance.
-void launch_init_layer0(const Tables& t, hipStream_t st);
+// C(0, e, s) written to the table: for every instance, or (only_short) only for
+// instances with L_b <= 2, whose layer 0 is read by the final reduce / export.
+void launch_init_layer0(const Tables& t, bool only_short, hipStream_t st);
+// True when the layer-1 launch builds layer 0 in registers and does not read it.
+bool layer0_in_registers(int S);
 // One layer l >= 1 for instances perm[first .. first + n_active):
 // min-plus product with argmin, fused with the shift by M(l,s), the + c(l,s)
 // and the +inf prefix.
 void launch_minplus(const Tables& t, int l, int first, int n_active, hipStream_t st);
-// best(e), best_s(e) over the last layer of every instance.
-void launch_final(const Tables& t, hipStream_t st);
+// best(e), best_s(e) over the last layer of instances perm[first .. first + count).
+void launch_final(const Tables& t, int first, int count, hipStream_t st);
 // Plans for nq queries (all pointers device).
 void launch_backtrack(const Tables& t, int nq, const int* q_inst, const int* q_e, int Lmax,
                       uint8_t* plan, float* cost, int* mem_used, hipStream_t st);

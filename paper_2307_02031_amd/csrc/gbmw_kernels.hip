@@ -89,8 +89,9 @@ void launch_prepare(const Tables& t, const float* R, int sumL, bool validate, hi
 // ---------------------------------------------------------------------------
 // layer 0:  C(0, e, s) = e >= M(0, s) ? c(0, s) : +inf
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_init_layer0(Tables t) {
+__global__ __launch_bounds__(256) void k_init_layer0(Tables t, int only_short) {
   const int inst = blockIdx.z, s = blockIdx.y;
+  if (only_short && t.L[inst] > 2) return;   // layer 1 rebuilds layer 0 in registers
   const int e = blockIdx.x * 256 + threadIdx.x;           // EP is a multiple of 256
   const int row = t.off[inst];
   const int m = t.M[(size_t)row * t.S + s];
@@ -99,8 +100,9 @@ __global__ __launch_bounds__(256) void k_init_layer0(Tables t) {
   C0[(size_t)s * t.EP + e] = (m >= 0 && e >= m && e <= t.E) ? cs : INFINITY;   // padding rows: +inf
 }
 
-void launch_init_layer0(const Tables& t, hipStream_t st) {
-  hipLaunchKernelGGL(k_init_layer0, dim3(t.EP / 256, t.S, t.B), dim3(256), 0, st, t);
+void launch_init_layer0(const Tables& t, bool only_short, hipStream_t st) {
+  hipLaunchKernelGGL(k_init_layer0, dim3(t.EP / 256, t.S, t.B), dim3(256), 0, st, t,
+                     only_short ? 1 : 0);
 }
 
 // ---------------------------------------------------------------------------
@@ -126,7 +128,7 @@ __device__ __forceinline__ float fmin3(float a, float b, float c) {
   return __builtin_fminf(__builtin_fminf(a, b), c);
 }
 
-template <int SP, int K, int NW, int CH>
+template <int SP, int K, int NW, int CH, bool FIRST>
 __global__ __launch_bounds__(64 * NW) void k_minplus(Tables t, int l, int tiles, int first) {
   constexpr int NC = (SP + CH - 1) / CH;                 // chunks (last may be short)
   constexpr int NP = NC / 2 + 1;                         // prefix minima / blocks
@@ -156,11 +158,29 @@ __global__ __launch_bounds__(64 * NW) void k_minplus(Tables t, int l, int tiles,
   // inside the allocation; rows in (E, EP) are padding whose results are
   // never stored into the table proper.
   float cp[K][SP];
+  if (FIRST) {
+    // l == 1: layer 0 is a closed form, C(0, e, s') = e >= M(0, s') ? c(0, s') : +inf,
+    // built here instead of being written to and read back from HBM.
+    cf32_t c0 = as_const(t.c) + (size_t)(row - 1) * S;
+    ci32_t m0 = as_const(t.M) + (size_t)(row - 1) * S;
 #pragma unroll
-  for (int sp = 0; sp < SP; ++sp) {
+    for (int sp = 0; sp < SP; ++sp) {
+      const bool col = (sp < SP - 3 || sp < S);
+      const float cv = col ? c0[sp] : INFINITY;
+      const int mv = col ? m0[sp] : 0;
 #pragma unroll
-    for (int j = 0; j < K; ++j)
-      cp[j][sp] = (sp < SP - 3 || sp < S) ? Cp[(size_t)sp * EP + e0 + 64 * j] : INFINITY;
+      for (int j = 0; j < K; ++j) {
+        const int e = e0 + 64 * j;
+        cp[j][sp] = (mv >= 0 && e >= mv && e <= E) ? cv : INFINITY;
+      }
+    }
+  } else {
+#pragma unroll
+    for (int sp = 0; sp < SP; ++sp) {
+#pragma unroll
+      for (int j = 0; j < K; ++j)
+        cp[j][sp] = (sp < SP - 3 || sp < S) ? Cp[(size_t)sp * EP + e0 + 64 * j] : INFINITY;
+    }
   }
 
   for (int s = 0; s < S; ++s) {
@@ -278,8 +298,12 @@ static void launch_minplus_sp(const Tables& t, int l, int first, int n_active, h
   constexpr int K = Blocking<SP>::K, NW = Blocking<SP>::NW, CH = Blocking<SP>::CH;
   const int tiles = (t.E + 1 + 64 * K * NW - 1) / (64 * K * NW);
   constexpr int RS = (SP + 2 + 3) / 4 * 4;
-  hipLaunchKernelGGL((k_minplus<SP, K, NW, CH>), dim3((unsigned)tiles * n_active), dim3(64 * NW),
-                     (size_t)t.S * RS * sizeof(float), st, t, l, tiles, first);
+  if (l == 1)
+    hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, true>), dim3((unsigned)tiles * n_active),
+                       dim3(64 * NW), (size_t)t.S * RS * sizeof(float), st, t, l, tiles, first);
+  else
+    hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, false>), dim3((unsigned)tiles * n_active),
+                       dim3(64 * NW), (size_t)t.S * RS * sizeof(float), st, t, l, tiles, first);
 }
 
 void launch_minplus(const Tables& t, int l, int first, int n_active, hipStream_t st) {
@@ -297,6 +321,8 @@ void launch_minplus(const Tables& t, int l, int first, int n_active, hipStream_t
                      (size_t)t.S * 64 * sizeof(float), st, t, l, tiles, first);
 }
 
+bool layer0_in_registers(int S) { return S <= 64; }
+
 const char* minplus_variant(int S) {
   return S <= 64 ? "register-blocked, LDS-staged R tile, prefix-min value pass + on-demand argmin rescan"
                  : "generic LDS-staged (S > 64)";
@@ -305,8 +331,8 @@ const char* minplus_variant(int S) {
 // ---------------------------------------------------------------------------
 // final reduce: best(e) = min_s C(L_b - 1, e, s), lowest-index argmin
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_final(Tables t) {
-  const int inst = blockIdx.y;
+__global__ __launch_bounds__(256) void k_final(Tables t, int first) {
+  const int inst = t.perm[first + blockIdx.y];
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e > t.E) return;
   const int l = t.L[inst] - 1;
@@ -321,8 +347,9 @@ __global__ __launch_bounds__(256) void k_final(Tables t) {
   t.best_s[(size_t)inst * t.EP + e] = (uint8_t)a;
 }
 
-void launch_final(const Tables& t, hipStream_t st) {
-  hipLaunchKernelGGL(k_final, dim3((t.E + 256) / 256, t.B), dim3(256), 0, st, t);
+void launch_final(const Tables& t, int first, int count, hipStream_t st) {
+  if (count <= 0) return;
+  hipLaunchKernelGGL(k_final, dim3((t.E + 256) / 256, count), dim3(256), 0, st, t, first);
 }
 
 // ---------------------------------------------------------------------------
