@@ -128,8 +128,8 @@ __device__ __forceinline__ float fmin3(float a, float b, float c) {
   return __builtin_fminf(__builtin_fminf(a, b), c);
 }
 
-template <int SP, int K, int NW, int CH, bool FIRST>
-__global__ __launch_bounds__(64 * NW) void k_minplus(Tables t, int l, int tiles, int first) {
+template <int SP, int K, int NW, int CH, int MINW, bool SAVE_X, bool FIRST>
+__global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int tiles, int first) {
   constexpr int NC = (SP + CH - 1) / CH;                 // chunks (last may be short)
   constexpr int NP = NC / 2 + 1;                         // prefix minima / blocks
   constexpr int RS = (SP + 2 + 3) / 4 * 4;               // row: SP x R, c, M, padding
@@ -233,8 +233,19 @@ __global__ __launch_bounds__(64 * NW) void k_minplus(Tables t, int l, int tiles,
             const int chi = (k == 0) ? 1 : ((2 * k + 1 < NC) ? 2 * k + 1 : NC);
             const int lo = clo * CH, hi = (chi * CH < SP) ? chi * CH : SP;
             int a = hi - 1;                              // implied when no earlier one matches
+            if (SAVE_X) {
 #pragma unroll
-            for (int i = hi - 2; i >= lo; --i) a = (x[i] == T) ? i : a;
+              for (int i = hi - 2; i >= lo; --i) a = (x[i] == T) ? i : a;
+            } else {
+            // the sums are not kept: redo them from the R row (same operands, same bits)
+            typedef const volatile __attribute__((address_space(3))) float* lds_cvf_t;
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Wold-style-cast"
+            lds_cvf_t rl = (lds_cvf_t)(rt_lds) + s * RS;
+#pragma clang diagnostic pop
+#pragma unroll
+            for (int i = hi - 2; i >= lo; --i) a = (cp[j][i] + rl[i] == T) ? i : a;
+            }
             arg = a;
           }
         }
@@ -291,18 +302,26 @@ struct Blocking {                       // budgets per lane for a given strategy
   static constexpr int K = 1;
   static constexpr int NW = 4;
   static constexpr int CH = 3;          // candidates per chunk minimum
+  // waves per SIMD the register allocation must allow: SP live table values
+  // plus about 30 working registers out of 512
+  // Keeping the S candidate sums live for the argmin rescan costs S registers;
+  // it only pays where dropping them would not buy another wave per SIMD.
+  static constexpr bool SAVE_X = (SP >= 60);
+  static constexpr int MINW = (SP <= 24) ? 8 : (SP <= 32) ? 7 : (SP <= 36) ? 6 : (SP <= 44) ? 5 : (SP <= 56) ? 4 : 3;
 };
 
 template <int SP>
 static void launch_minplus_sp(const Tables& t, int l, int first, int n_active, hipStream_t st) {
-  constexpr int K = Blocking<SP>::K, NW = Blocking<SP>::NW, CH = Blocking<SP>::CH;
+  constexpr int K = Blocking<SP>::K, NW = Blocking<SP>::NW, CH = Blocking<SP>::CH,
+                MINW = Blocking<SP>::MINW;
+  constexpr bool SAVE_X = Blocking<SP>::SAVE_X;
   const int tiles = (t.E + 1 + 64 * K * NW - 1) / (64 * K * NW);
   constexpr int RS = (SP + 2 + 3) / 4 * 4;
   if (l == 1)
-    hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, true>), dim3((unsigned)tiles * n_active),
+    hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, MINW, SAVE_X, true>), dim3((unsigned)tiles * n_active),
                        dim3(64 * NW), (size_t)t.S * RS * sizeof(float), st, t, l, tiles, first);
   else
-    hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, false>), dim3((unsigned)tiles * n_active),
+    hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, MINW, SAVE_X, false>), dim3((unsigned)tiles * n_active),
                        dim3(64 * NW), (size_t)t.S * RS * sizeof(float), st, t, l, tiles, first);
 }
 
