@@ -71,8 +71,14 @@ def cpu_baseline(p, budget_s=12.0):
         n += 1
         if t_used > budget_s:
             break
+    # the same oracle on one thread, on the first instance only
+    o, Lb = 0, int(p.L[0])
+    t0 = time.perf_counter()
+    oracle.solve(p.c[o:o + Lb], p.M[o:o + Lb], p.R[o:o + Lb], p.E, keep_C=False, keep_A=True, nthreads=1)
+    t1 = time.perf_counter() - t0
     return {"value": done_nominal / t_used, "unit": "cell-updates/s", "cores": threads,
             "kind": "oracle", "value_executed": done_exec / t_used,
+            "value_1_thread": Lb * p.E * p.S * p.S / t1,
             "sample": f"first {n} of {p.B} instances of the workload, {t_used:.1f} s of oracle time, "
                       f"OpenMP over budget rows"}
 
@@ -168,6 +174,19 @@ def main():
         "value_executed": executed / sec,
         "roofline": roofline,
     }
+    # row a4: plans for a window of budgets below E for every instance (the E_fwd window
+    # Algorithm 3 inspects), timed end to end through the ABI (upload, walk, download)
+    import numpy as np
+    window = min(256, p.E + 1)
+    qi = np.repeat(np.arange(p.B, dtype=np.int32), window)
+    qe = np.tile(np.arange(p.E - window + 1, p.E + 1, dtype=np.int32), p.B)
+    g.gbmw_backtrack(ctx, qi[:64], qe[:64])
+    t0 = time.perf_counter()
+    plan, cost, mem = g.gbmw_backtrack(ctx, qi, qe)
+    bt = time.perf_counter() - t0
+    out["backtrack"] = {"queries": int(len(qi)), "ms": bt * 1e3, "plans_per_s": len(qi) / bt,
+                        "note": "host-to-host through gbmw_backtrack: query upload, one lane per "
+                                "query walking L_b argmin records, plan download"}
     g.gbmw_destroy(ctx)
     del d
 
