@@ -51,6 +51,11 @@ def _bind(path: str):
                                           ct.c_int, u8p, f32p, i64p]
     lib.gbmw_oracle_backtrack.restype = None
     lib.gbmw_oracle_max_threads.restype = ct.c_int
+    lib.gbmw_oracle_e_all.argtypes = [ct.c_int, ct.c_int, i32p, i32p, i32p, u8p]
+    lib.gbmw_oracle_e_all.restype = ct.c_int64
+    lib.gbmw_oracle_select_budget.argtypes = [ct.c_int, ct.c_int, ct.c_int, i32p, u8p, f32p, u8p,
+                                              i32p, i32p, i32p, ct.POINTER(ct.c_int32), f32p, u8p, i64p]
+    lib.gbmw_oracle_select_budget.restype = None
     return lib
 
 
@@ -119,6 +124,31 @@ class Solution:
                                       _p(self.best_s, ct.c_uint8), int(e_q),
                                       _p(plan, ct.c_uint8), ct.byref(cost), ct.byref(mem))
         return plan, np.float32(cost.value), int(mem.value)
+
+
+def e_all(Of, Ob, Oms, plan) -> int:
+    """Overall memory of one plan (Eq. 2)."""
+    L, S = Of.shape
+    plan = np.ascontiguousarray(plan, dtype=np.uint8)
+    return int(_load().gbmw_oracle_e_all(L, S, _p(_chk(Of, np.int32, (L, S)), ct.c_int32),
+                                         _p(_chk(Ob, np.int32, (L, S)), ct.c_int32),
+                                         _p(_chk(Oms, np.int32, (L, S)), ct.c_int32), _p(plan, ct.c_uint8)))
+
+
+def select_budget(sol: "Solution", Of, Ob, Oms):
+    """Algorithm 3's outer loop on a solved instance whose M was Of + Oms:
+    (e_opt, cost, plan, e_all)."""
+    L, S = Of.shape
+    assert sol.A is not None and np.array_equal(sol.M, Of + Oms)
+    e_opt, cost, ea = ct.c_int32(), ct.c_float(), ct.c_int64()
+    plan = np.empty(L, np.uint8)
+    _load().gbmw_oracle_select_budget(L, S, sol.E, _p(sol.M, ct.c_int32), _p(sol.A, ct.c_uint8),
+                                      _p(sol.best, ct.c_float), _p(sol.best_s, ct.c_uint8),
+                                      _p(_chk(Of, np.int32, (L, S)), ct.c_int32),
+                                      _p(_chk(Ob, np.int32, (L, S)), ct.c_int32),
+                                      _p(_chk(Oms, np.int32, (L, S)), ct.c_int32),
+                                      ct.byref(e_opt), ct.byref(cost), _p(plan, ct.c_uint8), ct.byref(ea))
+    return int(e_opt.value), np.float32(cost.value), plan, int(ea.value)
 
 
 def solve(c, M, R, E, keep_C=True, keep_A=True, keep_T=False, nthreads=1) -> Solution:

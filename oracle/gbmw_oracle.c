@@ -248,6 +248,75 @@ void gbmw_oracle_backtrack(int L, int S, int E, const int32_t *M,
     *mem_out = mem;
 }
 
+/* ------------------------------------------------------------------ */
+/* Overall memory of a plan (Section 4.1.2, Eq. 2): when layer i runs    */
+/* its backward pass, the forward activations of layers 1..i, the         */
+/* backward activations of layer i and the model states of ALL layers     */
+/* are alive;  E_all is the largest such peak.                            */
+/*   E_all = max_i { sum_{k<=i} O_f(k,s_k) + O_b(i,s_i) } + sum_k O_ms(k,s_k) */
+/* (the equation prints O_b(i, S_{j_k}); the subscript is read as j_i).   */
+/* ------------------------------------------------------------------ */
+int64_t gbmw_oracle_e_all(int L, int S, const int32_t *Of, const int32_t *Ob,
+                          const int32_t *Oms, const uint8_t *plan)
+{
+    int64_t fwd = 0, ms = 0, peak = 0;
+    for (int i = 0; i < L; ++i) {
+        int s = plan[i];
+        fwd += Of[(size_t)i * S + s];
+        ms += Oms[(size_t)i * S + s];
+        int64_t here = fwd + Ob[(size_t)i * S + s];
+        if (i == 0 || here > peak) peak = here;
+    }
+    return peak + ms;
+}
+
+/* ------------------------------------------------------------------ */
+/* The outer loop of Appendix A, Algorithm 3, on top of a filled table    */
+/* (M = O_f + O_ms was the memory the table was filled with, E the total  */
+/* device budget).  b_up = max O_b bounds the backward peak, so every     */
+/* E_fwd <= E - b_up is valid without a check; the budgets above that are */
+/* visited in increasing order, each plan's E_all is checked against E,   */
+/* and the walk stops at the first plan that does not fit.                */
+/* Readings: E_fwd^opt starts at E - b_up with that budget's plan; if     */
+/* E - b_up < 0 nothing is valid a priori (start: none, window from 0);   */
+/* a budget with no feasible plan (best = +inf) has nothing to check and  */
+/* is passed over.                                                        */
+/* Outputs: *e_opt (-1: none), *cost = best[e_opt] (+inf if none or       */
+/* infeasible), plan[L] (0xFF if none/infeasible), *e_all (-1 likewise).  */
+/* ------------------------------------------------------------------ */
+void gbmw_oracle_select_budget(int L, int S, int E, const int32_t *M,
+                               const uint8_t *A, const float *best,
+                               const uint8_t *best_s, const int32_t *Of,
+                               const int32_t *Ob, const int32_t *Oms,
+                               int32_t *e_opt, float *cost, uint8_t *plan,
+                               int64_t *e_all)
+{
+    int64_t b_up = 0;
+    for (size_t i = 0; i < (size_t)L * S; ++i)
+        if (Ob[i] > b_up) b_up = Ob[i];
+    int64_t opt = (int64_t)E - b_up;
+    if (opt < 0) opt = -1;
+    uint8_t *cur = (uint8_t *)malloc((size_t)L);
+    for (int64_t e = opt + 1; e <= E; ++e) {
+        if (best[e] == INFINITY) continue;
+        float c_;
+        int64_t m_;
+        gbmw_oracle_backtrack(L, S, E, M, A, best, best_s, (int)e, cur, &c_, &m_);
+        if (gbmw_oracle_e_all(L, S, Of, Ob, Oms, cur) <= E) opt = e;
+        else break;
+    }
+    free(cur);
+    *e_opt = (int32_t)opt;
+    *cost = INFINITY;
+    *e_all = -1;
+    memset(plan, 0xFF, (size_t)L);
+    if (opt >= 0 && best[opt] != INFINITY) {
+        int64_t m_;
+        gbmw_oracle_backtrack(L, S, E, M, A, best, best_s, (int)opt, plan, cost, &m_);
+        *e_all = gbmw_oracle_e_all(L, S, Of, Ob, Oms, plan);
+    }
+}
+
 int gbmw_oracle_max_threads(void)
 {
 #ifdef _OPENMP

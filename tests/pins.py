@@ -302,6 +302,95 @@ def pin_special_cases(solve):
             assert plan[1] != 2 and plan[3] != 0 and not (plan[1] == 0 and plan[2] == 1)
 
 
+# ---------------------------------------------------------------- Algorithm 3 outer loop
+def py_e_all(Of, Ob, Oms, plan):
+    """Eq. 2 written out: max over i of (forward activations of layers <= i plus
+    backward activations of layer i), plus the model states of all layers."""
+    L = len(plan)
+    ms = sum(int(Oms[k, plan[k]]) for k in range(L))
+    return max(sum(int(Of[k, plan[k]]) for k in range(i + 1)) + int(Ob[i, plan[i]]) for i in range(L)) + ms
+
+
+def py_select(sol, Of, Ob, Oms, E):
+    """Algorithm 3's loop in Python on top of a solver's best[] and plans."""
+    b_up = int(Ob.max())
+    opt = E - b_up if E - b_up >= 0 else -1
+    for e in range(opt + 1, E + 1):
+        if np.isinf(sol.best[e]):
+            continue
+        plan, _, _ = sol.backtrack(e)
+        if py_e_all(Of, Ob, Oms, [int(x) for x in plan]) <= E:
+            opt = e
+        else:
+            break
+    if opt < 0 or np.isinf(sol.best[opt]):
+        return opt, INF, None, -1
+    plan, cost, _ = sol.backtrack(opt)
+    return opt, cost, plan, py_e_all(Of, Ob, Oms, [int(x) for x in plan])
+
+
+def split_memory(p, seed):
+    """O_f, O_b, O_ms with O_f + O_ms == M for a generated instance."""
+    st = gi.Stream(seed)
+    L, S = p.M.shape
+    frac = st.unit(L * S).reshape(L, S)
+    Oms = np.floor(p.M * frac).astype(np.int32)
+    Of = (p.M - Oms).astype(np.int32)
+    hi = max(1, int(p.M.max()))
+    Ob = st.integers(L * S, 0, hi).reshape(L, S).astype(np.int32)
+    return Of, Ob, Oms
+
+
+def pin_select_golden(solve, select, e_all):
+    with open(os.path.join(GOLDEN, "worked_example_alg3.json")) as f:
+        g = json.load(f)
+    with open(os.path.join(GOLDEN, g["base"])) as f:
+        b = json.load(f)
+    c = np.array(b["c"], np.float32); M = np.array(b["M"], np.int32); R = np.array(b["R"], np.float32)
+    Of = np.array(g["Of"], np.int32); Oms = np.array(g["Oms"], np.int32)
+    assert np.array_equal(Of + Oms, M)
+    sol = solve(c, M, R, b["E"])
+    for case in g["cases"]:
+        Ob = np.array(case["Ob"], np.int32)
+        for k, v in case["e_all_of"].items():
+            plan = [int(x) for x in k.split(",")]
+            assert e_all(Of, Ob, Oms, plan) == v == py_e_all(Of, Ob, Oms, plan), (k, v)
+        e_opt, cost, plan, ea = select(sol, Of, Ob, Oms)
+        assert (e_opt, float(cost), list(plan), ea) == (case["e_opt"], case["cost"], case["plan"], case["e_all"])
+
+
+def pin_select_properties(solve, select, e_all):
+    for seed, (L, S, E, Mhi) in enumerate([(4, 4, 120, 30), (6, 3, 90, 20), (5, 5, 60, 25), (3, 4, 40, 30),
+                                           (7, 2, 200, 40), (4, 3, 10, 12)]):
+        p = gi.random_instance(700 + seed, L, S, E, M_rng=(1, Mhi))
+        sol = solve(p.c, p.M, p.R, E)
+        for variant in range(3):
+            Of, Ob, Oms = split_memory(p, 800 + 10 * seed + variant)
+            if variant == 1:
+                Ob[:] = 0                       # no backward peak: every budget is valid
+            if variant == 2:
+                Ob[:] = np.minimum(Ob, 3)       # tiny window
+            b_up = int(Ob.max())
+            # E_all against the definition, for the plans of all budgets
+            for e in range(E + 1):
+                if np.isfinite(sol.best[e]):
+                    plan, _, mem = sol.backtrack(e)
+                    ea = e_all(Of, Ob, Oms, plan)
+                    assert ea == py_e_all(Of, Ob, Oms, [int(x) for x in plan])
+                    assert mem <= ea <= mem + b_up          # E_f <= E_all <= E_f + b_up
+                    if e <= E - b_up:
+                        assert ea <= E                      # no check needed below E - b_up
+            got = select(sol, Of, Ob, Oms)
+            exp = py_select(sol, Of, Ob, Oms, E)
+            assert got[0] == exp[0] and bits(got[1]) == bits(exp[1]) and got[3] == exp[3], (got, exp)
+            if exp[2] is None:
+                assert all(x == 255 for x in got[2])
+            else:
+                assert np.array_equal(got[2], exp[2]) and got[3] <= E
+            if variant == 1 and np.isfinite(sol.best[E]):
+                assert got[0] == E
+
+
 def run_all_pins(solve):
     pin_golden(solve)
     pin_bruteforce(solve)
