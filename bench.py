@@ -187,6 +187,18 @@ def main():
     out["backtrack"] = {"queries": int(len(qi)), "ms": bt * 1e3, "plans_per_s": len(qi) / bt,
                         "note": "host-to-host through gbmw_backtrack: query upload, one lane per "
                                 "query walking L_b argmin records, plan download"}
+    # Algorithm 3's outer loop (overall-memory check over the b_up window, largest valid
+    # E_fwd and its plan per instance) on synthetic O_f / O_b / O_ms with O_f + O_ms == M
+    Of, Ob, Oms = gi.split_memory(p, 4)
+    g.gbmw_select_forward_budget(ctx, Of, Ob, Oms)
+    t0 = time.perf_counter()
+    e_opt, _, _, _ = g.gbmw_select_forward_budget(ctx, Of, Ob, Oms)
+    sb = time.perf_counter() - t0
+    out["select_forward_budget"] = {"ms": sb * 1e3, "instances": p.B,
+                                    "budgets_checked": int(sum(min(int(Ob[int(o):int(o) + int(n)].max()), p.E + 1)
+                                                               for o, n in zip(p.offsets, p.L))),
+                                    "note": "host-to-host through the ABI, includes the upload of the three "
+                                            "O tables and the host-side O_f + O_ms == M check"}
     g.gbmw_destroy(ctx)
     del d
 

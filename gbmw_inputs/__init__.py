@@ -25,7 +25,7 @@ from dataclasses import dataclass
 import numpy as np
 
 __all__ = [
-    "Problem", "Stream", "make_config", "random_instance", "stack",
+    "Problem", "Stream", "make_config", "random_instance", "stack", "split_memory",
     "CONFIG_NAMES",
 ]
 
@@ -234,3 +234,17 @@ def make_config(k: int, B: int | None = None) -> Problem:
             parts.append(Problem(1, 64, 65536, np.array([96]), c, M, R))
         return stack(parts, CONFIG_NAMES[5] if nB == 16 else f"cfg5[:{nB}]")
     raise ValueError(f"unknown config {k}")
+
+
+def split_memory(p: Problem, seed: int, ob_max: int | None = None):
+    """Synthetic O_f, O_b, O_ms [sumL][S] int32 for the overall-memory check of
+    Algorithm 3, with O_f + O_ms == M: the model-state share of each M is a
+    uniform fraction, O_b ~ U{0..ob_max} (default: the largest M)."""
+    st = Stream(seed, lane=77)
+    n, S = p.M.shape
+    frac = st.unit(n * S).reshape(n, S)
+    Oms = np.floor(p.M.astype(np.float64) * frac).astype(np.int32)
+    Of = (p.M - Oms).astype(np.int32)
+    hi = max(1, int(p.M.max())) if ob_max is None else ob_max
+    Ob = st.integers(n * S, 0, hi).reshape(n, S).astype(np.int32)
+    return np.ascontiguousarray(Of), np.ascontiguousarray(Ob), np.ascontiguousarray(Oms)

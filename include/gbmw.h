@@ -118,6 +118,30 @@ gbmw_status gbmw_dp_solve_batched(const gbmw_problem* p, uint32_t flags, gbmw_ct
 gbmw_status gbmw_backtrack(gbmw_ctx* ctx, int32_t nq, const int32_t* q_instance,
                            const int32_t* q_e, uint8_t* plan, float* cost, int32_t* mem_used);
 
+/*
+ * The outer loop of Appendix A, Algorithm 3 on top of a solved context: choose
+ * the forward budget E_fwd_opt whose plan also respects the OVERALL memory
+ * E_all(plan) <= E of Section 4.1.2, Eq. 2,
+ *   E_all = max_i { sum_{k<=i} O_f(k,s_k) + O_b(i,s_i) } + sum_k O_ms(k,s_k),
+ * where the context was solved with M = O_f + O_ms and E = the device budget.
+ * With b_up = max O_b over the instance's layers and strategies, budgets up to
+ * E - b_up need no check; the budgets above are visited in increasing order and
+ * the walk stops at the first plan that does not fit (a budget without any
+ * feasible plan has nothing to check and is passed over; if E - b_up < 0
+ * nothing is valid a priori and the walk starts at 0).
+ * O_f, O_b, O_ms: HOST pointers, [sumL][S] each, same row order as M, all >= 0;
+ * O_f + O_ms must equal the M of the solve (else GBMW_ERR_INVALID_ARG).
+ * Outputs (HOST, caller-owned, any may be NULL):
+ *   e_opt [B]        chosen E_fwd (-1: none)
+ *   cost  [B]        best(e_opt) (+inf if none or infeasible)
+ *   plan  [B][Lmax]  strategies of the chosen plan (0xFF padded / if none)
+ *   e_all [B]        overall memory of the chosen plan (-1 if none)
+ * Waits for the solve and for its own kernels.
+ */
+gbmw_status gbmw_select_forward_budget(gbmw_ctx* ctx, const int32_t* O_f, const int32_t* O_b,
+                                       const int32_t* O_ms, int32_t* e_opt, float* cost,
+                                       uint8_t* plan, int32_t* e_all);
+
 /* Lmax of the last solve (row length of `plan` above); 0 if none. */
 int32_t gbmw_max_layers(const gbmw_ctx* ctx);
 

@@ -29,7 +29,7 @@ GBMW_FLAG_ONE_STREAM = 4
 GBMW_MAX_S = 256
 
 EXPORTS = [
-    "gbmw_dp_solve_batched", "gbmw_backtrack", "gbmw_max_layers", "gbmw_get_best",
+    "gbmw_dp_solve_batched", "gbmw_backtrack", "gbmw_select_forward_budget", "gbmw_max_layers", "gbmw_get_best",
     "gbmw_export_tables", "gbmw_synchronize", "gbmw_last_solve_ms", "gbmw_destroy",
     "gbmw_last_error", "gbmw_version",
 ]
@@ -55,6 +55,8 @@ _lib.gbmw_dp_solve_batched.argtypes = [ct.POINTER(gbmw_problem), ct.c_uint32, ct
 _lib.gbmw_dp_solve_batched.restype = ct.c_int
 _lib.gbmw_backtrack.argtypes = [ct.c_void_p, ct.c_int32] + [ct.c_void_p] * 5
 _lib.gbmw_backtrack.restype = ct.c_int
+_lib.gbmw_select_forward_budget.argtypes = [ct.c_void_p] * 8
+_lib.gbmw_select_forward_budget.restype = ct.c_int
 _lib.gbmw_max_layers.argtypes = [ct.c_void_p]
 _lib.gbmw_max_layers.restype = ct.c_int32
 _lib.gbmw_get_best.argtypes = [ct.c_void_p, ct.c_void_p, ct.c_void_p]
@@ -165,6 +167,23 @@ def gbmw_backtrack(ctx: Context, q_instance, q_e):
     _check(_lib.gbmw_backtrack(ctx.handle, nq, qi.ctypes.data, qe.ctypes.data, plan.ctypes.data,
                                cost.ctypes.data, mem.ctypes.data))
     return plan, cost, mem
+
+
+def gbmw_select_forward_budget(ctx: Context, O_f, O_b, O_ms):
+    """Algorithm 3's outer loop: e_opt [B] int32, cost [B] float32, plan [B][Lmax] uint8,
+    e_all [B] int32 (host arrays)."""
+    sumL = int(ctx.L.sum())
+    arrs = [np.ascontiguousarray(a, dtype=np.int32) for a in (O_f, O_b, O_ms)]
+    assert all(a.shape == (sumL, ctx.S) for a in arrs)
+    Lmax = gbmw_max_layers(ctx)
+    e_opt = np.empty(ctx.B, np.int32)
+    cost = np.empty(ctx.B, np.float32)
+    plan = np.empty((ctx.B, Lmax), np.uint8)
+    e_all = np.empty(ctx.B, np.int32)
+    _check(_lib.gbmw_select_forward_budget(ctx.handle, arrs[0].ctypes.data, arrs[1].ctypes.data,
+                                           arrs[2].ctypes.data, e_opt.ctypes.data, cost.ctypes.data,
+                                           plan.ctypes.data, e_all.ctypes.data))
+    return e_opt, cost, plan, e_all
 
 
 def gbmw_export_tables(ctx: Context, instance: int, l0: int = 0, l1: int | None = None,

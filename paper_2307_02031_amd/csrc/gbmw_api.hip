@@ -382,6 +382,59 @@ gbmw_status gbmw_backtrack(gbmw_ctx* c, int32_t nq, const int32_t* q_instance, c
   return GBMW_OK;
 }
 
+gbmw_status gbmw_select_forward_budget(gbmw_ctx* c, const int32_t* O_f, const int32_t* O_b,
+                                       const int32_t* O_ms, int32_t* e_opt, float* cost,
+                                       uint8_t* plan, int32_t* e_all) {
+  g_err[0] = 0;
+  gbmw_status st = wait_and_check(c);
+  if (st != GBMW_OK) return st;
+  if (!O_f || !O_b || !O_ms) return fail(GBMW_ERR_INVALID_ARG, "null O_f/O_b/O_ms");
+  const size_t n = (size_t)c->sumL * c->S, B = (size_t)c->B, Lm = (size_t)c->Lmax;
+  // O_f + O_ms must be the M the tables were filled with
+  std::vector<int> M(n);
+  HIP_TRY(hipMemcpy(M.data(), c->t.M, n * sizeof(int), hipMemcpyDeviceToHost));
+  for (size_t i = 0; i < n; ++i) {
+    if (O_f[i] < 0 || O_b[i] < 0 || O_ms[i] < 0)
+      return fail(GBMW_ERR_INVALID_ARG, "negative O_f/O_b/O_ms at %zu", i);
+    if ((long long)O_f[i] + O_ms[i] != M[i])
+      return fail(GBMW_ERR_INVALID_ARG, "O_f + O_ms differs from the solve's M at %zu", i);
+  }
+  std::vector<int> bup(B, 0);
+  int max_window = 0;
+  for (size_t b = 0; b < B; ++b) {
+    const size_t lo = (size_t)c->off[b] * c->S, hi = lo + (size_t)c->L[b] * c->S;
+    for (size_t i = lo; i < hi; ++i) bup[b] = std::max(bup[b], O_b[i]);
+    max_window = std::max(max_window, std::min(bup[b], c->E + 1));
+  }
+  // one device block: Of | Ob | Oms | bup | first_bad | e_opt | e_all | cost | plan
+  const size_t bytes = (3 * n + 4 * B) * sizeof(int) + B * sizeof(float) + B * Lm;
+  st = c->d_q.reserve(bytes);
+  if (st != GBMW_OK) return st;
+  int* d_of = (int*)c->d_q.p;
+  int* d_ob = d_of + n;
+  int* d_oms = d_ob + n;
+  int* d_bup = d_oms + n;
+  int* d_fb = d_bup + B;
+  int* d_eopt = d_fb + B;
+  int* d_eall = d_eopt + B;
+  float* d_cost = (float*)(d_eall + B);
+  uint8_t* d_plan = (uint8_t*)(d_cost + B);
+  hipStream_t s = c->stream;
+  HIP_TRY(hipMemcpyAsync(d_of, O_f, n * sizeof(int), hipMemcpyHostToDevice, s));
+  HIP_TRY(hipMemcpyAsync(d_ob, O_b, n * sizeof(int), hipMemcpyHostToDevice, s));
+  HIP_TRY(hipMemcpyAsync(d_oms, O_ms, n * sizeof(int), hipMemcpyHostToDevice, s));
+  HIP_TRY(hipMemcpyAsync(d_bup, bup.data(), B * sizeof(int), hipMemcpyHostToDevice, s));
+  gbmw::launch_select(c->t, d_of, d_ob, d_oms, d_bup, max_window, c->Lmax, d_fb, d_eopt, d_cost,
+                      d_plan, d_eall, s);
+  HIP_TRY(hipGetLastError());
+  if (e_opt) HIP_TRY(hipMemcpyAsync(e_opt, d_eopt, B * sizeof(int), hipMemcpyDeviceToHost, s));
+  if (e_all) HIP_TRY(hipMemcpyAsync(e_all, d_eall, B * sizeof(int), hipMemcpyDeviceToHost, s));
+  if (cost) HIP_TRY(hipMemcpyAsync(cost, d_cost, B * sizeof(float), hipMemcpyDeviceToHost, s));
+  if (plan) HIP_TRY(hipMemcpyAsync(plan, d_plan, B * Lm, hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));     // also keeps the host vector bup alive long enough
+  return GBMW_OK;
+}
+
 gbmw_status gbmw_export_tables(gbmw_ctx* c, int32_t inst, int32_t l0, int32_t l1, float* C,
                                uint8_t* A) {
   g_err[0] = 0;

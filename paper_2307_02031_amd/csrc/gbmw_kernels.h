@@ -51,6 +51,11 @@ void launch_final(const Tables& t, int first, int count, hipStream_t st);
 // Plans for nq queries (all pointers device).
 void launch_backtrack(const Tables& t, int nq, const int* q_inst, const int* q_e, int Lmax,
                       uint8_t* plan, float* cost, int* mem_used, hipStream_t st);
+// Algorithm 3's outer loop (all pointers device): Of/Ob/Oms [sumL][S], bup [B]
+// (max O_b per instance), first_bad [B] scratch, outputs per instance.
+void launch_select(const Tables& t, const int* Of, const int* Ob, const int* Oms, const int* bup,
+                   int max_window, int Lmax, int* first_bad, int* e_opt, float* cost,
+                   uint8_t* plan, int* e_all, hipStream_t st);
 // [S][EP] -> [E+1][S] for rows [row0, row0+n) of C (fp32; base pointer given) or A (bytes).
 void launch_export_f32(const float* src, float* dst, int n, int S, int E, int EP, hipStream_t st);
 void launch_export_u8(const uint8_t* src, uint8_t* dst, int n, int S, int E, int EP, hipStream_t st);

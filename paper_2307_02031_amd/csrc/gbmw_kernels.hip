@@ -420,6 +420,99 @@ void launch_backtrack(const Tables& t, int nq, const int* q_inst, const int* q_e
 }
 
 // ---------------------------------------------------------------------------
+// Algorithm 3's outer loop.  walk_plan follows the argmin records of instance
+// `inst` from budget e down and evaluates Eq. 2 on the way.  Going from the last
+// layer to the first, the forward prefix of layer i is F - suf_i with F the sum
+// of all O_f and suf_i the sum over the layers above i, so
+//   E_all = F + max_i (O_b(i) - suf_i) + sum O_ms.
+// ---------------------------------------------------------------------------
+__device__ long long walk_plan(const Tables& t, int inst, int e, const int* __restrict__ Of,
+                               const int* __restrict__ Ob, const int* __restrict__ Oms,
+                               uint8_t* plan) {
+  const int Lb = t.L[inst], row0 = t.off[inst], S = t.S;
+  int s = t.best_s[(size_t)inst * t.EP + e];
+  long long suf = 0, ms = 0, mx = 0;
+  for (int l = Lb - 1; l >= 0; --l) {
+    const size_t cell = (size_t)(row0 + l) * S + s;
+    if (plan) plan[l] = (uint8_t)s;
+    const long long here = (long long)Ob[cell] - suf;
+    mx = (l == Lb - 1 || here > mx) ? here : mx;
+    suf += Of[cell];
+    ms += Oms[cell];
+    if (l > 0) {
+      const int m = t.M[cell];
+      e -= m;                                            // budget left for layers < l
+      if (m < 0 || e < 0) return -2;                     // only reachable with invalid inputs
+      s = t.A[((size_t)(row0 + l) * S + s) * t.EP + e];
+    }
+  }
+  return suf + mx + ms;
+}
+
+__global__ void k_select_init(int B, int* first_bad) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < B) first_bad[b] = 0x7fffffff;
+}
+
+// one lane per (instance, budget of its window): record the lowest budget
+// whose plan does not fit the overall memory
+__global__ __launch_bounds__(64) void k_select_check(Tables t, const int* __restrict__ Of,
+                                                     const int* __restrict__ Ob,
+                                                     const int* __restrict__ Oms,
+                                                     const int* __restrict__ bup,
+                                                     int* __restrict__ first_bad) {
+  const int inst = blockIdx.y;
+  const int base = t.E - bup[inst];                      // last budget that needs no check
+  const int lo = (base < 0 ? -1 : base) + 1;
+  const int e = lo + blockIdx.x * 64 + threadIdx.x;
+  if (e > t.E) return;
+  if (t.best[(size_t)inst * t.EP + e] == INFINITY) return;   // no plan: nothing to check
+  const long long ea = walk_plan(t, inst, e, Of, Ob, Oms, nullptr);
+  if (ea > (long long)t.E || ea < 0) atomicMin(&first_bad[inst], e);
+}
+
+__global__ __launch_bounds__(64) void k_select_pick(Tables t, const int* __restrict__ Of,
+                                                    const int* __restrict__ Ob,
+                                                    const int* __restrict__ Oms,
+                                                    const int* __restrict__ bup,
+                                                    const int* __restrict__ first_bad, int Lmax,
+                                                    int* __restrict__ e_opt,
+                                                    float* __restrict__ cost,
+                                                    uint8_t* __restrict__ plan,
+                                                    int* __restrict__ e_all) {
+  const int inst = blockIdx.x * 64 + threadIdx.x;
+  if (inst >= t.B) return;
+  const int base = t.E - bup[inst];
+  const int init = base < 0 ? -1 : base;
+  const int fb = first_bad[inst];
+  const int last = (fb == 0x7fffffff) ? t.E : fb - 1;
+  int opt = init;
+  if (last > init && t.best[(size_t)inst * t.EP + last] != INFINITY) opt = last;
+  uint8_t* p = plan + (size_t)inst * Lmax;
+  for (int l = 0; l < Lmax; ++l) p[l] = 0xFF;
+  e_opt[inst] = opt;
+  float cst = INFINITY;
+  long long ea = -1;
+  if (opt >= 0) {
+    cst = t.best[(size_t)inst * t.EP + opt];
+    if (cst != INFINITY) ea = walk_plan(t, inst, opt, Of, Ob, Oms, p);
+  }
+  cost[inst] = cst;
+  e_all[inst] = (int)ea;
+}
+
+void launch_select(const Tables& t, const int* Of, const int* Ob, const int* Oms, const int* bup,
+                   int max_window, int Lmax, int* first_bad, int* e_opt, float* cost,
+                   uint8_t* plan, int* e_all, hipStream_t st) {
+  hipLaunchKernelGGL(k_select_init, dim3((t.B + 63) / 64), dim3(64), 0, st, t.B, first_bad);
+  if (max_window > 0)
+    hipLaunchKernelGGL(k_select_check, dim3((max_window + 63) / 64, t.B), dim3(64), 0, st, t, Of,
+                       Ob, Oms, bup, first_bad);
+  hipLaunchKernelGGL(k_select_pick, dim3((t.B + 63) / 64), dim3(64), 0, st, t, Of, Ob, Oms, bup,
+                     first_bad, Lmax, e_opt, cost, plan, e_all);
+}
+
+// ---------------------------------------------------------------------------
 // export: device [n][S][EP] -> logical [n][E+1][S] through a 64x64 LDS tile
 // ---------------------------------------------------------------------------
 template <typename T>

@@ -329,18 +329,6 @@ def py_select(sol, Of, Ob, Oms, E):
     return opt, cost, plan, py_e_all(Of, Ob, Oms, [int(x) for x in plan])
 
 
-def split_memory(p, seed):
-    """O_f, O_b, O_ms with O_f + O_ms == M for a generated instance."""
-    st = gi.Stream(seed)
-    L, S = p.M.shape
-    frac = st.unit(L * S).reshape(L, S)
-    Oms = np.floor(p.M * frac).astype(np.int32)
-    Of = (p.M - Oms).astype(np.int32)
-    hi = max(1, int(p.M.max()))
-    Ob = st.integers(L * S, 0, hi).reshape(L, S).astype(np.int32)
-    return Of, Ob, Oms
-
-
 def pin_select_golden(solve, select, e_all):
     with open(os.path.join(GOLDEN, "worked_example_alg3.json")) as f:
         g = json.load(f)
@@ -365,7 +353,7 @@ def pin_select_properties(solve, select, e_all):
         p = gi.random_instance(700 + seed, L, S, E, M_rng=(1, Mhi))
         sol = solve(p.c, p.M, p.R, E)
         for variant in range(3):
-            Of, Ob, Oms = split_memory(p, 800 + 10 * seed + variant)
+            Of, Ob, Oms = gi.split_memory(p, 800 + 10 * seed + variant)
             if variant == 1:
                 Ob[:] = 0                       # no backward peak: every budget is valid
             if variant == 2:
