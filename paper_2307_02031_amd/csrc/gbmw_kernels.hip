@@ -129,7 +129,8 @@ __device__ __forceinline__ float fmin3(float a, float b, float c) {
 }
 
 template <int SP, int K, int NW, int CH, int MINW, bool SAVE_X, bool FIRST>
-__global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int tiles, int first) {
+__global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int tiles, int first,
+                                                           int split) {
   constexpr int NC = (SP + CH - 1) / CH;                 // chunks (last may be short)
   constexpr int NP = NC / 2 + 1;                         // prefix minima / blocks
   constexpr int RS = (SP + 2 + 3) / 4 * 4;               // row: SP x R, c, M, padding
@@ -146,9 +147,17 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
   }
   __syncthreads();
 
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int wbase = (tile * NW + wave) * (64 * K);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, scalar
+  const int lane = threadIdx.x & 63;
+  // Normal mode: the workgroup's waves take consecutive row tiles and every
+  // output strategy.  Split mode (small problems, too few workgroups to fill the
+  // chip): the waves share one row tile and divide the output strategies, which
+  // shortens the serial chain per wave NW-fold at the price of loading the tile
+  // NW times (from L2).
+  const int wbase = (split ? tile : tile * NW + wave) * (64 * K);
   if (wbase > E) return;                                 // whole wave beyond the table
+  const int s_begin = split ? (wave * S) / NW : 0;
+  const int s_end = split ? ((wave + 1) * S) / NW : S;
   const float* __restrict__ Cp = c_table(t, inst, row - 1, l - 1);
   float* __restrict__ Cn = c_table(t, inst, row, l);
   uint8_t* __restrict__ An = t.A + (size_t)row * S * EP;
@@ -183,7 +192,7 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
     }
   }
 
-  for (int s = 0; s < S; ++s) {
+  for (int s = s_begin; s < s_end; ++s) {
     float r[RS];
 #pragma unroll
     for (int q = 0; q < RQ; ++q) {
@@ -315,14 +324,17 @@ static void launch_minplus_sp(const Tables& t, int l, int first, int n_active, h
   constexpr int K = Blocking<SP>::K, NW = Blocking<SP>::NW, CH = Blocking<SP>::CH,
                 MINW = Blocking<SP>::MINW;
   constexpr bool SAVE_X = Blocking<SP>::SAVE_X;
-  const int tiles = (t.E + 1 + 64 * K * NW - 1) / (64 * K * NW);
+  int tiles = (t.E + 1 + 64 * K * NW - 1) / (64 * K * NW);
+  // fewer than four workgroups per compute unit: split the strategies over the waves
+  const int split = ((long long)tiles * n_active < 1024) ? 1 : 0;
+  if (split) tiles = (t.E + 1 + 64 * K - 1) / (64 * K);
   constexpr int RS = (SP + 2 + 3) / 4 * 4;
   if (l == 1)
     hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, MINW, SAVE_X, true>), dim3((unsigned)tiles * n_active),
-                       dim3(64 * NW), (size_t)t.S * RS * sizeof(float), st, t, l, tiles, first);
+                       dim3(64 * NW), (size_t)t.S * RS * sizeof(float), st, t, l, tiles, first, split);
   else
     hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, MINW, SAVE_X, false>), dim3((unsigned)tiles * n_active),
-                       dim3(64 * NW), (size_t)t.S * RS * sizeof(float), st, t, l, tiles, first);
+                       dim3(64 * NW), (size_t)t.S * RS * sizeof(float), st, t, l, tiles, first, split);
 }
 
 void launch_minplus(const Tables& t, int l, int first, int n_active, hipStream_t st) {
