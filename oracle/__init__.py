@@ -56,6 +56,8 @@ def _bind(path: str):
     lib.gbmw_oracle_select_budget.argtypes = [ct.c_int, ct.c_int, ct.c_int, i32p, u8p, f32p, u8p,
                                               i32p, i32p, i32p, ct.POINTER(ct.c_int32), f32p, u8p, i64p]
     lib.gbmw_oracle_select_budget.restype = None
+    lib.gbmw_oracle_pipeline_cost.argtypes = [ct.c_int, ct.c_int, f32p, f32p]
+    lib.gbmw_oracle_pipeline_cost.restype = ct.c_float
     return lib
 
 
@@ -133,6 +135,14 @@ def e_all(Of, Ob, Oms, plan) -> int:
     return int(_load().gbmw_oracle_e_all(L, S, _p(_chk(Of, np.int32, (L, S)), ct.c_int32),
                                          _p(_chk(Ob, np.int32, (L, S)), ct.c_int32),
                                          _p(_chk(Oms, np.int32, (L, S)), ct.c_int32), _p(plan, ct.c_uint8)))
+
+
+def pipeline_cost(m: int, C, Cns) -> np.float32:
+    """Eq. 5 / Eq. 8: (m - 1) * max Cns + sum C over the stages."""
+    C = np.ascontiguousarray(C, np.float32)
+    Cns = np.ascontiguousarray(Cns, np.float32)
+    assert C.shape == Cns.shape and C.ndim == 1 and len(C) >= 1
+    return np.float32(_load().gbmw_oracle_pipeline_cost(len(C), int(m), _p(C, ct.c_float), _p(Cns, ct.c_float)))
 
 
 def select_budget(sol: "Solution", Of, Ob, Oms):

@@ -317,6 +317,28 @@ void gbmw_oracle_select_budget(int L, int S, int E, const int32_t *M,
     }
 }
 
+/* ------------------------------------------------------------------ */
+/* Pipeline time of P stages run with m micro-batches (Section 4.2.1,    */
+/* Eq. 5; Appendix C, Eq. 8):                                             */
+/*   C = (m - 1) * max_i Cns_i + sum_i C_i                                */
+/* C_i is a stage's time for the last micro-batch (with gradient          */
+/* synchronisation), Cns_i its time without it (Eq. 5 is the case         */
+/* Cns = C).  fp32: the sum is a left fold over the stages, the product   */
+/* and the final addition are rounded separately.  A stage with no        */
+/* feasible plan (+inf) makes the pipeline +inf.                          */
+/* ------------------------------------------------------------------ */
+float gbmw_oracle_pipeline_cost(int P, int m, const float *C, const float *Cns)
+{
+    float total = C[0], mx = Cns[0];
+    for (int i = 1; i < P; ++i) {
+        total = total + C[i];
+        if (Cns[i] > mx) mx = Cns[i];
+    }
+    if (total == INFINITY || mx == INFINITY) return INFINITY;
+    float head = (float)(m - 1) * mx;
+    return head + total;
+}
+
 int gbmw_oracle_max_threads(void)
 {
 #ifdef _OPENMP

@@ -64,6 +64,7 @@ struct gbmw_ctx {
   int device = 0;
   hipStream_t stream = nullptr;
   bool solved = false;
+  bool index_on_device = false;   // d_L / d_off / d_perm hold this->L / off / perm
   uint32_t flags = 0;
   int B = 0, S = 0, SP = 0, E = 0, EP = 0, sumL = 0, Lmax = 0;
   std::vector<int> L, off, perm;
@@ -223,6 +224,8 @@ gbmw_status gbmw_dp_solve_batched(const gbmw_problem* p, uint32_t flags, gbmw_ct
   c->B = B; c->S = S; c->E = E; c->sumL = sumL; c->Lmax = Lmax;
   c->SP = (S + 3) / 4 * 4;
   c->EP = (E + 1 + 255) / 256 * 256;
+  // a repeated solve of the same batch layout keeps the index arrays already on the device
+  const bool same_layout = !fresh && c->index_on_device && c->L == L && c->off == off && c->perm == perm;
   c->L = L; c->off = off; c->perm = perm;
   const int SP = c->SP, EP = c->EP;
   const bool keep = (flags & GBMW_FLAG_KEEP_ALL_C) != 0;
@@ -258,9 +261,13 @@ gbmw_status gbmw_dp_solve_batched(const gbmw_problem* p, uint32_t flags, gbmw_ct
   }
   // The small index arrays come from host vectors owned by the context, which
   // outlive the copies.
-  HIP_TRY_B(hipMemcpyAsync(c->d_L.p, c->L.data(), sizeof(int) * B, hipMemcpyHostToDevice, st));
-  HIP_TRY_B(hipMemcpyAsync(c->d_off.p, c->off.data(), sizeof(int) * B, hipMemcpyHostToDevice, st));
-  HIP_TRY_B(hipMemcpyAsync(c->d_perm.p, c->perm.data(), sizeof(int) * B, hipMemcpyHostToDevice, st));
+  if (!same_layout) {
+    c->index_on_device = false;
+    HIP_TRY_B(hipMemcpyAsync(c->d_L.p, c->L.data(), sizeof(int) * B, hipMemcpyHostToDevice, st));
+    HIP_TRY_B(hipMemcpyAsync(c->d_off.p, c->off.data(), sizeof(int) * B, hipMemcpyHostToDevice, st));
+    HIP_TRY_B(hipMemcpyAsync(c->d_perm.p, c->perm.data(), sizeof(int) * B, hipMemcpyHostToDevice, st));
+    c->index_on_device = true;
+  }
 
   gbmw::Tables& t = c->t;
   t.B = B; t.S = S; t.SP = SP; t.RS = RS; t.E = E; t.EP = EP; t.keep_all = keep ? 1 : 0;
