@@ -142,6 +142,34 @@ gbmw_status gbmw_select_forward_budget(gbmw_ctx* ctx, const int32_t* O_f, const 
                                        const int32_t* O_ms, int32_t* e_opt, float* cost,
                                        uint8_t* plan, int32_t* e_all);
 
+/*
+ * Pipeline time of Section 4.2.1, Eq. 5 / Appendix C, Eq. 8 for n_pipe
+ * pipelines whose stages are instances of a solved context:
+ *   cost = (m - 1) * max_i Cns_i + sum_i C_i
+ * over the stages i of the pipeline, with C_i = best(e_i) of the stage's
+ * instance at the forward budget e_i chosen for it, and Cns_i the same plan's
+ * time re-evaluated with c_nosync (layer times without gradient
+ * synchronisation; R unchanged): v = c_ns(0,s_0); v = (v + R(l,s_{l-1},s_l)) +
+ * c_ns(l,s_l).  c_nosync == NULL means Cns_i = C_i (Eq. 5).  fp32: the sum is a
+ * left fold over the stages in the order given; product and final addition are
+ * rounded separately.  A stage with e_i < 0 or no feasible plan makes its
+ * pipeline +inf.
+ * All pointers HOST:
+ *   stage_begin     [n_pipe + 1]  stages of pipeline p are stage_begin[p] ..
+ *                                 stage_begin[p+1] - 1 (at least one each)
+ *   stage_instance  [n_stage]     instance index of each stage
+ *   stage_e         [n_stage]     forward budget of each stage (-1..E)
+ *   microbatches    [n_pipe]      m >= 1
+ *   c_nosync        [sumL][S]     >= 0, or NULL
+ *   cost            [n_pipe]      out
+ *   stage_cost, stage_cost_nosync [n_stage] out, either may be NULL
+ * Waits for the solve and for its own kernels.
+ */
+gbmw_status gbmw_pipeline_cost(gbmw_ctx* ctx, int32_t n_pipe, const int32_t* stage_begin,
+                               const int32_t* stage_instance, const int32_t* stage_e,
+                               const int32_t* microbatches, const float* c_nosync, float* cost,
+                               float* stage_cost, float* stage_cost_nosync);
+
 /* Lmax of the last solve (row length of `plan` above); 0 if none. */
 int32_t gbmw_max_layers(const gbmw_ctx* ctx);
 

@@ -29,7 +29,8 @@ GBMW_FLAG_ONE_STREAM = 4
 GBMW_MAX_S = 256
 
 EXPORTS = [
-    "gbmw_dp_solve_batched", "gbmw_backtrack", "gbmw_select_forward_budget", "gbmw_max_layers", "gbmw_get_best",
+    "gbmw_dp_solve_batched", "gbmw_backtrack", "gbmw_select_forward_budget", "gbmw_pipeline_cost",
+    "gbmw_max_layers", "gbmw_get_best",
     "gbmw_export_tables", "gbmw_synchronize", "gbmw_last_solve_ms", "gbmw_destroy",
     "gbmw_last_error", "gbmw_version",
 ]
@@ -57,6 +58,8 @@ _lib.gbmw_backtrack.argtypes = [ct.c_void_p, ct.c_int32] + [ct.c_void_p] * 5
 _lib.gbmw_backtrack.restype = ct.c_int
 _lib.gbmw_select_forward_budget.argtypes = [ct.c_void_p] * 8
 _lib.gbmw_select_forward_budget.restype = ct.c_int
+_lib.gbmw_pipeline_cost.argtypes = [ct.c_void_p, ct.c_int32] + [ct.c_void_p] * 8
+_lib.gbmw_pipeline_cost.restype = ct.c_int
 _lib.gbmw_max_layers.argtypes = [ct.c_void_p]
 _lib.gbmw_max_layers.restype = ct.c_int32
 _lib.gbmw_get_best.argtypes = [ct.c_void_p, ct.c_void_p, ct.c_void_p]
@@ -184,6 +187,26 @@ def gbmw_select_forward_budget(ctx: Context, O_f, O_b, O_ms):
                                            arrs[2].ctypes.data, e_opt.ctypes.data, cost.ctypes.data,
                                            plan.ctypes.data, e_all.ctypes.data))
     return e_opt, cost, plan, e_all
+
+
+def gbmw_pipeline_cost(ctx: Context, stage_begin, stage_instance, stage_e, microbatches, c_nosync=None):
+    """Eq. 5 / Eq. 8: cost [n_pipe], stage_cost [n_stage], stage_cost_nosync [n_stage] (float32)."""
+    sb = np.ascontiguousarray(stage_begin, dtype=np.int32)
+    si = np.ascontiguousarray(stage_instance, dtype=np.int32)
+    se = np.ascontiguousarray(stage_e, dtype=np.int32)
+    mb = np.ascontiguousarray(microbatches, dtype=np.int32)
+    n_pipe = len(mb)
+    assert sb.shape == (n_pipe + 1,) and si.shape == se.shape == (int(sb[-1]),)
+    cns = None if c_nosync is None else np.ascontiguousarray(c_nosync, dtype=np.float32)
+    if cns is not None:
+        assert cns.shape == (int(ctx.L.sum()), ctx.S)
+    cost = np.empty(n_pipe, np.float32)
+    sc = np.empty(len(si), np.float32)
+    scn = np.empty(len(si), np.float32)
+    _check(_lib.gbmw_pipeline_cost(ctx.handle, n_pipe, sb.ctypes.data, si.ctypes.data, se.ctypes.data,
+                                   mb.ctypes.data, None if cns is None else cns.ctypes.data,
+                                   cost.ctypes.data, sc.ctypes.data, scn.ctypes.data))
+    return cost, sc, scn
 
 
 def gbmw_export_tables(ctx: Context, instance: int, l0: int = 0, l1: int | None = None,

@@ -442,6 +442,63 @@ gbmw_status gbmw_select_forward_budget(gbmw_ctx* c, const int32_t* O_f, const in
   return GBMW_OK;
 }
 
+gbmw_status gbmw_pipeline_cost(gbmw_ctx* c, int32_t n_pipe, const int32_t* stage_begin,
+                               const int32_t* stage_instance, const int32_t* stage_e,
+                               const int32_t* microbatches, const float* c_nosync, float* cost,
+                               float* stage_cost, float* stage_cost_nosync) {
+  g_err[0] = 0;
+  gbmw_status st = wait_and_check(c);
+  if (st != GBMW_OK) return st;
+  if (n_pipe < 0) return fail(GBMW_ERR_INVALID_ARG, "n_pipe=%d", n_pipe);
+  if (n_pipe == 0) return GBMW_OK;
+  if (!stage_begin || !stage_instance || !stage_e || !microbatches || !cost)
+    return fail(GBMW_ERR_INVALID_ARG, "null argument");
+  if (stage_begin[0] != 0) return fail(GBMW_ERR_INVALID_ARG, "stage_begin[0] must be 0");
+  for (int p = 0; p < n_pipe; ++p) {
+    if (stage_begin[p + 1] <= stage_begin[p])
+      return fail(GBMW_ERR_INVALID_ARG, "pipeline %d has no stage", p);
+    if (microbatches[p] < 1) return fail(GBMW_ERR_INVALID_ARG, "microbatches[%d]=%d", p, microbatches[p]);
+  }
+  const size_t ns = (size_t)stage_begin[n_pipe], np_ = (size_t)n_pipe, Lm = (size_t)c->Lmax;
+  for (size_t i = 0; i < ns; ++i) {
+    if (stage_instance[i] < 0 || stage_instance[i] >= c->B)
+      return fail(GBMW_ERR_INVALID_ARG, "stage_instance[%zu]=%d", i, stage_instance[i]);
+    if (stage_e[i] < -1 || stage_e[i] > c->E)
+      return fail(GBMW_ERR_INVALID_ARG, "stage_e[%zu]=%d not in -1..%d", i, stage_e[i], c->E);
+  }
+  const size_t ncs = c_nosync ? (size_t)c->sumL * c->S : 0;
+  for (size_t i = 0; i < ncs; ++i)
+    if (!(c_nosync[i] >= 0.0f)) return fail(GBMW_ERR_INVALID_ARG, "c_nosync[%zu] is NaN or negative", i);
+  // one device block: begin | mb | inst | e | C | Cns | cost | c_nosync | plan scratch
+  const size_t bytes = (np_ + 1 + np_ + 2 * ns) * sizeof(int) + (2 * ns + np_ + ncs) * sizeof(float) + ns * Lm;
+  st = c->d_q.reserve(bytes);
+  if (st != GBMW_OK) return st;
+  int* d_begin = (int*)c->d_q.p;
+  int* d_mb = d_begin + np_ + 1;
+  int* d_inst = d_mb + np_;
+  int* d_e = d_inst + ns;
+  float* d_C = (float*)(d_e + ns);
+  float* d_Cns = d_C + ns;
+  float* d_cost = d_Cns + ns;
+  float* d_cns = d_cost + np_;
+  uint8_t* d_plan = (uint8_t*)(d_cns + ncs);
+  hipStream_t s = c->stream;
+  HIP_TRY(hipMemcpyAsync(d_begin, stage_begin, (np_ + 1) * sizeof(int), hipMemcpyHostToDevice, s));
+  HIP_TRY(hipMemcpyAsync(d_mb, microbatches, np_ * sizeof(int), hipMemcpyHostToDevice, s));
+  HIP_TRY(hipMemcpyAsync(d_inst, stage_instance, ns * sizeof(int), hipMemcpyHostToDevice, s));
+  HIP_TRY(hipMemcpyAsync(d_e, stage_e, ns * sizeof(int), hipMemcpyHostToDevice, s));
+  if (ncs) HIP_TRY(hipMemcpyAsync(d_cns, c_nosync, ncs * sizeof(float), hipMemcpyHostToDevice, s));
+  gbmw::launch_pipeline_cost(c->t, (int)ns, d_inst, d_e, ncs ? d_cns : nullptr, d_plan, c->Lmax, d_C,
+                             d_Cns, n_pipe, d_begin, d_mb, d_cost, s);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipMemcpyAsync(cost, d_cost, np_ * sizeof(float), hipMemcpyDeviceToHost, s));
+  if (stage_cost) HIP_TRY(hipMemcpyAsync(stage_cost, d_C, ns * sizeof(float), hipMemcpyDeviceToHost, s));
+  if (stage_cost_nosync)
+    HIP_TRY(hipMemcpyAsync(stage_cost_nosync, d_Cns, ns * sizeof(float), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  return GBMW_OK;
+}
+
 gbmw_status gbmw_export_tables(gbmw_ctx* c, int32_t inst, int32_t l0, int32_t l1, float* C,
                                uint8_t* A) {
   g_err[0] = 0;

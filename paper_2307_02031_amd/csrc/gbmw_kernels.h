@@ -56,6 +56,12 @@ void launch_backtrack(const Tables& t, int nq, const int* q_inst, const int* q_e
 void launch_select(const Tables& t, const int* Of, const int* Ob, const int* Oms, const int* bup,
                    int max_window, int Lmax, int* first_bad, int* e_opt, float* cost,
                    uint8_t* plan, int* e_all, hipStream_t st);
+// Pipeline time (all pointers device): per stage C = best and Cns = the plan under
+// c_ns (nullptr: C); per pipeline (m - 1) * max Cns + sum C.
+void launch_pipeline_cost(const Tables& t, int n_stage, const int* st_inst, const int* st_e,
+                          const float* c_ns, uint8_t* plan_scratch, int Lmax, float* st_C,
+                          float* st_Cns, int n_pipe, const int* st_begin, const int* mb,
+                          float* cost, hipStream_t st);
 // [S][EP] -> [E+1][S] for rows [row0, row0+n) of C (fp32; base pointer given) or A (bytes).
 void launch_export_f32(const float* src, float* dst, int n, int S, int E, int EP, hipStream_t st);
 void launch_export_u8(const uint8_t* src, uint8_t* dst, int n, int S, int E, int EP, hipStream_t st);

@@ -525,6 +525,87 @@ void launch_select(const Tables& t, const int* Of, const int* Ob, const int* Oms
 }
 
 // ---------------------------------------------------------------------------
+// Pipeline time (Eq. 5 / Eq. 8).  One lane per stage walks its plan down the
+// argmin records into a scratch row, then re-evaluates it upward with the costs
+// without gradient synchronisation; R(l, s', s) is read from the transposed
+// table Rt[row][s][s'].
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void k_stage_cost(Tables t, int n_stage,
+                                                   const int* __restrict__ st_inst,
+                                                   const int* __restrict__ st_e,
+                                                   const float* __restrict__ c_ns,
+                                                   uint8_t* __restrict__ plan_scratch, int Lmax,
+                                                   float* __restrict__ st_C,
+                                                   float* __restrict__ st_Cns) {
+  const int q = blockIdx.x * 64 + threadIdx.x;
+  if (q >= n_stage) return;
+  const int inst = st_inst[q];
+  int e = st_e[q];
+  float C = INFINITY, Cns = INFINITY;
+  if (e >= 0) C = t.best[(size_t)inst * t.EP + e];
+  if (C != INFINITY) {
+    if (!c_ns) {
+      Cns = C;
+    } else {
+      const int Lb = t.L[inst], row0 = t.off[inst], S = t.S;
+      uint8_t* plan = plan_scratch + (size_t)q * Lmax;
+      int s = t.best_s[(size_t)inst * t.EP + e];
+      bool ok = true;
+      for (int l = Lb - 1; l >= 1; --l) {
+        plan[l] = (uint8_t)s;
+        e -= t.M[(size_t)(row0 + l) * S + s];
+        if (e < 0) { ok = false; break; }                // only reachable with invalid inputs
+        s = t.A[((size_t)(row0 + l) * S + s) * t.EP + e];
+      }
+      if (ok) {
+        plan[0] = (uint8_t)s;
+        float v = c_ns[(size_t)row0 * S + s];
+        for (int l = 1; l < Lb; ++l) {
+          const int sn = plan[l];
+          const float r = t.Rt[((size_t)(row0 + l) * S + sn) * t.RS + s];
+          v = (v + r) + c_ns[(size_t)(row0 + l) * S + sn];
+          s = sn;
+        }
+        Cns = v;
+      }
+    }
+  }
+  st_C[q] = C;
+  st_Cns[q] = Cns;
+}
+
+__global__ __launch_bounds__(64) void k_pipeline_cost(int n_pipe, const int* __restrict__ st_begin,
+                                                      const int* __restrict__ mb,
+                                                      const float* __restrict__ st_C,
+                                                      const float* __restrict__ st_Cns,
+                                                      float* __restrict__ cost) {
+  const int p = blockIdx.x * 64 + threadIdx.x;
+  if (p >= n_pipe) return;
+  const int b = st_begin[p], e = st_begin[p + 1];
+  float total = st_C[b], mx = st_Cns[b];
+  for (int i = b + 1; i < e; ++i) {
+    total = total + st_C[i];
+    mx = st_Cns[i] > mx ? st_Cns[i] : mx;
+  }
+  float out = INFINITY;
+  if (total != INFINITY && mx != INFINITY) {
+    const float head = (float)(mb[p] - 1) * mx;
+    out = head + total;
+  }
+  cost[p] = out;
+}
+
+void launch_pipeline_cost(const Tables& t, int n_stage, const int* st_inst, const int* st_e,
+                          const float* c_ns, uint8_t* plan_scratch, int Lmax, float* st_C,
+                          float* st_Cns, int n_pipe, const int* st_begin, const int* mb,
+                          float* cost, hipStream_t st) {
+  hipLaunchKernelGGL(k_stage_cost, dim3((n_stage + 63) / 64), dim3(64), 0, st, t, n_stage, st_inst,
+                     st_e, c_ns, plan_scratch, Lmax, st_C, st_Cns);
+  hipLaunchKernelGGL(k_pipeline_cost, dim3((n_pipe + 63) / 64), dim3(64), 0, st, n_pipe, st_begin,
+                     mb, st_C, st_Cns, cost);
+}
+
+// ---------------------------------------------------------------------------
 // export: device [n][S][EP] -> logical [n][E+1][S] through a 64x64 LDS tile
 // ---------------------------------------------------------------------------
 template <typename T>
