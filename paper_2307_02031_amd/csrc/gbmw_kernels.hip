@@ -246,14 +246,18 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
 #pragma unroll
               for (int i = hi - 2; i >= lo; --i) a = (x[i] == T) ? i : a;
             } else {
-            // the sums are not kept: redo them from the R row (same operands, same bits)
-            typedef const volatile __attribute__((address_space(3))) float* lds_cvf_t;
-#pragma clang diagnostic push
-#pragma clang diagnostic ignored "-Wold-style-cast"
-            lds_cvf_t rl = (lds_cvf_t)(rt_lds) + s * RS;
-#pragma clang diagnostic pop
+              // The sums are not kept: redo them from the R row (same operands, same
+              // bits).  The row offset goes through an opaque register so that these
+              // reads are not merged with the value pass's (which would keep the whole
+              // row live), yet can be issued together.
+              int roff = s * RS;
+              asm volatile("" : "+v"(roff));
+              const float* rl = reinterpret_cast<const float*>(rt_lds) + roff;
+              float rr[2 * CH];
 #pragma unroll
-            for (int i = hi - 2; i >= lo; --i) a = (cp[j][i] + rl[i] == T) ? i : a;
+              for (int i = lo; i < hi - 1; ++i) rr[i - lo] = rl[i];
+#pragma unroll
+              for (int i = hi - 2; i >= lo; --i) a = (cp[j][i] + rr[i - lo] == T) ? i : a;
             }
             arg = a;
           }
