@@ -141,7 +141,7 @@ gbmw_status gbmw_dp_solve_batched(const gbmw_problem* p, uint32_t flags, gbmw_ct
   if (!p->L || !p->c || !p->M || !p->R) return fail(GBMW_ERR_INVALID_ARG, "null L/c/M/R");
   if (p->B < 1 || p->B > 65535) return fail(GBMW_ERR_INVALID_ARG, "B=%d not in 1..65535", p->B);
   if (p->S < 1 || p->S > GBMW_MAX_S) return fail(GBMW_ERR_INVALID_ARG, "S=%d not in 1..256", p->S);
-  if (p->E < 0 || p->E > (1 << 30)) return fail(GBMW_ERR_INVALID_ARG, "E=%d out of range", p->E);
+  if (p->E < 0 || p->E > (1 << 28)) return fail(GBMW_ERR_INVALID_ARG, "E=%d out of range", p->E);
   if (p->ptr_space != GBMW_PTR_HOST && p->ptr_space != GBMW_PTR_DEVICE)
     return fail(GBMW_ERR_INVALID_ARG, "ptr_space=%d", p->ptr_space);
   if (flags & ~(uint32_t)(GBMW_FLAG_KEEP_ALL_C | GBMW_FLAG_TIME_KERNELS | GBMW_FLAG_ONE_STREAM))

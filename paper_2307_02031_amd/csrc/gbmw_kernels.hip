@@ -124,6 +124,9 @@ void launch_init_layer0(const Tables& t, bool only_short, hipStream_t st) {
 //   compares into wave masks; a block is re-scanned only when some lane of
 //   the wave first hits it, which for neighbouring budgets is usually one.
 // ---------------------------------------------------------------------------
+// Word 3 of a gfx9-family raw buffer descriptor: 32-bit data format, no swizzle.
+constexpr int kBufWord3 = 0x00020000;
+
 __device__ __forceinline__ float fmin3(float a, float b, float c) {
   return __builtin_fminf(__builtin_fminf(a, b), c);
 }
@@ -199,9 +202,22 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
       const float4 v = rt_lds[s * RQ + q];
       r[4 * q] = v.x; r[4 * q + 1] = v.y; r[4 * q + 2] = v.z; r[4 * q + 3] = v.w;
     }
-    const float cs = r[SP];
-    const int m_raw = __float_as_int(r[SP + 1]);
-    const int m = m_raw < 0 ? 0x7fffffff : m_raw;        // invalid M: column infeasible
+    // c(l,s) and M(l,s) are the same in every lane: move them to scalar registers.
+    const float cs = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(r[SP])));
+    const int m_raw = __builtin_amdgcn_readfirstlane(__float_as_int(r[SP + 1]));
+    // invalid (negative) M: the column is infeasible; beyond E + 1 nothing changes
+    const int m = (m_raw < 0 || m_raw > E + 1) ? E + 1 : m_raw;
+    // Stores go through buffer descriptors of column s: the address is a scalar base
+    // plus the lane's byte offset (no per-lane pointer arithmetic in the loop), and
+    // the hardware range check drops what lies outside [0, num_records):
+    //   bc:   rows 0..E of column s         -> the shifted store at e' + m is dropped
+    //                                          beyond E without a compare
+    //   binf: rows 0..m-1 of column s       -> the +inf prefix
+    //   ba:   rows 0..EP-1 of column s of A (padding rows are harmless)
+    float* Cs = Cn + (size_t)s * EP;
+    const __amdgpu_buffer_rsrc_t bc = __builtin_amdgcn_make_buffer_rsrc(Cs, 0, (E + 1) * 4, kBufWord3);
+    const __amdgpu_buffer_rsrc_t binf = __builtin_amdgcn_make_buffer_rsrc(Cs, 0, m * 4, kBufWord3);
+    const __amdgpu_buffer_rsrc_t ba = __builtin_amdgcn_make_buffer_rsrc(An + (size_t)s * EP, 0, EP, kBufWord3);
 
 #pragma unroll
     for (int j = 0; j < K; ++j) {
@@ -267,9 +283,10 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
       }
 
       const int e = e0 + 64 * j;                         // pre-shift budget e'
-      An[(size_t)s * EP + e] = (uint8_t)arg;
-      if (m <= E - e) Cn[(size_t)s * EP + e + m] = T + cs;
-      if (e < m || e > E) Cn[(size_t)s * EP + e] = INFINITY;
+      __builtin_amdgcn_raw_buffer_store_b8((unsigned char)arg, ba, e, 0, 0);
+      __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(T + cs), bc, (e + m) * 4, 0, 0);
+      if (wbase + 64 * j < m)                            // wave-uniform: some lane is below M
+        __builtin_amdgcn_raw_buffer_store_b32(0x7f800000u, binf, e * 4, 0, 0);
     }
   }
 }
