@@ -74,7 +74,7 @@ enum {
 typedef struct {
   int32_t B;        /* number of instances, >= 1                               */
   int32_t S;        /* strategies per layer, 1..GBMW_MAX_S (shared)            */
-  int32_t E;        /* forward budget in units, >= 0; tables have rows 0..E    */
+  int32_t E;        /* forward budget in units, 0..2^28; tables have rows 0..E */
   const int32_t* L; /* [B] layers per instance, each >= 1                      */
   const float* c;   /* [sumL][S]     c[off_b + l][s]  >= 0, +inf = forbidden   */
   const int32_t* M; /* [sumL][S]     M[off_b + l][s]  >= 0                     */
