@@ -26,7 +26,8 @@ import numpy as np
 
 __all__ = [
     "Problem", "Stream", "make_config", "random_instance", "stack", "split_memory",
-    "CONFIG_NAMES",
+    "CONFIG_NAMES", "PipelineModel", "random_pipeline_model", "structured_pipeline_model",
+    "uniform_pipeline_model", "proportional_partition",
 ]
 
 _MASK = np.uint64(0xFFFFFFFFFFFFFFFF)
@@ -248,3 +249,121 @@ def split_memory(p: Problem, seed: int, ob_max: int | None = None):
     hi = max(1, int(p.M.max())) if ob_max is None else ob_max
     Ob = st.integers(n * S, 0, hi).reshape(n, S).astype(np.int32)
     return np.ascontiguousarray(Of), np.ascontiguousarray(Ob), np.ascontiguousarray(Oms)
+
+
+# --------------------------------------------------------------------------
+# Whole models cut into pipeline stages (inputs of Algorithm 2's partition
+# loop).  The memory of a layer depends on the stage it sits in: under 1F1B
+# stage i of P keeps the activations of P - i micro-batches (Section 4.2.1).
+# --------------------------------------------------------------------------
+@dataclass
+class PipelineModel:
+    """One (batch size, PP degree) pair: Lm layers, P stages, m micro-batches.
+    c, c_ns float32 [Lm][S]; R float32 [Lm][S][S]; M int32 [P][Lm][S];
+    p0, p_t int32 [P] (initial and time-balanced partition: layers per stage)."""
+    S: int
+    E: int
+    P: int
+    m: int
+    c: np.ndarray
+    c_ns: np.ndarray
+    R: np.ndarray
+    M: np.ndarray
+    p0: np.ndarray
+    p_t: np.ndarray | None
+    name: str = ""
+
+    def __post_init__(self):
+        self.c = np.ascontiguousarray(self.c, dtype=np.float32)
+        self.c_ns = np.ascontiguousarray(self.c_ns, dtype=np.float32)
+        self.R = np.ascontiguousarray(self.R, dtype=np.float32)
+        self.M = np.ascontiguousarray(self.M, dtype=np.int32)
+        self.p0 = np.ascontiguousarray(self.p0, dtype=np.int32)
+        if self.p_t is not None:
+            self.p_t = np.ascontiguousarray(self.p_t, dtype=np.int32)
+        Lm = self.c.shape[0]
+        assert self.c.shape == (Lm, self.S) and self.c_ns.shape == (Lm, self.S)
+        assert self.R.shape == (Lm, self.S, self.S) and self.M.shape == (self.P, Lm, self.S)
+        for p in (self.p0, self.p_t):
+            assert p is None or (p.shape == (self.P,) and p.min() >= 1 and int(p.sum()) == Lm)
+
+    @property
+    def Lm(self) -> int:
+        return self.c.shape[0]
+
+    def as_dict(self) -> dict:
+        return dict(c=self.c, c_ns=self.c_ns, R=self.R, M=self.M)
+
+
+def proportional_partition(Lm: int, weights) -> np.ndarray:
+    """Layer counts proportional to the weights, each at least 1, summing to Lm
+    (largest remainders first, the earlier stage on a tie)."""
+    w = np.asarray(weights, np.float64)
+    P = len(w)
+    assert Lm >= P
+    share = (Lm - P) * w / w.sum()
+    p = np.floor(share).astype(np.int64)
+    rest = Lm - P - int(p.sum())
+    order = sorted(range(P), key=lambda i: (-(share[i] - p[i]), i))
+    for i in order[:rest]:
+        p[i] += 1
+    return (p + 1).astype(np.int32)
+
+
+def _stage_memory(state, act, P):
+    """M[i] = state + act * (P - i), rounded half away from zero, at least 1."""
+    inflight = np.arange(P, 0, -1, dtype=np.float64)
+    M = state[None] + act[None] * inflight[:, None, None]
+    return np.maximum(1.0, _round_half_away(M)).astype(np.int64)
+
+
+def random_pipeline_model(seed: int, Lm: int, S: int, P: int, E: int, m: int = 4,
+                          c_rng=(1.0, 10.0), M_rng=(1, 8), R_rng=(0.0, 2.0),
+                          with_pt: bool = True, name: str = "") -> PipelineModel:
+    """Unstructured model: c, state and activation memory, R uniform;
+    c_ns = c * U[0.5, 1); p0 favours deep stages (weights 1..P), p_t is even."""
+    st = Stream(seed, lane=5)
+    c = st.uniform(Lm * S, *c_rng).reshape(Lm, S)
+    c_ns = (c.astype(np.float64) * st.uniform(Lm * S, 0.5, 1.0).reshape(Lm, S)).astype(np.float32)
+    state = st.integers(Lm * S, *M_rng).reshape(Lm, S).astype(np.float64)
+    act = st.integers(Lm * S, *M_rng).reshape(Lm, S).astype(np.float64) / 2.0
+    R = _zero_diag(st.uniform(Lm * S * S, *R_rng).reshape(Lm, S, S))
+    M = _stage_memory(state, act, P)
+    p0 = proportional_partition(Lm, np.arange(1, P + 1))
+    p_t = proportional_partition(Lm, np.ones(P)) if with_pt else None
+    return PipelineModel(S, E, P, m, c, c_ns, R, M, p0, p_t, name or f"pipe-rand{seed}")
+
+
+def structured_pipeline_model(seed: int, Lm: int, P: int, E: int, m: int = 8, S: int = 44,
+                              act_scale: float = 0.25, name: str = "") -> PipelineModel:
+    """The 22/44-strategy layer model of _structured_instance as a whole model:
+    state = Mbase/2, activation per in-flight micro-batch = Mbase/2 * act_scale
+    (halved under checkpointing), both divided by shard_j; c_ns = 0.8 c for the
+    data-parallel-heavy bases (j mod 4 < 2), c otherwise.  p0 puts more layers
+    on deep stages (weights 1/(P - i + 1/act_scale), i.e. inverse to the stage's
+    share of memory), p_t is the even split."""
+    st = Stream(seed, lane=6)
+    c, _, R = _structured_instance(st, Lm, S)
+    s = np.arange(S)
+    j, k = s % 22, s // 22
+    shard = 2.0 ** (j % 4)
+    Mbase = Stream(seed, lane=7).integers(Lm, 512, 4096).astype(np.float64)
+    state = (Mbase[:, None] / 2.0) / shard[None, :]
+    act = (Mbase[:, None] / 2.0) * act_scale * np.where(k == 1, 0.5, 1.0)[None, :] / shard[None, :]
+    M = _stage_memory(state, act, P)
+    c_ns = (c.astype(np.float64) * np.where(j % 4 < 2, 0.8, 1.0)[None, :]).astype(np.float32)
+    w = 1.0 / (np.arange(P, 0, -1) + 1.0 / act_scale)
+    return PipelineModel(S, E, P, m, c, c_ns, R, M, proportional_partition(Lm, w),
+                         proportional_partition(Lm, np.ones(P)), name or f"pipe-struct{seed}")
+
+
+def uniform_pipeline_model(Lm: int, P: int, E: int, p0, cost: float = 2.0, r: float = 0.5,
+                           mem=None, m: int = 2, p_t=None) -> PipelineModel:
+    """S = 1, every layer alike: time cost, transformation r, memory mem[i] per
+    layer in stage i (default 1).  A stage of n layers then takes exactly
+    n*cost + (n-1)*r (dyadic values) and mem[i]*n memory."""
+    mem = [1] * P if mem is None else mem
+    c = np.full((Lm, 1), cost, np.float32)
+    R = np.full((Lm, 1, 1), r, np.float32)
+    M = np.array([[[mem[i]]] * Lm for i in range(P)], np.int32)
+    return PipelineModel(1, E, P, m, c, c * np.float32(0.5), R, M, np.array(p0), p_t, "pipe-uniform")

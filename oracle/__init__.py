@@ -85,6 +85,7 @@ def plan_cost(c, M, R, plan):
     """(cost float32, mem int) of one plan by the plain definition."""
     L, S = c.shape
     plan = np.ascontiguousarray(plan, dtype=np.uint8)
+    assert L >= 1 and plan.shape == (L,) and int(plan.max()) < S, "not a plan of this instance"
     cost, mem = ct.c_float(), ct.c_int64()
     _load().gbmw_oracle_plan_cost(L, S, _p(_chk(c, np.float32, (L, S)), ct.c_float),
                                   _p(_chk(M, np.int32, (L, S)), ct.c_int32),
