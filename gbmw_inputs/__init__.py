@@ -319,9 +319,10 @@ def _stage_memory(state, act, P):
 
 def random_pipeline_model(seed: int, Lm: int, S: int, P: int, E: int, m: int = 4,
                           c_rng=(1.0, 10.0), M_rng=(1, 8), R_rng=(0.0, 2.0),
-                          with_pt: bool = True, name: str = "") -> PipelineModel:
+                          with_pt: bool = True, skew: bool = False, name: str = "") -> PipelineModel:
     """Unstructured model: c, state and activation memory, R uniform;
-    c_ns = c * U[0.5, 1); p0 favours deep stages (weights 1..P), p_t is even."""
+    c_ns = c * U[0.5, 1); p0 favours deep stages (weights 1..P; with skew: one
+    layer per stage and all the others on the last), p_t is even."""
     st = Stream(seed, lane=5)
     c = st.uniform(Lm * S, *c_rng).reshape(Lm, S)
     c_ns = (c.astype(np.float64) * st.uniform(Lm * S, 0.5, 1.0).reshape(Lm, S)).astype(np.float32)
@@ -329,30 +330,30 @@ def random_pipeline_model(seed: int, Lm: int, S: int, P: int, E: int, m: int = 4
     act = st.integers(Lm * S, *M_rng).reshape(Lm, S).astype(np.float64) / 2.0
     R = _zero_diag(st.uniform(Lm * S * S, *R_rng).reshape(Lm, S, S))
     M = _stage_memory(state, act, P)
-    p0 = proportional_partition(Lm, np.arange(1, P + 1))
+    p0 = proportional_partition(Lm, [0.0] * (P - 1) + [1.0] if skew else np.arange(1, P + 1))
     p_t = proportional_partition(Lm, np.ones(P)) if with_pt else None
     return PipelineModel(S, E, P, m, c, c_ns, R, M, p0, p_t, name or f"pipe-rand{seed}")
 
 
 def structured_pipeline_model(seed: int, Lm: int, P: int, E: int, m: int = 8, S: int = 44,
-                              act_scale: float = 0.25, name: str = "") -> PipelineModel:
+                              act_scale: float = 1.0, name: str = "") -> PipelineModel:
     """The 22/44-strategy layer model of _structured_instance as a whole model:
-    state = Mbase/2, activation per in-flight micro-batch = Mbase/2 * act_scale
+    state = Mbase/8, activation per in-flight micro-batch = Mbase/2 * act_scale
     (halved under checkpointing), both divided by shard_j; c_ns = 0.8 c for the
     data-parallel-heavy bases (j mod 4 < 2), c otherwise.  p0 puts more layers
-    on deep stages (weights 1/(P - i + 1/act_scale), i.e. inverse to the stage's
-    share of memory), p_t is the even split."""
+    on deep stages (weights 1/(P - i), inverse to the micro-batches in flight),
+    p_t is the even split."""
     st = Stream(seed, lane=6)
     c, _, R = _structured_instance(st, Lm, S)
     s = np.arange(S)
     j, k = s % 22, s // 22
     shard = 2.0 ** (j % 4)
     Mbase = Stream(seed, lane=7).integers(Lm, 512, 4096).astype(np.float64)
-    state = (Mbase[:, None] / 2.0) / shard[None, :]
+    state = (Mbase[:, None] / 8.0) / shard[None, :]
     act = (Mbase[:, None] / 2.0) * act_scale * np.where(k == 1, 0.5, 1.0)[None, :] / shard[None, :]
     M = _stage_memory(state, act, P)
     c_ns = (c.astype(np.float64) * np.where(j % 4 < 2, 0.8, 1.0)[None, :]).astype(np.float32)
-    w = 1.0 / (np.arange(P, 0, -1) + 1.0 / act_scale)
+    w = 1.0 / np.arange(P, 0, -1)
     return PipelineModel(S, E, P, m, c, c_ns, R, M, proportional_partition(Lm, w),
                          proportional_partition(Lm, np.ones(P)), name or f"pipe-struct{seed}")
 

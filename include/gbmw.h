@@ -54,12 +54,14 @@ enum {
   GBMW_FLAG_KEEP_ALL_C = 1u,   /* keep every layer's fp32 table (default: last two) */
   GBMW_FLAG_TIME_KERNELS = 2u, /* record a HIP event pair around every min-plus launch
                                   (implies GBMW_FLAG_ONE_STREAM)                       */
-  GBMW_FLAG_ONE_STREAM = 4u    /* enqueue every kernel on p->stream itself.  Default: the
+  GBMW_FLAG_ONE_STREAM = 4u,   /* enqueue every kernel on p->stream itself.  Default: the
                                   instances are split into groups whose per-layer
                                   launches run on library-owned helper streams of default
                                   priority that fork from and join back into p->stream
                                   with events, so the call is still ordered on p->stream
                                   as a whole                                             */
+  GBMW_FLAG_RESOLVE_ALL = 8u   /* gbmw_partition_search only: solve every stage of every
+                                  live pair in every round                               */
 };
 
 #define GBMW_MAX_S 256
@@ -169,6 +171,99 @@ gbmw_status gbmw_pipeline_cost(gbmw_ctx* ctx, int32_t n_pipe, const int32_t* sta
                                const int32_t* stage_instance, const int32_t* stage_e,
                                const int32_t* microbatches, const float* c_nosync, float* cost,
                                float* stage_cost, float* stage_cost_nosync);
+
+/*
+ * The inner while-loop of Algorithm 2 (bi-objective optimisation of the pipeline
+ * partition, Section 4.2.2 and Appendix B) for n_chain independent
+ * (batch size, PP degree) pairs at once.  Pair k cuts its model of Lm_k layers
+ * into P_k stages; a partition p is the list of layer counts per stage.  Starting
+ * from p0 (the memory-balanced partition), each round
+ *   - searches p: every stage's layers are solved under budget E with that
+ *     stage's memory table (Eq. 3), the plan at e = E gives the stage time C_i,
+ *     its time without gradient synchronisation Cns_i and its memory O_i; the
+ *     pipeline time is Eq. 8, the balance degrees are Eq. 6
+ *       alpha_t = 1 - max_i C_i / sum_i C_i,  alpha_m = 1 - max_i O_i / sum_i O_i;
+ *   - PP_Partition_Adjust: the slowest stage (lowest index among equals) hands
+ *     its boundary layer to the adjacent stage with the smaller time (the earlier
+ *     one among equals); a stage of one layer hands nothing over;
+ *   - Validate: with every layer keeping the strategy just found, each stage of
+ *     the new partition must (1) take no longer than the slowest stage did,
+ *     (2) need no more than E, (3) need no more than O_t, the largest stage
+ *     memory of the searched time-balanced partition p_t (no such limit when p_t
+ *     is NULL or its search is infeasible).  A partition searched before is not
+ *     searched again.
+ * The chain of a pair ends when the new partition is rejected, when a search is
+ * infeasible (pipeline time +inf), or after max_iter searches.  Algorithm 2's
+ * value for the pair is the cost of its last trace entry.
+ * Rounds of all pairs run in lockstep, each as ONE batched table solve of the
+ * stages that changed (a stage whose layers did not change keeps its result;
+ * GBMW_FLAG_RESOLVE_ALL solves every stage of every live pair each round, with
+ * identical results).
+ *
+ * fp32 contract: stage times as in gbmw_dp_solve_batched; re-evaluations under
+ * fixed strategies as in gbmw_pipeline_cost (v = c(a, s_a); v = (v + R(l,
+ * s_{l-1}, s_l)) + c(l, s_l); the first layer of a stage pays no R); alpha_t is
+ * 1 - max / (left fold of C in stage order), all fp32; alpha_m is computed in
+ * fp64 from the integer memories and rounded to fp32; both are 0 for a zero sum
+ * and for an infeasible search.
+ *
+ * All pointers are HOST pointers; the call copies the model in, runs every step
+ * in kernels on `stream` (one small device-to-host read of the accept flags per
+ * round) and returns when the outputs are complete.  Row order: pairs are
+ * concatenated; lrow_k = Lm_0 + .. + Lm_{k-1}, prow_k = P_0 + .. + P_{k-1},
+ * mrow_k = P_0*Lm_0 + .. + P_{k-1}*Lm_{k-1}.
+ */
+typedef struct {
+  int32_t n_chain;       /* number of pairs, >= 1                                     */
+  int32_t S;             /* strategies, 1..GBMW_MAX_S                                 */
+  int32_t E;             /* memory budget of every stage, 0..2^28                     */
+  int32_t max_iter;      /* searches per pair, 1..4096                                */
+  const int32_t* P;      /* [n_chain] stages, 1..64                                   */
+  const int32_t* Lm;     /* [n_chain] layers of the pair's model, >= P_k              */
+  const int32_t* m;      /* [n_chain] micro-batches, >= 1                             */
+  const float* c;        /* [sum Lm][S]      c[lrow_k + l][s]                         */
+  const float* c_nosync; /* [sum Lm][S]      or NULL (then Cns = C)                   */
+  const float* R;        /* [sum Lm][S][S]   R[lrow_k + l][s_prev][s]; the slab of a
+                            stage's first layer is not used                          */
+  const int32_t* M;      /* [sum P*Lm][S]    M[mrow_k + i*Lm_k + l][s]: layer l under s
+                            when it belongs to stage i                               */
+  const int32_t* p0;     /* [sum P]          p0[prow_k + i] >= 1, summing to Lm_k     */
+  const int32_t* p_t;    /* [sum P] or NULL  the time-balanced partition              */
+  void* stream;          /* hipStream_t or NULL                                       */
+} gbmw_partition_problem;
+
+/* Outputs of gbmw_partition_search; HOST memory owned by the caller.  Pmax = max P_k,
+ * Lmmax = max Lm_k.  Entry j of pair k's trace is its j-th searched partition;
+ * entries j >= n_iter[k] and stage slots i >= P_k are left untouched.  Any pointer
+ * except n_iter may be NULL. */
+typedef struct {
+  int32_t* n_iter;   /* [n_chain]                    searches done (>= 1)             */
+  int32_t* O_t;      /* [n_chain]                    limit 3 (INT32_MAX: none)        */
+  int32_t* p;        /* [n_chain][max_iter][Pmax]    partition                        */
+  float* cost;       /* [n_chain][max_iter]          Eq. 8 (+inf: infeasible)         */
+  float* C;          /* [n_chain][max_iter][Pmax]    stage times (+inf: infeasible)   */
+  float* Cns;        /* [n_chain][max_iter][Pmax]                                     */
+  int32_t* O;        /* [n_chain][max_iter][Pmax]    stage memories (-1: infeasible)  */
+  float* alpha_t;    /* [n_chain][max_iter]                                           */
+  float* alpha_m;    /* [n_chain][max_iter]                                           */
+  uint8_t* strat;    /* [n_chain][Lmmax]  strategies of the last searched partition
+                        (0xFF: layer of an infeasible stage, or l >= Lm_k)           */
+  int32_t rounds;        /* out: lockstep rounds, the p_t round included              */
+  int32_t stage_solves;  /* out: stage instances solved over all rounds               */
+  int64_t cell_updates;  /* out: sum over them of (layers - 1) * (E + 1) * S * S      */
+  float device_ms;       /* out: first launch to last kernel, HIP events on `stream`  */
+} gbmw_partition_result;
+
+/*
+ * *ctx is in/out as for gbmw_dp_solve_batched: the context supplies the device
+ * buffers of the table solves and of the search state and can be handed to later
+ * calls of either kind; after the call it holds no solution.  Inputs are
+ * validated on the host first (GBMW_ERR_INVALID_ARG: NaN or negative c / c_nosync
+ * / R, negative M, a partition with an empty stage or the wrong sum, sizes out of
+ * range).
+ */
+gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, uint32_t flags,
+                                  gbmw_partition_result* out, gbmw_ctx** ctx);
 
 /* Lmax of the last solve (row length of `plan` above); 0 if none. */
 int32_t gbmw_max_layers(const gbmw_ctx* ctx);

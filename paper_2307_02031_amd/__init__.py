@@ -26,10 +26,12 @@ GBMW_PTR_HOST, GBMW_PTR_DEVICE = 0, 1
 GBMW_FLAG_KEEP_ALL_C = 1
 GBMW_FLAG_TIME_KERNELS = 2
 GBMW_FLAG_ONE_STREAM = 4
+GBMW_FLAG_RESOLVE_ALL = 8
 GBMW_MAX_S = 256
 
 EXPORTS = [
     "gbmw_dp_solve_batched", "gbmw_backtrack", "gbmw_select_forward_budget", "gbmw_pipeline_cost",
+    "gbmw_partition_search",
     "gbmw_max_layers", "gbmw_get_best",
     "gbmw_export_tables", "gbmw_synchronize", "gbmw_last_solve_ms", "gbmw_destroy",
     "gbmw_last_error", "gbmw_version",
@@ -40,6 +42,21 @@ class gbmw_problem(ct.Structure):
     _fields_ = [("B", ct.c_int32), ("S", ct.c_int32), ("E", ct.c_int32),
                 ("L", ct.c_void_p), ("c", ct.c_void_p), ("M", ct.c_void_p), ("R", ct.c_void_p),
                 ("ptr_space", ct.c_int32), ("stream", ct.c_void_p)]
+
+
+class gbmw_partition_problem(ct.Structure):
+    _fields_ = [("n_chain", ct.c_int32), ("S", ct.c_int32), ("E", ct.c_int32), ("max_iter", ct.c_int32),
+                ("P", ct.c_void_p), ("Lm", ct.c_void_p), ("m", ct.c_void_p), ("c", ct.c_void_p),
+                ("c_nosync", ct.c_void_p), ("R", ct.c_void_p), ("M", ct.c_void_p), ("p0", ct.c_void_p),
+                ("p_t", ct.c_void_p), ("stream", ct.c_void_p)]
+
+
+class gbmw_partition_result(ct.Structure):
+    _fields_ = [("n_iter", ct.c_void_p), ("O_t", ct.c_void_p), ("p", ct.c_void_p), ("cost", ct.c_void_p),
+                ("C", ct.c_void_p), ("Cns", ct.c_void_p), ("O", ct.c_void_p), ("alpha_t", ct.c_void_p),
+                ("alpha_m", ct.c_void_p), ("strat", ct.c_void_p),
+                ("rounds", ct.c_int32), ("stage_solves", ct.c_int32), ("cell_updates", ct.c_int64),
+                ("device_ms", ct.c_float)]
 
 
 class GbmwError(RuntimeError):
@@ -60,6 +77,9 @@ _lib.gbmw_select_forward_budget.argtypes = [ct.c_void_p] * 8
 _lib.gbmw_select_forward_budget.restype = ct.c_int
 _lib.gbmw_pipeline_cost.argtypes = [ct.c_void_p, ct.c_int32] + [ct.c_void_p] * 8
 _lib.gbmw_pipeline_cost.restype = ct.c_int
+_lib.gbmw_partition_search.argtypes = [ct.POINTER(gbmw_partition_problem), ct.c_uint32,
+                                       ct.POINTER(gbmw_partition_result), ct.POINTER(ct.c_void_p)]
+_lib.gbmw_partition_search.restype = ct.c_int
 _lib.gbmw_max_layers.argtypes = [ct.c_void_p]
 _lib.gbmw_max_layers.restype = ct.c_int32
 _lib.gbmw_get_best.argtypes = [ct.c_void_p, ct.c_void_p, ct.c_void_p]
@@ -207,6 +227,46 @@ def gbmw_pipeline_cost(ctx: Context, stage_begin, stage_instance, stage_e, micro
                                    mb.ctypes.data, None if cns is None else cns.ctypes.data,
                                    cost.ctypes.data, sc.ctypes.data, scn.ctypes.data))
     return cost, sc, scn
+
+
+def gbmw_partition_search(P, Lm, m, c, c_nosync, R, M, p0, p_t, S: int, E: int, max_iter: int = 64,
+                          flags: int = 0, ctx: Context | None = None, stream: int | None = None):
+    """Algorithm 2's inner loop for n_chain = len(P) pairs (host numpy arrays, the
+    pairs' rows concatenated; c_nosync and p_t may be None).  Returns (result dict,
+    ctx): n_iter, O_t [n]; p, C, Cns, O [n][max_iter][Pmax]; cost, alpha_t, alpha_m
+    [n][max_iter]; strat [n][Lmmax]; rounds, stage_solves, cell_updates, device_ms."""
+    i32 = lambda a: None if a is None else np.ascontiguousarray(a, dtype=np.int32)
+    f32 = lambda a: None if a is None else np.ascontiguousarray(a, dtype=np.float32)
+    P, Lm, m, M, p0, p_t = (i32(a) for a in (P, Lm, m, M, p0, p_t))
+    c, c_nosync, R = (f32(a) for a in (c, c_nosync, R))
+    n, sumLm, sumP = len(P), int(Lm.sum()), int(P.sum())
+    sumPL = int((P.astype(np.int64) * Lm).sum())
+    assert Lm.shape == m.shape == (n,) and c.shape == (sumLm, S) and R.shape == (sumLm, S, S)
+    assert M.shape == (sumPL, S) and p0.shape == (sumP,)
+    assert c_nosync is None or c_nosync.shape == c.shape
+    assert p_t is None or p_t.shape == p0.shape
+    Pmax, Lmmax = int(P.max()), int(Lm.max())
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else 0
+    ptr = lambda a: None if a is None else a.ctypes.data
+    q = gbmw_partition_problem(n, S, E, max_iter, ptr(P), ptr(Lm), ptr(m), ptr(c), ptr(c_nosync), ptr(R),
+                               ptr(M), ptr(p0), ptr(p_t), stream)
+    mi = max(1, max_iter)
+    res = dict(n_iter=np.zeros(n, np.int32), O_t=np.zeros(n, np.int32),
+               p=np.zeros((n, mi, Pmax), np.int32), cost=np.zeros((n, mi), np.float32),
+               C=np.zeros((n, mi, Pmax), np.float32), Cns=np.zeros((n, mi, Pmax), np.float32),
+               O=np.zeros((n, mi, Pmax), np.int32), alpha_t=np.zeros((n, mi), np.float32),
+               alpha_m=np.zeros((n, mi), np.float32), strat=np.zeros((n, Lmmax), np.uint8))
+    out = gbmw_partition_result(*[res[k].ctypes.data for k in ("n_iter", "O_t", "p", "cost", "C", "Cns", "O",
+                                                               "alpha_t", "alpha_m", "strat")], 0, 0, 0, 0.0)
+    if ctx is None:
+        ctx = Context()
+    _check(_lib.gbmw_partition_search(ct.byref(q), flags, ct.byref(out), ct.byref(ctx.handle)))
+    ctx.B = ctx.S = ctx.E = 0
+    ctx.L, ctx._keep = None, ()
+    res.update(rounds=out.rounds, stage_solves=out.stage_solves, cell_updates=out.cell_updates,
+               device_ms=out.device_ms)
+    return res, ctx
 
 
 def gbmw_export_tables(ctx: Context, instance: int, l0: int = 0, l1: int | None = None,

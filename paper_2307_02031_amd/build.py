@@ -8,8 +8,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgbmw.so")
-SOURCES = ["gbmw_kernels.hip", "gbmw_api.hip"]
-HEADERS = ["gbmw_kernels.h", os.path.join("..", "..", "include", "gbmw.h")]
+SOURCES = ["gbmw_kernels.hip", "gbmw_api.hip", "gbmw_partition.hip"]
+HEADERS = ["gbmw_kernels.h", "gbmw_ctx.h", os.path.join("..", "..", "include", "gbmw.h")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

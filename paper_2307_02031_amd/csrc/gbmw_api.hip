@@ -12,6 +12,7 @@
 #include <numeric>
 #include <vector>
 
+#include "gbmw_ctx.h"
 #include "gbmw_kernels.h"
 
 namespace {
@@ -22,6 +23,10 @@ thread_local char g_err[512] = "";
 // from overlapping one group's ramp-down with the other's launch saturates.
 constexpr int kGroups = 2;
 
+}  // namespace
+
+namespace gbmw_detail {
+
 gbmw_status fail(gbmw_status st, const char* fmt, ...) {
   va_list ap;
   va_start(ap, fmt);
@@ -30,53 +35,13 @@ gbmw_status fail(gbmw_status st, const char* fmt, ...) {
   return st;
 }
 
-#define HIP_TRY(expr)                                                                       \
-  do {                                                                                      \
-    hipError_t e_ = (expr);                                                                 \
-    if (e_ != hipSuccess) {                                                                 \
-      (void)hipGetLastError();                                                              \
-      return fail(e_ == hipErrorOutOfMemory ? GBMW_ERR_OOM : GBMW_ERR_DEVICE, "%s: %s",     \
-                  #expr, hipGetErrorString(e_));                                            \
-    }                                                                                       \
-  } while (0)
+void clear_error() { g_err[0] = 0; }
 
-struct DevBuf {
-  void* p = nullptr;
-  size_t cap = 0;
-  gbmw_status reserve(size_t bytes) {
-    if (bytes <= cap) return GBMW_OK;
-    if (p) { (void)hipFree(p); p = nullptr; cap = 0; }
-    if (bytes == 0) return GBMW_OK;
-    HIP_TRY(hipMalloc(&p, bytes));
-    cap = bytes;
-    return GBMW_OK;
-  }
-  void release() {
-    if (p) (void)hipFree(p);
-    p = nullptr;
-    cap = 0;
-  }
-};
+}  // namespace gbmw_detail
 
-}  // namespace
-
-struct gbmw_ctx {
-  int device = 0;
-  hipStream_t stream = nullptr;
-  bool solved = false;
-  bool index_on_device = false;   // d_L / d_off / d_perm hold this->L / off / perm
-  uint32_t flags = 0;
-  int B = 0, S = 0, SP = 0, E = 0, EP = 0, sumL = 0, Lmax = 0;
-  std::vector<int> L, off, perm;
-  gbmw::Tables t{};
-  DevBuf d_L, d_off, d_perm, d_c, d_M, d_R, d_Rt, d_C, d_A, d_best, d_best_s, d_status, d_q,
-      d_stage;
-  hipEvent_t ev0 = nullptr, ev1 = nullptr, ev_fork = nullptr;
-  std::vector<hipStream_t> aux;              // extra streams for instance groups
-  std::vector<hipEvent_t> ev_join;
-  std::vector<hipEvent_t> ev_layer;          // pairs around min-plus launches
-  int timed_launches = 0;
-};
+using gbmw_detail::DevBuf;
+using gbmw_detail::fail;
+using gbmw_detail::wait_and_check;
 
 namespace {
 
@@ -85,7 +50,8 @@ void free_ctx(gbmw_ctx* c) {
   (void)hipSetDevice(c->device);
   (void)hipStreamSynchronize(c->stream);
   for (DevBuf* b : {&c->d_L, &c->d_off, &c->d_perm, &c->d_c, &c->d_M, &c->d_R, &c->d_Rt, &c->d_C,
-                    &c->d_A, &c->d_best, &c->d_best_s, &c->d_status, &c->d_q, &c->d_stage})
+                    &c->d_A, &c->d_best, &c->d_best_s, &c->d_status, &c->d_q, &c->d_stage,
+                    &c->d_search, &c->d_gather})
     b->release();
   if (c->ev0) (void)hipEventDestroy(c->ev0);
   if (c->ev1) (void)hipEventDestroy(c->ev1);
@@ -110,6 +76,21 @@ gbmw_status check_host_values(const gbmw_problem* p, const std::vector<int>& L,
   return GBMW_OK;
 }
 
+}  // namespace
+
+namespace gbmw_detail {
+
+gbmw_status new_ctx(gbmw_ctx** out) {
+  gbmw_ctx* c = new (std::nothrow) gbmw_ctx();
+  if (!c) return fail(GBMW_ERR_OOM, "host allocation failed");
+  if (hipGetDevice(&c->device) != hipSuccess) {
+    delete c;
+    return fail(GBMW_ERR_DEVICE, "no HIP device available");
+  }
+  *out = c;
+  return GBMW_OK;
+}
+
 gbmw_status wait_and_check(gbmw_ctx* c) {
   if (!c) return fail(GBMW_ERR_INVALID_ARG, "null context");
   if (!c->solved) return fail(GBMW_ERR_INVALID_ARG, "context holds no solution");
@@ -125,7 +106,7 @@ gbmw_status wait_and_check(gbmw_ctx* c) {
   return GBMW_OK;
 }
 
-}  // namespace
+}  // namespace gbmw_detail
 
 extern "C" {
 
@@ -189,12 +170,8 @@ gbmw_status gbmw_dp_solve_batched(const gbmw_problem* p, uint32_t flags, gbmw_ct
   gbmw_ctx* c = *out;
   const bool fresh = (c == nullptr);
   if (fresh) {
-    c = new (std::nothrow) gbmw_ctx();
-    if (!c) return fail(GBMW_ERR_OOM, "host allocation failed");
-    if (hipGetDevice(&c->device) != hipSuccess) {
-      delete c;
-      return fail(GBMW_ERR_DEVICE, "no HIP device available");
-    }
+    gbmw_status st_new = gbmw_detail::new_ctx(&c);
+    if (st_new != GBMW_OK) return st_new;
   }
   c->solved = false;
 

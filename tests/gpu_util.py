@@ -75,3 +75,44 @@ def check_plans_by_definition(g, ctx, p: gi.Problem, b: int, q_es, best):
         v, m = oracle.plan_cost(p.c[o:o + Lb], p.M[o:o + Lb], p.R[o:o + Lb], plan[i, :Lb])
         assert pins.bits(v) == pins.bits(cost[i]), (p.name, b, e, v, cost[i])
         assert m == mem[i] and m <= e
+
+
+def pack_models(models):
+    """Concatenate PipelineModels (same S and E) into the arrays of one
+    gbmw_partition_search call."""
+    S, E = models[0].S, models[0].E
+    assert all(m.S == S and m.E == E for m in models)
+    have_pt = [m.p_t is not None for m in models]
+    assert all(have_pt) or not any(have_pt)
+    return dict(
+        P=np.array([m.P for m in models], np.int32), Lm=np.array([m.Lm for m in models], np.int32),
+        m=np.array([m.m for m in models], np.int32),
+        c=np.concatenate([m.c for m in models]), c_nosync=np.concatenate([m.c_ns for m in models]),
+        R=np.concatenate([m.R for m in models]),
+        M=np.concatenate([m.M.reshape(m.P * m.Lm, S) for m in models]),
+        p0=np.concatenate([m.p0 for m in models]),
+        p_t=np.concatenate([m.p_t for m in models]) if all(have_pt) else None, S=S, E=E)
+
+
+def check_partition_search(res, models, max_iter):
+    """The library's traces against the oracle's, pair by pair, bit for bit."""
+    import oracle.bmw as bmw
+    for k, mod in enumerate(models):
+        ref = bmw.partition_search(mod.as_dict(), mod.p0, mod.E, mod.m, p_t=mod.p_t, max_iter=max_iter)
+        what = f"{mod.name} (pair {k})"
+        n = len(ref["trace"])
+        assert int(res["n_iter"][k]) == n, (what, int(res["n_iter"][k]), [t["p"] for t in ref["trace"]])
+        assert int(res["O_t"][k]) == ref["O_t"], what
+        P = mod.P
+        for j, t in enumerate(ref["trace"]):
+            assert list(res["p"][k, j, :P]) == t["p"], (what, j)
+            assert pins.bits(res["cost"][k, j]) == pins.bits(t["cost"]), (what, j, res["cost"][k, j], t["cost"])
+            pins.assert_same_f32(res["C"][k, j, :P], t["C"], f"{what} C[{j}]")
+            pins.assert_same_f32(res["Cns"][k, j, :P], t["Cns"], f"{what} Cns[{j}]")
+            assert [int(x) for x in res["O"][k, j, :P]] == [int(x) for x in t["O"]], (what, j)
+            assert pins.bits(res["alpha_t"][k, j]) == pins.bits(t["alpha_t"]), (what, j)
+            assert pins.bits(res["alpha_m"][k, j]) == pins.bits(t["alpha_m"]), (what, j)
+        assert np.array_equal(res["strat"][k, :mod.Lm], ref["strat"]), what
+        assert np.all(res["strat"][k, mod.Lm:] == 255)
+        assert not res["p"][k, n:].any() and not res["cost"][k, n:].any()
+    return True

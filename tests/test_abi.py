@@ -100,3 +100,33 @@ def test_without_a_gpu_the_solve_fails_loudly():
     with pytest.raises(g.GbmwError) as ei:
         g.gbmw_dp_solve_batched([2], c, np.ones((2, 3), np.int32), np.zeros((2, 3, 3), np.float32), 3, 10)
     assert ei.value.status in (g.GBMW_ERR_DEVICE, g.GBMW_ERR_OOM)
+
+
+def test_partition_search_rejects_bad_arguments_before_touching_the_device():
+    import paper_2307_02031_amd as g
+    import gbmw_inputs as gi
+    mod = gi.uniform_pipeline_model(6, 2, 100, [2, 4], p_t=[3, 3])
+
+    def status(max_iter=8, flags=0, **over):
+        a = dict(P=[2], Lm=[6], m=[2], c=mod.c, c_nosync=mod.c_ns, R=mod.R, M=mod.M.reshape(12, 1),
+                 p0=mod.p0, p_t=mod.p_t, S=1, E=100)
+        a.update(over)
+        try:
+            g.gbmw_partition_search(a["P"], a["Lm"], a["m"], a["c"], a["c_nosync"], a["R"], a["M"], a["p0"],
+                                    a["p_t"], a["S"], a["E"], max_iter=max_iter, flags=flags)
+        except g.GbmwError as e:
+            return e.status, str(e)
+        return g.GBMW_OK, ""
+
+    for kw, word in [(dict(p0=np.array([2, 5])), "sums to"), (dict(p0=np.array([0, 6])), "empty"),
+                     (dict(p_t=np.array([6, 0])), "empty"), (dict(m=[0]), "m[0]"), (dict(E=-1), "E="),
+                     (dict(max_iter=0), "max_iter"), (dict(flags=1), "flag"),
+                     (dict(c=-mod.c), "c[0]"), (dict(c_nosync=mod.c_ns * np.nan), "c_nosync[0]"),
+                     (dict(M=-mod.M.reshape(12, 1)), "M[0]")]:
+        st, msg = status(**kw)
+        assert st == g.GBMW_ERR_INVALID_ARG and word in msg, (kw, st, msg)
+    badR = mod.R.copy(); badR[1, 0, 0] = -1.0
+    assert status(R=badR)[0] == g.GBMW_ERR_INVALID_ARG
+    st, msg = status(P=[7], M=np.ones((42, 1), np.int32), p0=np.ones(7, np.int32), p_t=None)   # more stages than layers
+    assert st == g.GBMW_ERR_INVALID_ARG and "Lm[0]" in msg
+    assert g._lib.gbmw_partition_search(None, 0, None, None) == g.GBMW_ERR_INVALID_ARG

@@ -1,0 +1,110 @@
+"""Algorithm 2's partition search on the GPU against the oracle (needs an MI355X)."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+import gbmw_inputs as gi
+import pins
+import pins_partition as pp
+from gpu_util import check_partition_search, pack_models
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def g():
+    import paper_2307_02031_amd as g
+    return g
+
+
+def _search(g, models, max_iter=64, flags=0, ctx=None):
+    a = pack_models(models)
+    return g.gbmw_partition_search(a["P"], a["Lm"], a["m"], a["c"], a["c_nosync"], a["R"], a["M"], a["p0"],
+                                   a["p_t"], a["S"], a["E"], max_iter=max_iter, flags=flags, ctx=ctx)
+
+
+def test_worked_example(g):
+    """The hand-worked cases, straight against the fixture's numbers."""
+    with open(os.path.join(pins.GOLDEN, "worked_example_partition.json")) as f:
+        gold = json.load(f)
+    for case in gold["cases"]:
+        model, m = pp.fixture_model(gold, case)
+        P, Lm = model["M"].shape[0], model["c"].shape[0]
+        res, ctx = g.gbmw_partition_search([P], [Lm], [m], model["c"], model["c_ns"], model["R"],
+                                           model["M"].reshape(P * Lm, -1), case["p0"], case["p_t"],
+                                           model["c"].shape[1], case["E"], max_iter=16)
+        n = int(res["n_iter"][0])
+        got = dict(O_t=int(res["O_t"][0]), strat=res["strat"][0],
+                   trace=[dict(p=list(res["p"][0, j]), cost=res["cost"][0, j], C=res["C"][0, j],
+                               Cns=res["Cns"][0, j], O=res["O"][0, j], alpha_t=res["alpha_t"][0, j],
+                               alpha_m=res["alpha_m"][0, j]) for j in range(n)])
+        pp.check_trace_against(case, got)
+        g.gbmw_destroy(ctx)
+
+
+@pytest.mark.parametrize("flags", [0, 8], ids=["changed-stages", "resolve-all"])
+def test_uniform_models(g, flags):
+    """Closed-form models (S = 1): neighbour choice, ties, the searched-before
+    rule, memory limits, an infeasible start, single-stage and one-layer-per-stage
+    pairs -- all in one lockstep call."""
+    models = [gi.uniform_pipeline_model(Lm, 2, 1000, [1, Lm - 1], m=3) for Lm in (6, 7, 10, 11)]
+    models += [gi.uniform_pipeline_model(10, 3, 1000, p0) for p0 in ([2, 6, 2], [7, 2, 1], [4, 2, 4])]
+    models += [gi.uniform_pipeline_model(5, 1, 1000, [5]), gi.uniform_pipeline_model(3, 3, 1000, [1, 1, 1])]
+    res, ctx = _search(g, models, flags=flags)
+    check_partition_search(res, models, 64)
+    assert [list(x) for x in res["p"][4, :4]] == [[2, 6, 2], [3, 5, 2], [3, 4, 3], [4, 3, 3]]
+    for p_t in (None, [2, 8], [5, 5]):
+        lim = [gi.uniform_pipeline_model(10, 2, 9, p0, mem=[3, 1], p_t=p_t) for p0 in ([1, 9], [4, 6])]
+        res, ctx = _search(g, lim, flags=flags, ctx=ctx)
+        check_partition_search(res, lim, 64)
+    res, ctx = _search(g, models, max_iter=2, flags=flags, ctx=ctx)
+    check_partition_search(res, models, 2)
+    assert res["n_iter"].max() == 2
+    g.gbmw_destroy(ctx)
+
+
+@pytest.mark.parametrize("flags", [0, 8], ids=["changed-stages", "resolve-all"])
+@pytest.mark.parametrize("S,E,with_pt", [(3, 60, True), (5, 90, False), (22, 400, True), (44, 700, True),
+                                         (70, 500, False)])
+def test_random_models(g, S, E, with_pt, flags):
+    """Pairs of different depth and PP degree searched in lockstep."""
+    st = gi.Stream(8100 + S)
+    models = []
+    for k in range(9):
+        P = int(st.integers(1, 1, 6)[0])
+        Lm = int(st.integers(1, P, P + 14)[0])
+        models.append(gi.random_pipeline_model(9000 + 31 * S + k, Lm, S, P, E, m=int(st.integers(1, 1, 9)[0]),
+                                               M_rng=(1, max(2, E // 24)), R_rng=(0.0, 0.5), with_pt=with_pt,
+                                               skew=(k % 2 == 0)))
+    res, ctx = _search(g, models, max_iter=24, flags=flags)
+    check_partition_search(res, models, 24)
+    assert res["n_iter"].max() > 2, "the models must exercise the adjustment"
+    assert res["stage_solves"] >= sum(m.P for m in models)
+    g.gbmw_destroy(ctx)
+
+
+def test_changed_stage_reuse_solves_less_and_agrees(g):
+    models = [gi.random_pipeline_model(9500 + k, 24, 22, 4, 600, M_rng=(1, 40)) for k in range(6)]
+    a, ctx = _search(g, models, max_iter=32)
+    b, ctx = _search(g, models, max_iter=32, flags=g.GBMW_FLAG_RESOLVE_ALL, ctx=ctx)
+    for key in ("n_iter", "O_t", "p", "cost", "C", "Cns", "O", "alpha_t", "alpha_m", "strat"):
+        assert np.array_equal(a[key].view(np.uint8), b[key].view(np.uint8)), key
+    assert a["rounds"] == b["rounds"] and a["n_iter"].max() > 2
+    assert a["stage_solves"] < b["stage_solves"] and a["cell_updates"] < b["cell_updates"]
+    # the context goes on to serve an ordinary solve
+    p = gi.make_config(1)
+    ctx = g.gbmw_dp_solve_batched(p.L, p.c, p.M, p.R, p.S, p.E, ctx=ctx)
+    best, _ = g.gbmw_get_best(ctx)
+    assert np.isfinite(best[0, -1])
+    g.gbmw_destroy(ctx)
+
+
+def test_structured_models(g):
+    """Paper-shaped pairs: 44 strategies, 24-32 layers, PP degrees 2, 4 and 8."""
+    models = [gi.structured_pipeline_model(70 + k, Lm, P, 3072, m=8)
+              for k, (Lm, P) in enumerate([(24, 2), (24, 4), (32, 4), (32, 8)])]
+    res, ctx = _search(g, models, max_iter=12)
+    check_partition_search(res, models, 12)
+    g.gbmw_destroy(ctx)
