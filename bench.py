@@ -83,6 +83,62 @@ def cpu_baseline(p, budget_s=12.0):
                       f"OpenMP over budget rows"}
 
 
+def partition_workload(gi):
+    """16 (batch size, PP degree) pairs of a 48-layer, 44-strategy model: batch
+    sizes scale the activation memory (x0.5, x1, x2, x4), PP degrees 2, 4, 8, 16."""
+    models = []
+    for q, act in enumerate((0.5, 1.0, 2.0, 4.0)):
+        for P in (2, 4, 8, 16):
+            models.append(gi.structured_pipeline_model(500 + q, 48, P, 32768, m=8, act_scale=act,
+                                                       name=f"bmw48 act x{act} P={P}"))
+    return models
+
+
+def partition_leg(g, gi, cpu: bool, budget_s=10.0):
+    """Algorithm 2's partition loop through gbmw_partition_search, host to host
+    (model upload, every round's batched solve of the changed stages, trace
+    download), with a reused context; the same with every stage re-solved in
+    every round; and the oracle on the first pairs."""
+    import numpy as np
+    models = partition_workload(gi)
+    S, E = models[0].S, models[0].E
+    a = dict(P=np.array([m.P for m in models], np.int32), Lm=np.array([m.Lm for m in models], np.int32),
+             m=np.array([m.m for m in models], np.int32), c=np.concatenate([m.c for m in models]),
+             cns=np.concatenate([m.c_ns for m in models]), R=np.concatenate([m.R for m in models]),
+             M=np.concatenate([m.M.reshape(m.P * m.Lm, S) for m in models]),
+             p0=np.concatenate([m.p0 for m in models]), p_t=np.concatenate([m.p_t for m in models]))
+    out = {"workload": "16 pairs: 48 layers, S=44, E=32768, PP 2/4/8/16 x 4 activation scales, max_iter 32"}
+    ctx = None
+    for name, flags in (("changed_stages", 0), ("resolve_all", g.GBMW_FLAG_RESOLVE_ALL)):
+        best = None
+        for _ in range(3):
+            t0 = time.perf_counter()
+            res, ctx = g.gbmw_partition_search(a["P"], a["Lm"], a["m"], a["c"], a["cns"], a["R"], a["M"], a["p0"],
+                                               a["p_t"], S, E, max_iter=32, flags=flags, ctx=ctx)
+            dt = time.perf_counter() - t0
+            best = dt if best is None else min(best, dt)
+        out[name] = {"ms": best * 1e3, "device_ms": res["device_ms"], "rounds": res["rounds"],
+                     "stage_solves": res["stage_solves"], "cell_updates": int(res["cell_updates"]),
+                     "cell_updates_per_s": res["cell_updates"] / best,
+                     "searched_partitions": int(res["n_iter"].sum())}
+    g.gbmw_destroy(ctx)
+    if cpu:
+        import oracle.bmw as bmw
+        t_used, n, upd = 0.0, 0, 0
+        for mod in models:
+            t0 = time.perf_counter()
+            ref = bmw.partition_search(mod.as_dict(), mod.p0, mod.E, mod.m, p_t=mod.p_t, max_iter=32)
+            t_used += time.perf_counter() - t0
+            n += 1
+            upd += (len(ref["trace"]) + 1) * (mod.Lm - mod.P) * (E + 1) * S * S
+            if t_used > budget_s:
+                break
+        out["cpu_oracle"] = {"ms_per_pair": t_used / n * 1e3, "pairs": n, "cores": 1,
+                             "cell_updates_per_s": upd / t_used,
+                             "note": "plain Python over the C oracle, every stage solved in every round"}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -97,6 +153,9 @@ def main():
                          "(a kernel of known traffic against which HBM byte counters are scaled)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other configs")
+    ap.add_argument("--no-partition", action="store_true", help="skip the partition-search leg (Algorithm 2)")
+    ap.add_argument("--only-partition", action="store_true",
+                    help="run the partition-search leg alone and print it (for profiling that leg)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; the search shards by instance with no "
@@ -121,6 +180,10 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": True, "bytes_read_per_copy": 4 * n,
                           "bytes_written_per_copy": 4 * n, "copies": 5}), flush=True)
+        return
+
+    if args.only_partition:
+        print(json.dumps({"partition_search": partition_leg(g, gi, cpu=not args.no_cpu_baseline)}), flush=True)
         return
 
     p = gi.make_config(args.config)
@@ -215,6 +278,9 @@ def main():
             g.gbmw_destroy(c2)
             del dq
         out["other_configs"] = others
+
+    if not args.no_partition:
+        out["partition_search"] = partition_leg(g, gi, cpu=not args.no_cpu_baseline)
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(p)

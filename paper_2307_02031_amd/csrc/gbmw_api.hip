@@ -118,6 +118,13 @@ const char* gbmw_version(void) {
 
 gbmw_status gbmw_dp_solve_batched(const gbmw_problem* p, uint32_t flags, gbmw_ctx** out) {
   g_err[0] = 0;
+  return gbmw_detail::solve_batched(p, flags, out, 0);
+}
+
+}  // extern "C"
+
+gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gbmw_ctx** out,
+                                       int final_from) {
   if (!p || !out) return fail(GBMW_ERR_INVALID_ARG, "null problem or context pointer");
   if (!p->L || !p->c || !p->M || !p->R) return fail(GBMW_ERR_INVALID_ARG, "null L/c/M/R");
   if (p->B < 1 || p->B > 65535) return fail(GBMW_ERR_INVALID_ARG, "B=%d not in 1..65535", p->B);
@@ -248,6 +255,7 @@ gbmw_status gbmw_dp_solve_batched(const gbmw_problem* p, uint32_t flags, gbmw_ct
 
   gbmw::Tables& t = c->t;
   t.B = B; t.S = S; t.SP = SP; t.RS = RS; t.E = E; t.EP = EP; t.keep_all = keep ? 1 : 0;
+  t.final_from = std::min(std::max(final_from, 0), E);
   t.L = (const int*)c->d_L.p; t.off = (const int*)c->d_off.p; t.perm = (const int*)c->d_perm.p;
   t.c = dc; t.M = dM; t.Rt = (const float*)c->d_Rt.p;
   t.Cbuf = (float*)c->d_C.p; t.A = (uint8_t*)c->d_A.p;
@@ -276,10 +284,18 @@ gbmw_status gbmw_dp_solve_batched(const gbmw_problem* p, uint32_t flags, gbmw_ct
   HIP_TRY_B(hipEventRecord(c->ev0, st));
   gbmw::launch_prepare(t, dR, sumL, p->ptr_space == GBMW_PTR_DEVICE, st);
   {
-    // Layer 0 goes to memory only where something reads it from there.
+    // Layer 0 goes to memory only where something reads it from there.  Inside a
+    // group the instances are ordered by L descending, so the short ones are a suffix.
     const bool all = keep || !gbmw::layer0_in_registers(S);
-    const bool some = std::any_of(L.begin(), L.end(), [](int x) { return x <= 2; });
-    if (all || some) gbmw::launch_init_layer0(t, !all, st);
+    if (all) {
+      gbmw::launch_init_layer0(t, 0, B, st);
+    } else {
+      for (int g = 0; g < G; ++g) {
+        int n_short = 0;
+        for (int i = gfirst[g + 1] - 1; i >= gfirst[g] && L[perm[i]] <= 2; --i) ++n_short;
+        gbmw::launch_init_layer0(t, gfirst[g + 1] - n_short, n_short, st);
+      }
+    }
   }
   if (G > 1) HIP_TRY_B(hipEventRecord(c->ev_fork, st));
   for (int g = 0; g < G; ++g) {
@@ -309,6 +325,8 @@ gbmw_status gbmw_dp_solve_batched(const gbmw_problem* p, uint32_t flags, gbmw_ct
   *out = c;
   return GBMW_OK;
 }
+
+extern "C" {
 
 gbmw_status gbmw_synchronize(gbmw_ctx* ctx) {
   g_err[0] = 0;

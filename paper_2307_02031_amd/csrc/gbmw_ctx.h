@@ -42,6 +42,10 @@ struct DevBuf {
   }
 };
 
+// gbmw_dp_solve_batched with one more knob: best / best_s are produced for budgets
+// e >= final_from only (0: all of them; E: just the full budget).
+gbmw_status solve_batched(const gbmw_problem* p, uint32_t flags, gbmw_ctx** ctx, int final_from);
+
 // A new, empty context on the current device.
 gbmw_status new_ctx(gbmw_ctx** out);
 

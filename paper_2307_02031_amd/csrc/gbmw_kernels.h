@@ -22,6 +22,7 @@ namespace gbmw {
 struct Tables {
   int B, S, SP, RS, E, EP;
   int keep_all;        // 1: Call[row][S][EP] for every layer row; 0: rolling pair
+  int final_from;      // the final reduce fills best / best_s for e >= final_from only
   const int* L;        // [B]   device
   const int* off;      // [B]   device, first row of each instance
   const int* perm;     // [B]   device, instances ordered by L descending
@@ -37,16 +38,18 @@ struct Tables {
 
 // R -> Rt (transpose + pad) and validation of device-resident inputs.
 void launch_prepare(const Tables& t, const float* R, int sumL, bool validate, hipStream_t st);
-// C(0, e, s) written to the table: for every instance, or (only_short) only for
-// instances with L_b <= 2, whose layer 0 is read by the final reduce / export.
-void launch_init_layer0(const Tables& t, bool only_short, hipStream_t st);
+// C(0, e, s) written to the table for instances perm[first .. first + count).  Needed
+// where something reads layer 0 from memory: instances with L_b <= 2 (final reduce,
+// export), every instance when all layers are kept or S > 64.
+void launch_init_layer0(const Tables& t, int first, int count, hipStream_t st);
 // True when the layer-1 launch builds layer 0 in registers and does not read it.
 bool layer0_in_registers(int S);
 // One layer l >= 1 for instances perm[first .. first + n_active):
 // min-plus product with argmin, fused with the shift by M(l,s), the + c(l,s)
 // and the +inf prefix.
 void launch_minplus(const Tables& t, int l, int first, int n_active, hipStream_t st);
-// best(e), best_s(e) over the last layer of instances perm[first .. first + count).
+// best(e), best_s(e) for e = final_from .. E over the last layer of instances
+// perm[first .. first + count).
 void launch_final(const Tables& t, int first, int count, hipStream_t st);
 // Plans for nq queries (all pointers device).
 void launch_backtrack(const Tables& t, int nq, const int* q_inst, const int* q_e, int Lmax,

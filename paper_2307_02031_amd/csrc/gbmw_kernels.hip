@@ -89,9 +89,8 @@ void launch_prepare(const Tables& t, const float* R, int sumL, bool validate, hi
 // ---------------------------------------------------------------------------
 // layer 0:  C(0, e, s) = e >= M(0, s) ? c(0, s) : +inf
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_init_layer0(Tables t, int only_short) {
-  const int inst = blockIdx.z, s = blockIdx.y;
-  if (only_short && t.L[inst] > 2) return;   // layer 1 rebuilds layer 0 in registers
+__global__ __launch_bounds__(256) void k_init_layer0(Tables t, int first) {
+  const int inst = t.perm[first + blockIdx.z], s = blockIdx.y;
   const int e = blockIdx.x * 256 + threadIdx.x;           // EP is a multiple of 256
   const int row = t.off[inst];
   const int m = t.M[(size_t)row * t.S + s];
@@ -100,9 +99,9 @@ __global__ __launch_bounds__(256) void k_init_layer0(Tables t, int only_short) {
   C0[(size_t)s * t.EP + e] = (m >= 0 && e >= m && e <= t.E) ? cs : INFINITY;   // padding rows: +inf
 }
 
-void launch_init_layer0(const Tables& t, bool only_short, hipStream_t st) {
-  hipLaunchKernelGGL(k_init_layer0, dim3(t.EP / 256, t.S, t.B), dim3(256), 0, st, t,
-                     only_short ? 1 : 0);
+void launch_init_layer0(const Tables& t, int first, int count, hipStream_t st) {
+  if (count <= 0) return;
+  hipLaunchKernelGGL(k_init_layer0, dim3(t.EP / 256, t.S, count), dim3(256), 0, st, t, first);
 }
 
 // ---------------------------------------------------------------------------
@@ -385,7 +384,7 @@ const char* minplus_variant(int S) {
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_final(Tables t, int first) {
   const int inst = t.perm[first + blockIdx.y];
-  const int e = blockIdx.x * 256 + threadIdx.x;
+  const int e = t.final_from + blockIdx.x * 256 + threadIdx.x;
   if (e > t.E) return;
   const int l = t.L[inst] - 1;
   const float* __restrict__ C = c_table(t, inst, t.off[inst] + l, l);
@@ -401,7 +400,7 @@ __global__ __launch_bounds__(256) void k_final(Tables t, int first) {
 
 void launch_final(const Tables& t, int first, int count, hipStream_t st) {
   if (count <= 0) return;
-  hipLaunchKernelGGL(k_final, dim3((t.E + 256) / 256, count), dim3(256), 0, st, t, first);
+  hipLaunchKernelGGL(k_final, dim3((t.E - t.final_from + 256) / 256, count), dim3(256), 0, st, t, first);
 }
 
 // ---------------------------------------------------------------------------

@@ -462,7 +462,7 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
     pr.B = nb; pr.S = S; pr.E = E; pr.L = h_L.data();
     pr.c = gc; pr.M = gM; pr.R = gR; pr.ptr_space = GBMW_PTR_DEVICE; pr.stream = st;
     gbmw_ctx* cc = c;
-    gbmw_status rs = gbmw_dp_solve_batched(&pr, 0, &cc);
+    gbmw_status rs = gbmw_detail::solve_batched(&pr, 0, &cc, E);   // only best(E) is read
     if (rs != GBMW_OK) return rs;
     c->solved = false;                                 // the tables are an intermediate of this call
     hipLaunchKernelGGL(gbmw::k_stage_result, dim3((nb + 63) / 64), dim3(64), 0, st, c->t, s, g_chain,
