@@ -27,7 +27,7 @@ import numpy as np
 __all__ = [
     "Problem", "Stream", "make_config", "random_instance", "stack", "split_memory",
     "CONFIG_NAMES", "PipelineModel", "random_pipeline_model", "structured_pipeline_model",
-    "uniform_pipeline_model", "proportional_partition",
+    "uniform_pipeline_model", "proportional_partition", "TABLE1", "table1_layers", "default_hardware",
 ]
 
 _MASK = np.uint64(0xFFFFFFFFFFFFFFFF)
@@ -368,3 +368,39 @@ def uniform_pipeline_model(Lm: int, P: int, E: int, p0, cost: float = 2.0, r: fl
     R = np.full((Lm, 1, 1), r, np.float32)
     M = np.array([[[mem[i]]] * Lm for i in range(P)], np.int32)
     return PipelineModel(1, E, P, m, c, c * np.float32(0.5), R, M, np.array(p0), p_t, "pipe-uniform")
+
+
+# --------------------------------------------------------------------------
+# Layer shapes for the analytic cost model: rows of the paper's model table
+# (Table 1: layers, hidden size, parameters, activation bytes per sample), cut
+# into equal layers.  Shapes only: the cost model itself lives elsewhere.
+# --------------------------------------------------------------------------
+TABLE1 = {
+    # name: (layers, hidden, parameters, activation MB per sample, tokens per sample)
+    "BERT-Huge-32": (32, 1280, 672e6, 3149.39, 512),
+    "BERT-Huge-48": (48, 1280, 987e6, 4657.51, 512),
+    "BERT-xHuge": (128, 2560, 10.2e9, 24210.05, 512),
+    "ViT-Huge-32": (32, 1280, 632e6, 646.5, 197),
+    "GPT3-15B": (48, 5120, 15.4e9, 32889.04, 2048),
+}
+
+
+def table1_layers(name: str) -> np.ndarray:
+    """float64 [L][4]: parameters, forward FLOPs per sample, boundary and
+    intermediate activation bytes per sample of each layer.  A layer holds
+    1/L of the parameters and of the activations; forward FLOPs = 2 x parameters
+    x tokens; the boundary activation is tokens x hidden x 2 bytes."""
+    L, hidden, params, act_mb, tokens = TABLE1[name]
+    p = params / L
+    act = act_mb * 2.0 ** 20 / L
+    bnd = float(tokens * hidden * 2)
+    assert bnd < act
+    row = [p, 2.0 * p * tokens, bnd, act - bnd]
+    return np.ascontiguousarray(np.tile(np.array(row, np.float64), (L, 1)))
+
+
+def default_hardware(unit_mb: float = 8.0) -> dict:
+    """A100-class node of 8 devices in NVLink islands of 8, as in the paper's
+    testbed description: numbers are round figures, not measurements."""
+    return dict(rate=150e12, bw_in=150e9, bw_out=12.5e9, param_bytes=2.0, state_bytes=16.0, slow=1.3,
+                unit_bytes=unit_mb * 2.0 ** 20, island=8)

@@ -265,6 +265,100 @@ typedef struct {
 gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, uint32_t flags,
                                   gbmw_partition_result* out, gbmw_ctx** ctx);
 
+/*
+ * Candidate hybrid-parallelism strategies of one layer on a device group of
+ * `group_size` devices (Section 3.2): every decision tree whose levels are
+ * distinct paradigms out of DP, SDP and TP (at most three levels), each with a
+ * degree from {2, 4, 8, ...}, the degrees multiplying to group_size; the order
+ * of the levels matters (level 0 is the outermost, i.e. spans the slowest
+ * links).  takeaway3 != 0 drops the trees that hold both DP and SDP; with_ckpt
+ * != 0 lists every tree twice, first all without, then all with activation
+ * checkpointing.  For 8 devices and PP degrees 1/2/4/8 (groups of 8/4/2/1) this
+ * gives 21+9+3+1 = 34 trees, 68 with CKPT, and 11+7+3+1 = 22, 44 with CKPT,
+ * after Takeaway #3.
+ * Order: fewer levels first, then the degree tuples in lexicographic order, then
+ * the paradigm tuples in lexicographic order with DP < SDP < TP.
+ * Host-only routine (no device work).  Returns the number of strategies, writing
+ * at most `cap` of them to `out` (out may be NULL to ask for the count);
+ * -1 if group_size is not a power of two in 1..2^20.
+ */
+enum { GBMW_DP = 1, GBMW_SDP = 2, GBMW_TP = 3 };
+typedef struct {
+  int32_t n_levels;   /* 0..3                                   */
+  int32_t kind[3];    /* GBMW_DP / GBMW_SDP / GBMW_TP, outer first; 0 beyond n_levels */
+  int32_t degree[3];  /* 2, 4, 8, ...; 0 beyond n_levels        */
+  int32_t ckpt;       /* 1: activation checkpointing            */
+} gbmw_strategy;
+
+int32_t gbmw_enumerate_strategies(int32_t group_size, int32_t with_ckpt, int32_t takeaway3,
+                                  gbmw_strategy* out, int32_t cap);
+
+/*
+ * A small analytic cost model in the spirit of Section 5 that turns layer
+ * shapes into the inputs of the search, evaluated on the device for every
+ * (layer, strategy) and (layer, strategy pair).  Fixed by the paper: backward
+ * computation is twice the forward; all-reduce moves 2(N-1)/N and SDP 3(N-1)/N
+ * of the parameter bytes (Takeaway #3); CKPT adds one forward pass (with TP's
+ * all-reduce) to the backward step, keeps only the boundary activations in the
+ * forward pass and needs the intermediate ones during backward (Section 3.1);
+ * computation and communication that overlap slow each other down by `slow`
+ * (1.3 in Section 5); O_f / O_b / O_ms as in Eq. 2.  The rest is this library's
+ * modelling choice, stated here in full.  With dp, sdp, tp the degrees of the
+ * strategy (1 if absent), span_x = degree_x times the degrees of the levels
+ * inside level x, bw(span) = span <= island ? bw_in : bw_out, all in fp64 and in
+ * exactly this order of operations:
+ *   lb     = Bm / (dp * sdp)                           samples per device
+ *   t_f    = lb * flops / tp / rate
+ *   tp_ar  = tp > 1 ? 2 (tp-1) / tp * (lb * bnd) / bw(span_tp) : 0
+ *   pbytes = params * param_bytes / tp
+ *   sdp_ag = sdp > 1 ? (sdp-1) / sdp * pbytes / bw(span_sdp) : 0
+ *   dp_ar  = dp > 1 ? 2 (dp-1) / dp * pbytes / bw(span_dp) : 0
+ *   fwd    = t_f + tp_ar + sdp_ag
+ *   bwd    = 2 t_f + tp_ar, plus (t_f + tp_ar) under CKPT
+ *   ov(a,b) = slow * min(a,b) + (max(a,b) - min(a,b))
+ *   c      = fwd + ov(bwd, sdp_ag + (dp_ar + sdp_ag))   c_nosync = fwd + ov(bwd, sdp_ag)
+ *   ms     = params * state_bytes / (tp * sdp)
+ *   act_f  = CKPT ? lb * bnd : lb * (bnd + intm / tp);  act_b = CKPT ? lb * (intm / tp) : 0
+ *   O_ms, O_f, O_b = ceil(ms | act_f | act_b / unit_bytes)
+ *   M[i]   = O_ms + (P - i) * O_f     stage i of a 1F1B pipeline keeps P - i micro-batches
+ *   R(l, s', s) = 0 if the two strategies lay the activations out alike (same
+ *            sequence of levels with DP and SDP both counted as batch splits), else
+ *            Bm * bnd(l-1) * share / bw_out with b = dp * sdp, share = |1/b - 1/b'| if
+ *            b != b' else 1/b; the l == 0 slab is zero.
+ * c, c_nosync, R are rounded to fp32 at the end.
+ * layers, strategies, hw: HOST pointers.  Outputs: all HOST (out_space ==
+ * GBMW_PTR_HOST) or all DEVICE pointers (GBMW_PTR_DEVICE; filled in place, ready to
+ * be handed to gbmw_dp_solve_batched); any may be NULL.  The kernels run on `stream`
+ * and the call returns when they have finished (it reads back their range check).  Shapes: c, c_nosync [L][S] fp32; O_f, O_b,
+ * O_ms [L][S] int32; M [P][L][S] int32; R [L][S][S] fp32.
+ * GBMW_ERR_INVALID_ARG: sizes out of range, a strategy that breaks the rules
+ * above, non-positive rate / bandwidth / unit, negative shapes, or a memory that
+ * does not fit int32.
+ */
+typedef struct {
+  double params; /* parameter count                         */
+  double flops;  /* forward FLOPs per sample                */
+  double bnd;    /* boundary activation bytes per sample    */
+  double intm;   /* intermediate activation bytes per sample */
+} gbmw_layer_shape;
+
+typedef struct {
+  double rate;        /* device FLOP/s                                      */
+  double bw_in;       /* bytes/s inside an island                           */
+  double bw_out;      /* bytes/s across islands                             */
+  double param_bytes; /* bytes per parameter on the wire                    */
+  double state_bytes; /* bytes of model state per parameter (weights, gradients, optimizer) */
+  double slow;        /* slowdown of overlapped compute / communication, >= 1 */
+  double unit_bytes;  /* bytes per memory unit of the search's budget axis  */
+  int32_t island;     /* devices per island                                 */
+} gbmw_hardware;
+
+gbmw_status gbmw_cost_model(const gbmw_layer_shape* layers, int32_t L,
+                            const gbmw_strategy* strategies, int32_t S, const gbmw_hardware* hw,
+                            double Bm, int32_t P, int32_t out_space, float* c, float* c_nosync,
+                            int32_t* O_f, int32_t* O_b, int32_t* O_ms, int32_t* M, float* R,
+                            void* stream);
+
 /* Lmax of the last solve (row length of `plan` above); 0 if none. */
 int32_t gbmw_max_layers(const gbmw_ctx* ctx);
 

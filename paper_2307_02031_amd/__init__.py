@@ -31,7 +31,7 @@ GBMW_MAX_S = 256
 
 EXPORTS = [
     "gbmw_dp_solve_batched", "gbmw_backtrack", "gbmw_select_forward_budget", "gbmw_pipeline_cost",
-    "gbmw_partition_search",
+    "gbmw_partition_search", "gbmw_enumerate_strategies", "gbmw_cost_model",
     "gbmw_max_layers", "gbmw_get_best",
     "gbmw_export_tables", "gbmw_synchronize", "gbmw_last_solve_ms", "gbmw_destroy",
     "gbmw_last_error", "gbmw_version",
@@ -59,6 +59,20 @@ class gbmw_partition_result(ct.Structure):
                 ("device_ms", ct.c_float)]
 
 
+class gbmw_strategy(ct.Structure):
+    _fields_ = [("n_levels", ct.c_int32), ("kind", ct.c_int32 * 3), ("degree", ct.c_int32 * 3), ("ckpt", ct.c_int32)]
+
+
+class gbmw_hardware(ct.Structure):
+    _fields_ = [("rate", ct.c_double), ("bw_in", ct.c_double), ("bw_out", ct.c_double),
+                ("param_bytes", ct.c_double), ("state_bytes", ct.c_double), ("slow", ct.c_double),
+                ("unit_bytes", ct.c_double), ("island", ct.c_int32)]
+
+
+STRATEGY_DTYPE = np.dtype([("n_levels", np.int32), ("kind", np.int32, 3), ("degree", np.int32, 3), ("ckpt", np.int32)])
+GBMW_DP, GBMW_SDP, GBMW_TP = 1, 2, 3
+
+
 class GbmwError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__(f"gbmw status {status}: {message}")
@@ -80,6 +94,11 @@ _lib.gbmw_pipeline_cost.restype = ct.c_int
 _lib.gbmw_partition_search.argtypes = [ct.POINTER(gbmw_partition_problem), ct.c_uint32,
                                        ct.POINTER(gbmw_partition_result), ct.POINTER(ct.c_void_p)]
 _lib.gbmw_partition_search.restype = ct.c_int
+_lib.gbmw_enumerate_strategies.argtypes = [ct.c_int32, ct.c_int32, ct.c_int32, ct.c_void_p, ct.c_int32]
+_lib.gbmw_enumerate_strategies.restype = ct.c_int32
+_lib.gbmw_cost_model.argtypes = [ct.c_void_p, ct.c_int32, ct.c_void_p, ct.c_int32, ct.POINTER(gbmw_hardware),
+                                 ct.c_double, ct.c_int32, ct.c_int32] + [ct.c_void_p] * 8
+_lib.gbmw_cost_model.restype = ct.c_int
 _lib.gbmw_max_layers.argtypes = [ct.c_void_p]
 _lib.gbmw_max_layers.restype = ct.c_int32
 _lib.gbmw_get_best.argtypes = [ct.c_void_p, ct.c_void_p, ct.c_void_p]
@@ -267,6 +286,43 @@ def gbmw_partition_search(P, Lm, m, c, c_nosync, R, M, p0, p_t, S: int, E: int, 
     res.update(rounds=out.rounds, stage_solves=out.stage_solves, cell_updates=out.cell_updates,
                device_ms=out.device_ms)
     return res, ctx
+
+
+def gbmw_enumerate_strategies(group_size: int, with_ckpt: bool = True, takeaway3: bool = True) -> np.ndarray:
+    """Structured array (STRATEGY_DTYPE) of the candidate strategies of one layer."""
+    n = _lib.gbmw_enumerate_strategies(group_size, int(with_ckpt), int(takeaway3), None, 0)
+    if n < 0:
+        raise GbmwError(GBMW_ERR_INVALID_ARG, gbmw_last_error())
+    out = np.zeros(n, STRATEGY_DTYPE)
+    assert STRATEGY_DTYPE.itemsize == ct.sizeof(gbmw_strategy)
+    _lib.gbmw_enumerate_strategies(group_size, int(with_ckpt), int(takeaway3), out.ctypes.data, n)
+    return out
+
+
+def gbmw_cost_model(layers, strategies, hw: dict, Bm: float, P: int, device: bool = False,
+                    stream: int | None = None) -> dict:
+    """c, c_nosync [L][S] f32; O_f, O_b, O_ms [L][S] i32; M [P][L][S] i32; R [L][S][S] f32 --
+    numpy arrays, or torch CUDA tensors if ``device``.  layers: float64 [L][4] (params,
+    flops, bnd, intm); strategies: STRATEGY_DTYPE array."""
+    layers = np.ascontiguousarray(layers, dtype=np.float64)
+    strategies = np.ascontiguousarray(strategies, dtype=STRATEGY_DTYPE)
+    L, S = len(layers), len(strategies)
+    assert layers.shape == (L, 4)
+    h = gbmw_hardware(hw["rate"], hw["bw_in"], hw["bw_out"], hw["param_bytes"], hw["state_bytes"], hw["slow"],
+                      hw["unit_bytes"], hw["island"])
+    shapes = dict(c=((L, S), np.float32), c_nosync=((L, S), np.float32), O_f=((L, S), np.int32),
+                  O_b=((L, S), np.int32), O_ms=((L, S), np.int32), M=((P, L, S), np.int32), R=((L, S, S), np.float32))
+    if device:
+        tdt = {np.float32: torch.float32, np.int32: torch.int32}
+        out = {k: torch.empty(sh, dtype=tdt[dt], device="cuda") for k, (sh, dt) in shapes.items()}
+    else:
+        out = {k: np.empty(sh, dt) for k, (sh, dt) in shapes.items()}
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else 0
+    _check(_lib.gbmw_cost_model(layers.ctypes.data, L, strategies.ctypes.data, S, ct.byref(h), float(Bm), P,
+                                GBMW_PTR_DEVICE if device else GBMW_PTR_HOST,
+                                *[_ptr(out[k]) for k in ("c", "c_nosync", "O_f", "O_b", "O_ms", "M", "R")], stream))
+    return out
 
 
 def gbmw_export_tables(ctx: Context, instance: int, l0: int = 0, l1: int | None = None,

@@ -1,0 +1,107 @@
+"""The analytic cost model on the GPU against the oracle, bit for bit, and its
+device outputs feeding the table solve directly (needs an MI355X)."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+import gbmw_inputs as gi
+import oracle
+import oracle.strategy as ost
+import pins
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def g():
+    import paper_2307_02031_amd as g
+    return g
+
+
+def _layers_as_dicts(layers):
+    return [dict(params=float(r[0]), flops=float(r[1]), bnd=float(r[2]), int=float(r[3])) for r in layers]
+
+
+def _compare(got, ref):
+    for k in ("c", "c_nosync", "R"):
+        pins.assert_same_f32(np.asarray(got[k]), ref["c_ns" if k == "c_nosync" else k], k)
+    for k in ("O_f", "O_b", "O_ms", "M"):
+        assert np.array_equal(np.asarray(got[k]), ref[k]), k
+
+
+def test_worked_example(g):
+    with open(os.path.join(pins.GOLDEN, "worked_example_cost_model.json")) as f:
+        gold = json.load(f)
+    strat = np.zeros(len(gold["cases"]), g.STRATEGY_DTYPE)
+    for s, case in enumerate(gold["cases"]):
+        strat[s]["n_levels"] = len(case["levels"])
+        for i, (k, d) in enumerate(case["levels"]):
+            strat[s]["kind"][i], strat[s]["degree"][i] = k, d
+        strat[s]["ckpt"] = case["ckpt"]
+    ly = gold["layer"]
+    layers = np.array([[ly["params"], ly["flops"], ly["bnd"], ly["int"]]] * 2)
+    out = g.gbmw_cost_model(layers, strat, gold["hw"], gold["Bm"], 3)
+    for s, case in enumerate(gold["cases"]):
+        assert float(out["c"][1, s]) == case["c"] and float(out["c_nosync"][0, s]) == case["c_ns"]
+        assert [int(out[k][1, s]) for k in ("O_ms", "O_f", "O_b")] == case["units"]
+        assert [int(out["M"][i, 0, s]) for i in range(3)] == [case["units"][0] + (3 - i) * case["units"][1] for i in range(3)]
+    assert not out["R"][0].any()
+    assert [float(out["R"][1, 0, 1]), float(out["R"][1, 0, 2]), float(out["R"][1, 0, 0])] == [0.01171875, 0.015625, 0.0]
+
+
+@pytest.mark.parametrize("name,group,P,Bm,island", [("BERT-Huge-32", 8, 1, 16.0, 8), ("BERT-Huge-48", 4, 2, 8.0, 4),
+                                                     ("ViT-Huge-32", 2, 4, 24.0, 2), ("GPT3-15B", 16, 4, 6.0, 8),
+                                                     ("BERT-xHuge", 1, 8, 3.0, 8)])
+def test_table1_models_against_the_oracle(g, name, group, P, Bm, island):
+    layers = gi.table1_layers(name)
+    layers[1::3, 1] *= 1.37                     # some variety between the layers
+    layers[2::5, 2] *= 0.61
+    hw = dict(gi.default_hardware(unit_mb=3.0), island=island)
+    strat = g.gbmw_enumerate_strategies(group)
+    ref = ost.cost_model(_layers_as_dicts(layers), ost.enumerate_strategies(group), hw, Bm, P, hw["unit_bytes"])
+    _compare(g.gbmw_cost_model(layers, strat, hw, Bm, P), ref)
+    dev = g.gbmw_cost_model(layers, strat, hw, Bm, P, device=True)
+    _compare({k: v.cpu().numpy() for k, v in dev.items()}, ref)
+
+
+def test_device_outputs_feed_the_search(g):
+    """Shapes -> cost model on the device -> table solve, nothing passing through the
+    host; against the oracle's cost model and table solve."""
+    import torch
+    layers = gi.table1_layers("BERT-Huge-32")[:12]
+    hw = gi.default_hardware(unit_mb=16.0)
+    strat = g.gbmw_enumerate_strategies(8)
+    P, Bm, E = 2, 16.0, 1536                                   # 24 GiB in 16 MiB units
+    dev = g.gbmw_cost_model(layers, strat, hw, Bm, P, device=True)
+    S = len(strat)
+    for i in range(P):
+        M = dev["M"][i].contiguous()
+        ctx = g.gbmw_dp_solve_batched([len(layers)], dev["c"], M, dev["R"], S, E)
+        best, _ = g.gbmw_get_best(ctx)
+        ref_in = ost.cost_model(_layers_as_dicts(layers), ost.enumerate_strategies(8), hw, Bm, P, hw["unit_bytes"])
+        ref = oracle.solve(ref_in["c"], np.ascontiguousarray(ref_in["M"][i]), ref_in["R"], E, keep_C=False)
+        pins.assert_same_f32(best[0], ref.best, f"best, stage position {i}")
+        plan, cost, mem = g.gbmw_backtrack(ctx, [0], [E])
+        rp, rc, rm = ref.backtrack(E)
+        assert np.array_equal(plan[0], rp) and pins.bits(cost[0]) == pins.bits(rc) and mem[0] == rm
+        assert np.isfinite(cost[0]), "the budget must admit a plan"
+        g.gbmw_destroy(ctx)
+    del torch
+
+
+def test_argument_errors(g):
+    layers = gi.table1_layers("ViT-Huge-32")
+    strat = g.gbmw_enumerate_strategies(4)
+    hw = gi.default_hardware()
+    with pytest.raises(g.GbmwError):
+        g.gbmw_cost_model(layers, strat, dict(hw, unit_bytes=1e-6), 8.0, 2)      # memories overflow int32
+    with pytest.raises(g.GbmwError):
+        g.gbmw_cost_model(layers, strat, dict(hw, rate=0.0), 8.0, 2)
+    bad = strat.copy(); bad[3]["degree"][0] = 3
+    with pytest.raises(g.GbmwError):
+        g.gbmw_cost_model(layers, bad, hw, 8.0, 2)
+    bad = strat.copy(); bad[-1]["kind"][1] = bad[-1]["kind"][0]
+    with pytest.raises(g.GbmwError):
+        g.gbmw_cost_model(layers, bad, hw, 8.0, 2)
