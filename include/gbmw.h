@@ -195,10 +195,13 @@ gbmw_status gbmw_pipeline_cost(gbmw_ctx* ctx, int32_t n_pipe, const int32_t* sta
  * The chain of a pair ends when the new partition is rejected, when a search is
  * infeasible (pipeline time +inf), or after max_iter searches.  Algorithm 2's
  * value for the pair is the cost of its last trace entry.
- * Rounds of all pairs run in lockstep, each as ONE batched table solve of the
- * stages that changed (a stage whose layers did not change keeps its result;
- * GBMW_FLAG_RESOLVE_ALL solves every stage of every live pair each round, with
- * identical results).
+ * Rounds of all pairs run in lockstep, each as ONE batched table solve of what the
+ * accepted moves invalidated: a stage whose layers did not change keeps its
+ * result, a stage that gained a layer at its end runs one more layer step on its
+ * kept table, a stage that lost its last layer only reduces best(E) again, a stage
+ * whose first layer changed is solved again (GBMW_FLAG_RESOLVE_ALL solves every
+ * stage of every live pair from scratch each round, with identical results).
+ * Device memory: per (pair, stage) argmin rows for Lm_k - P_k + 1 layers.
  *
  * fp32 contract: stage times as in gbmw_dp_solve_batched; re-evaluations under
  * fixed strategies as in gbmw_pipeline_cost (v = c(a, s_a); v = (v + R(l,

@@ -80,6 +80,19 @@ gbmw_status check_host_values(const gbmw_problem* p, const std::vector<int>& L,
 
 namespace gbmw_detail {
 
+gbmw_status ensure_streams(gbmw_ctx* c, int G) {
+  while ((int)c->aux.size() < G - 1) {
+    hipStream_t a;
+    HIP_TRY(hipStreamCreateWithFlags(&a, hipStreamNonBlocking));   // default priority
+    c->aux.push_back(a);
+    hipEvent_t e;
+    HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    c->ev_join.push_back(e);
+  }
+  if (G > 1 && !c->ev_fork) HIP_TRY(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
+  return GBMW_OK;
+}
+
 gbmw_status new_ctx(gbmw_ctx** out) {
   gbmw_ctx* c = new (std::nothrow) gbmw_ctx();
   if (!c) return fail(GBMW_ERR_OOM, "host allocation failed");
@@ -271,15 +284,7 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
     }
   }
 
-  while ((int)c->aux.size() < G - 1) {
-    hipStream_t a;
-    HIP_TRY_B(hipStreamCreateWithFlags(&a, hipStreamNonBlocking));   // default priority
-    c->aux.push_back(a);
-    hipEvent_t e;
-    HIP_TRY_B(hipEventCreateWithFlags(&e, hipEventDisableTiming));
-    c->ev_join.push_back(e);
-  }
-  if (G > 1 && !c->ev_fork) HIP_TRY_B(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
+  TRY(gbmw_detail::ensure_streams(c, G));
 
   HIP_TRY_B(hipEventRecord(c->ev0, st));
   gbmw::launch_prepare(t, dR, sumL, p->ptr_space == GBMW_PTR_DEVICE, st);

@@ -46,6 +46,9 @@ struct DevBuf {
 // e >= final_from only (0: all of them; E: just the full budget).
 gbmw_status solve_batched(const gbmw_problem* p, uint32_t flags, gbmw_ctx** ctx, int final_from);
 
+// Helper streams (default priority) and fork / join events for G instance groups.
+gbmw_status ensure_streams(gbmw_ctx* c, int G);
+
 // A new, empty context on the current device.
 gbmw_status new_ctx(gbmw_ctx** out);
 

@@ -2,17 +2,26 @@
 // and Appendix B) for many (batch size, PP degree) pairs in lockstep.  See
 // include/gbmw.h for the contract.
 //
-// Per round the host only decides WHICH stages are solved (it mirrors the
+// Every (pair, stage) owns a slot: table rows for as many layers as the stage can
+// ever hold, a pair of fp32 layer tables, its best row.  The slots live for the
+// whole call, so a round only computes what the accepted move invalidated:
+//   the stage whose FIRST layer changed          all of its layers again
+//   the stage that gained a layer at its END     one more layer step on its kept table
+//   the stage that lost its LAST layer           nothing but the final reduce, if the
+//                                                table of its new last layer is still there
+//   every other stage                            nothing
+// Per round the host only decides which slots are touched (it mirrors the
 // partitions from the accept flags it reads back); everything that produces a
 // value runs in kernels:
-//   k_gather        rows of the resident model -> the batch the table solve reads
-//   (table solve)   gbmw_dp_solve_batched on device pointers
-//   k_stage_result  plan at e = E of every solved stage -> strategies, C, Cns, O
+//   k_gather        rows of the resident model -> the rows of the touched slots
+//   table solve     the layer kernels of gbmw_kernels.hip on the touched slots
+//   k_stage_result  plan at e = E of every touched stage -> strategies, C, Cns, O
 //   k_chain_step    Eq. 8, Eq. 6, PP_Partition_Adjust, Validate, trace entry
 #include <algorithm>
 #include <climits>
 #include <cmath>
 #include <cstring>
+#include <utility>
 #include <vector>
 
 #include "gbmw_ctx.h"
@@ -40,36 +49,38 @@ __global__ void k_fill_u32(uint32_t* p, size_t n, uint32_t v) {
   if (i < n) p[i] = v;
 }
 
-// one workgroup per batch row: c, M and the S x S slab of R of its source layer
+// one workgroup per row: c, M and the S x S slab of R of a model layer -> a slot row
 __global__ __launch_bounds__(256) void k_gather(const float* __restrict__ c,
                                                 const int* __restrict__ M,
                                                 const float* __restrict__ R,
                                                 const int* __restrict__ row_src,
-                                                const int* __restrict__ row_msrc, int S,
+                                                const int* __restrict__ row_msrc,
+                                                const int* __restrict__ row_dst, int S,
                                                 float* __restrict__ c_g, int* __restrict__ M_g,
                                                 float* __restrict__ R_g) {
-  const int r = blockIdx.x;
-  const size_t src = (size_t)row_src[r], msrc = (size_t)row_msrc[r];
+  const size_t src = (size_t)row_src[blockIdx.x], msrc = (size_t)row_msrc[blockIdx.x];
+  const size_t dst = (size_t)row_dst[blockIdx.x];
   for (int i = threadIdx.x; i < S; i += 256) {
-    c_g[(size_t)r * S + i] = c[src * S + i];
-    M_g[(size_t)r * S + i] = M[msrc * S + i];
+    c_g[dst * S + i] = c[src * S + i];
+    M_g[dst * S + i] = M[msrc * S + i];
   }
   const int SS = S * S;
-  for (int i = threadIdx.x; i < SS; i += 256) R_g[(size_t)r * SS + i] = R[src * SS + i];
+  for (int i = threadIdx.x; i < SS; i += 256) R_g[dst * SS + i] = R[src * SS + i];
 }
 
 // One lane per solved stage: walk its plan at e = E down the argmin records,
 // leave the strategies in the model-wide array, the stage's time, memory and
 // time without gradient synchronisation in the pair's stage slots.
 __global__ __launch_bounds__(64) void k_stage_result(Tables t, Search s,
-                                                     const int* __restrict__ inst_chain,
-                                                     const int* __restrict__ inst_stage,
-                                                     const int* __restrict__ inst_first, int nb) {
-  const int b = blockIdx.x * 64 + threadIdx.x;
-  if (b >= nb) return;
-  const int k = inst_chain[b], i = inst_stage[b], a = inst_first[b], n = t.L[b], S = t.S;
+                                                     const int* __restrict__ touched, int nt,
+                                                     const int* __restrict__ slot_chain,
+                                                     const int* __restrict__ slot_first) {
+  const int q = blockIdx.x * 64 + threadIdx.x;
+  if (q >= nt) return;
+  const int b = touched[q];                                // slot = instance of the table solve
+  const int k = slot_chain[b], a = slot_first[b], n = t.L[b], S = t.S;
   const size_t lrow = (size_t)s.lrow[k] + a;
-  const int slot = s.prow[k] + i;
+  const int slot = b;
   uint8_t* st = s.strat + lrow;
   float C = t.best[(size_t)b * t.EP + t.E];
   int mem = 0;
@@ -357,6 +368,23 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
   HIP_TRY_B(hipSetDevice(c->device));
   hipStream_t st = (hipStream_t)q->stream;
   c->solved = false;
+  c->index_on_device = false;
+  c->stream = st;
+
+  // ---- slots: one per (pair, stage), with room for the longest stage it can become ----
+  const int B = (int)sumP;
+  std::vector<int> slot_chain(B), slot_stage(B), off(B), cap(B);
+  long long rows_total = 0;
+  for (int k = 0, b = 0; k < n; ++k)
+    for (int i = 0; i < q->P[k]; ++i, ++b) {
+      slot_chain[b] = k; slot_stage[b] = i;
+      cap[b] = q->Lm[k] - q->P[k] + 1;
+      off[b] = (int)rows_total;
+      rows_total += cap[b];
+    }
+  if (rows_total > (1 << 24)) return bail(fail(GBMW_ERR_INVALID_ARG, "too many table rows (%lld)", rows_total));
+  const int SP = (S + 3) / 4 * 4, RS = (SP + 2 + 3) / 4 * 4, EP = (E + 1 + 255) / 256 * 256;
+  const size_t slab = (size_t)S * EP;
 
   // ---- device state -------------------------------------------------------
   const Dims d{(size_t)n, (size_t)sumP, (size_t)sumLm, (size_t)sumPL, (size_t)S, tr, trP};
@@ -378,18 +406,20 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
   s.P = dP; s.Lm = dLm; s.m = dm; s.lrow = dlrow; s.prow = dprow; s.mrow = dmrow;
   s.c = dc; s.cns = dcns; s.R = dR; s.M = dM;
 
-  // per-round batch: gathered inputs and the index arrays that describe it
+  // rows of the slots (what the layer kernels read) and the per-round index arrays
+  const size_t rows = (size_t)rows_total;
   float *gc = nullptr, *gR = nullptr;
-  int *gM = nullptr, *g_src = nullptr, *g_msrc = nullptr, *g_chain = nullptr, *g_stage = nullptr,
-      *g_first = nullptr;
+  int *gM = nullptr, *g_src = nullptr, *g_msrc = nullptr, *g_dst = nullptr, *g_touched = nullptr,
+      *g_chain = nullptr, *g_first = nullptr;
   auto carve_gather = [&](Carver& w) {
-    gc = w.take<float>(d.sumLm * d.S);
-    gM = w.take<int>(d.sumLm * d.S);
-    gR = w.take<float>(d.sumLm * d.S * d.S);
-    g_src = w.take<int>(d.sumLm);
-    g_msrc = w.take<int>(d.sumLm);
+    gc = w.take<float>(rows * d.S);
+    gM = w.take<int>(rows * d.S);
+    gR = w.take<float>(rows * d.S * d.S);
+    g_src = w.take<int>(rows);
+    g_msrc = w.take<int>(rows);
+    g_dst = w.take<int>(rows);
+    g_touched = w.take<int>(d.sumP);
     g_chain = w.take<int>(d.sumP);
-    g_stage = w.take<int>(d.sumP);
     g_first = w.take<int>(d.sumP);
     return w.used;
   };
@@ -399,6 +429,25 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
     Carver cv(c->d_gather.p);
     carve_gather(cv);
   }
+  TRY(c->d_L.reserve(sizeof(int) * B));
+  TRY(c->d_off.reserve(sizeof(int) * B));
+  TRY(c->d_perm.reserve(sizeof(int) * B));
+  TRY(c->d_status.reserve(sizeof(int)));
+  TRY(c->d_Rt.reserve(sizeof(float) * rows * S * RS));
+  TRY(c->d_C.reserve(sizeof(float) * slab * 2 * B));
+  TRY(c->d_A.reserve(slab * rows));
+  TRY(c->d_best.reserve(sizeof(float) * (size_t)B * EP));
+  TRY(c->d_best_s.reserve((size_t)B * EP));
+  constexpr int kFreshGroups = 2;
+  TRY(gbmw_detail::ensure_streams(c, kFreshGroups));
+
+  gbmw::Tables& t = c->t;
+  t.B = B; t.S = S; t.SP = SP; t.RS = RS; t.E = E; t.EP = EP; t.keep_all = 0; t.final_from = E;
+  t.L = (const int*)c->d_L.p; t.off = (const int*)c->d_off.p; t.perm = (const int*)c->d_perm.p;
+  t.c = gc; t.M = gM; t.Rt = (const float*)c->d_Rt.p;
+  t.Cbuf = (float*)c->d_C.p; t.A = (uint8_t*)c->d_A.p;
+  t.best = (float*)c->d_best.p; t.best_s = (uint8_t*)c->d_best_s.p;
+  t.status = (int*)c->d_status.p;
 
   HIP_TRY_B(hipEventCreate(&ev0));
   HIP_TRY_B(hipEventCreate(&ev1));
@@ -415,102 +464,198 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
   HIP_TRY_B(hipMemcpyAsync(dR, q->R, sizeof(float) * d.sumLm * S * S, H2D, st));
   HIP_TRY_B(hipMemcpyAsync(dM, q->M, sizeof(int) * d.sumPL * S, H2D, st));
   HIP_TRY_B(hipMemcpyAsync(s.part, q->p0, sizeof(int) * d.sumP, H2D, st));
+  HIP_TRY_B(hipMemcpyAsync(c->d_off.p, off.data(), sizeof(int) * B, H2D, st));
+  HIP_TRY_B(hipMemcpyAsync(g_chain, slot_chain.data(), sizeof(int) * B, H2D, st));
   hipLaunchKernelGGL(gbmw::k_fill_u32, dim3((unsigned)((zero_words + 255) / 256)), dim3(256), 0, st,
                      zero_begin, zero_words, 0u);
   hipLaunchKernelGGL(gbmw::k_fill_u32, dim3((unsigned)((d.n + 255) / 256)), dim3(256), 0, st,
                      (uint32_t*)s.live, d.n, 1u);
   hipLaunchKernelGGL(gbmw::k_fill_u32, dim3((unsigned)((d.n + 255) / 256)), dim3(256), 0, st,
                      (uint32_t*)s.Ot, d.n, (uint32_t)INT_MAX);      // no limit 3 until p_t is searched
+  // every row of the slots is readable from the start (rows beyond a stage's layers are never used)
+  for (auto [ptr, words] : {std::pair<void*, size_t>{gc, rows * d.S}, {gM, rows * d.S}, {gR, rows * d.S * d.S}})
+    hipLaunchKernelGGL(gbmw::k_fill_u32, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st,
+                       (uint32_t*)ptr, words, 0u);
   HIP_TRY_B(hipGetLastError());
 
   // ---- rounds -------------------------------------------------------------
+  enum Mode { kSkip = 0, kFresh = 1, kAppend = 2, kFinalOnly = 3 };
   std::vector<std::vector<int>> part(n);             // host mirror of the partitions
   std::vector<char> live(n, 1);
-  std::vector<int> h_L, h_src, h_msrc, h_chain, h_stage, h_first, h_flags(3 * (size_t)n);
+  // per slot: layers it holds, first model layer, and which of its fp32 layer tables are in
+  // memory (the rolling pair keeps the last two computed; hi = -1: none)
+  std::vector<int> slotL(B, 0), slot_first(B, 0), c_hi(B, -1), c_lo(B, -1), mode(B, kSkip);
+  std::vector<int> h_src, h_msrc, h_dst, h_touched, h_perm, h_flags(3 * (size_t)n);
   int rounds = 0, stage_solves = 0;
   long long cell_updates = 0;
+  const bool l0_in_regs = gbmw::layer0_in_registers(S);
 
-  // stages[k]: which stages of pair k are solved this round, under partition pp[k]
-  auto run_round = [&](const std::vector<std::vector<int>>& pp, const std::vector<std::vector<int>>& stages,
-                       int phase) -> gbmw_status {
-    h_L.clear(); h_src.clear(); h_msrc.clear(); h_chain.clear(); h_stage.clear(); h_first.clear();
-    for (int k = 0; k < n; ++k) {
-      if (stages[k].empty()) continue;
-      std::vector<int> first(pp[k].size(), 0);
-      for (size_t i = 1; i < pp[k].size(); ++i) first[i] = first[i - 1] + pp[k][i - 1];
-      for (int i : stages[k]) {
-        h_chain.push_back(k); h_stage.push_back(i); h_first.push_back(first[i]); h_L.push_back(pp[k][i]);
-        for (int l = first[i]; l < first[i] + pp[k][i]; ++l) {
-          h_src.push_back(lrow[k] + l);
-          h_msrc.push_back(mrow[k] + i * q->Lm[k] + l);
+  // One round: the slots with mode != kSkip get their new layer count slotL / first layer
+  // slot_first, are brought up to date and read back into the pairs' stage results.
+  auto run_round = [&](int phase) -> gbmw_status {
+    h_src.clear(); h_msrc.clear(); h_dst.clear(); h_touched.clear();
+    std::vector<int> fresh, append, final_only;
+    for (int b = 0; b < B; ++b) {
+      if (mode[b] == kSkip) continue;
+      const int k = slot_chain[b], i = slot_stage[b], L = slotL[b];
+      h_touched.push_back(b);
+      if (mode[b] == kFresh) {
+        fresh.push_back(b);
+        for (int l = 0; l < L; ++l) {
+          h_src.push_back(lrow[k] + slot_first[b] + l);
+          h_msrc.push_back(mrow[k] + i * q->Lm[k] + slot_first[b] + l);
+          h_dst.push_back(off[b] + l);
         }
-        cell_updates += (long long)(pp[k][i] - 1) * (E + 1) * S * S;
+        cell_updates += (long long)(L - 1) * (E + 1) * S * S;
+        // what a complete solve leaves in the rolling pair: L-1 and L-2, layer 0 only if it
+        // was written to memory (stages of one or two layers, or S > 64)
+        c_hi[b] = L - 1;
+        c_lo[b] = (L >= 2 && (L - 2 >= 1 || L <= 2 || !l0_in_regs)) ? L - 2 : -1;
+      } else if (mode[b] == kAppend) {
+        append.push_back(b);
+        h_src.push_back(lrow[k] + slot_first[b] + L - 1);
+        h_msrc.push_back(mrow[k] + i * q->Lm[k] + slot_first[b] + L - 1);
+        h_dst.push_back(off[b] + L - 1);
+        cell_updates += (long long)(E + 1) * S * S;
+        c_lo[b] = L - 2;
+        c_hi[b] = L - 1;
+      } else {
+        final_only.push_back(b);
       }
     }
-    const int nb = (int)h_L.size(), rows = (int)h_src.size();
-    if (nb == 0) return GBMW_OK;
+    const int nt = (int)h_touched.size();
+    if (nt == 0) return GBMW_OK;
     ++rounds;
-    stage_solves += nb;
-    HIP_TRY(hipMemcpyAsync(g_src, h_src.data(), sizeof(int) * rows, H2D, st));
-    HIP_TRY(hipMemcpyAsync(g_msrc, h_msrc.data(), sizeof(int) * rows, H2D, st));
-    HIP_TRY(hipMemcpyAsync(g_chain, h_chain.data(), sizeof(int) * nb, H2D, st));
-    HIP_TRY(hipMemcpyAsync(g_stage, h_stage.data(), sizeof(int) * nb, H2D, st));
-    HIP_TRY(hipMemcpyAsync(g_first, h_first.data(), sizeof(int) * nb, H2D, st));
-    hipLaunchKernelGGL(gbmw::k_gather, dim3(rows), dim3(256), 0, st, dc, dM, dR, g_src, g_msrc, S, gc, gM, gR);
+    stage_solves += nt;
+    // launch order: two groups of complete solves (longest first, dealt alternately), the
+    // one-step slots ordered by their layer index, the reduce-only slots
+    auto longer = [&](int a2, int b2) { return slotL[a2] > slotL[b2]; };
+    std::stable_sort(fresh.begin(), fresh.end(), longer);
+    std::stable_sort(append.begin(), append.end(), longer);
+    const int G = std::max(1, std::min(kFreshGroups, (int)fresh.size()));
+    h_perm.clear();
+    std::vector<int> gfirst(G + 1, 0);
+    for (int g = 0; g < G; ++g) {
+      gfirst[g] = (int)h_perm.size();
+      for (size_t x = g; x < fresh.size(); x += G) h_perm.push_back(fresh[x]);
+    }
+    gfirst[G] = (int)h_perm.size();
+    const int a_first = (int)h_perm.size();
+    h_perm.insert(h_perm.end(), append.begin(), append.end());
+    h_perm.insert(h_perm.end(), final_only.begin(), final_only.end());
+
+    const int nrows = (int)h_src.size();
+    HIP_TRY(hipMemcpyAsync(c->d_L.p, slotL.data(), sizeof(int) * B, H2D, st));
+    HIP_TRY(hipMemcpyAsync(c->d_perm.p, h_perm.data(), sizeof(int) * h_perm.size(), H2D, st));
+    HIP_TRY(hipMemcpyAsync(g_first, slot_first.data(), sizeof(int) * B, H2D, st));
+    HIP_TRY(hipMemcpyAsync(g_touched, h_touched.data(), sizeof(int) * nt, H2D, st));
+    if (nrows) {
+      HIP_TRY(hipMemcpyAsync(g_src, h_src.data(), sizeof(int) * nrows, H2D, st));
+      HIP_TRY(hipMemcpyAsync(g_msrc, h_msrc.data(), sizeof(int) * nrows, H2D, st));
+      HIP_TRY(hipMemcpyAsync(g_dst, h_dst.data(), sizeof(int) * nrows, H2D, st));
+      hipLaunchKernelGGL(gbmw::k_gather, dim3(nrows), dim3(256), 0, st, dc, dM, dR, g_src, g_msrc, g_dst, S,
+                         gc, gM, gR);
+      // inputs were validated on the host; rows outside the stages hold zeros
+      gbmw::launch_prepare(t, gR, (int)rows, false, st);
+    }
+    // layer 0 goes to memory where something reads it from there
+    for (int g = 0; g < G; ++g) {
+      int n_init = gfirst[g + 1] - gfirst[g];
+      if (l0_in_regs) {
+        n_init = 0;
+        for (int x = gfirst[g + 1] - 1; x >= gfirst[g] && slotL[h_perm[x]] <= 2; --x) ++n_init;
+      }
+      gbmw::launch_init_layer0(t, gfirst[g + 1] - n_init, n_init, st);
+    }
     HIP_TRY(hipGetLastError());
-    gbmw_problem pr{};
-    pr.B = nb; pr.S = S; pr.E = E; pr.L = h_L.data();
-    pr.c = gc; pr.M = gM; pr.R = gR; pr.ptr_space = GBMW_PTR_DEVICE; pr.stream = st;
-    gbmw_ctx* cc = c;
-    gbmw_status rs = gbmw_detail::solve_batched(&pr, 0, &cc, E);   // only best(E) is read
-    if (rs != GBMW_OK) return rs;
-    c->solved = false;                                 // the tables are an intermediate of this call
-    hipLaunchKernelGGL(gbmw::k_stage_result, dim3((nb + 63) / 64), dim3(64), 0, st, c->t, s, g_chain,
-                       g_stage, g_first, nb);
+    if (G > 1) HIP_TRY(hipEventRecord(c->ev_fork, st));
+    for (int g = 0; g < G; ++g) {
+      hipStream_t sg = (g == 0) ? st : c->aux[g - 1];
+      if (g > 0) HIP_TRY(hipStreamWaitEvent(sg, c->ev_fork, 0));
+      if (g == G - 1) {
+        // the one-step slots: all slots whose new last layer has the same index share a launch
+        for (size_t x = 0; x < append.size();) {
+          size_t y = x;
+          while (y < append.size() && slotL[append[y]] == slotL[append[x]]) ++y;
+          gbmw::launch_minplus(t, slotL[append[x]] - 1, a_first + (int)x, (int)(y - x), sg);
+          x = y;
+        }
+        gbmw::launch_final(t, a_first, (int)h_perm.size() - a_first, sg);
+      }
+      const int gn = gfirst[g + 1] - gfirst[g];
+      const int Lmax_g = gn ? slotL[h_perm[gfirst[g]]] : 0;
+      for (int l = 1; l < Lmax_g; ++l) {
+        int na = 0;
+        while (na < gn && slotL[h_perm[gfirst[g] + na]] > l) ++na;
+        gbmw::launch_minplus(t, l, gfirst[g], na, sg);
+      }
+      gbmw::launch_final(t, gfirst[g], gn, sg);
+      if (g > 0) {
+        HIP_TRY(hipEventRecord(c->ev_join[g - 1], sg));
+        HIP_TRY(hipStreamWaitEvent(st, c->ev_join[g - 1], 0));
+      }
+    }
+    hipLaunchKernelGGL(gbmw::k_stage_result, dim3((nt + 63) / 64), dim3(64), 0, st, t, s, g_touched, nt,
+                       g_chain, g_first);
     hipLaunchKernelGGL(gbmw::k_chain_step, dim3((n + 63) / 64), dim3(64), 0, st, s, phase);
     HIP_TRY(hipGetLastError());
-    // accept flags: live | moved (two per pair); also ends the round for the host vectors above
+    // accept flags: live | moved (two per pair); the wait also ends the round for the host vectors
     HIP_TRY(hipMemcpyAsync(h_flags.data(), s.live, sizeof(int) * n, hipMemcpyDeviceToHost, st));
     HIP_TRY(hipMemcpyAsync(h_flags.data() + n, s.moved, sizeof(int) * 2 * n, hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
     return GBMW_OK;
   };
 
-  std::vector<std::vector<int>> stages(n);
-  if (q->p_t) {
+  // every stage of every pair from scratch, under the partitions `part`
+  auto all_fresh = [&]() {
     for (int k = 0; k < n; ++k) {
-      part[k].assign(q->p_t + prow[k], q->p_t + prow[k] + q->P[k]);
-      stages[k].resize(q->P[k]);
-      for (int i = 0; i < q->P[k]; ++i) stages[k][i] = i;
+      int a = 0;
+      for (int i = 0; i < q->P[k]; ++i) {
+        const int b = prow[k] + i;
+        mode[b] = kFresh; slotL[b] = part[k][i]; slot_first[b] = a;
+        a += part[k][i];
+      }
     }
-    TRY(run_round(part, stages, 0));
+  };
+  if (q->p_t) {
+    for (int k = 0; k < n; ++k) part[k].assign(q->p_t + prow[k], q->p_t + prow[k] + q->P[k]);
+    all_fresh();
+    TRY(run_round(0));
   }
-  for (int k = 0; k < n; ++k) {
-    part[k].assign(q->p0 + prow[k], q->p0 + prow[k] + q->P[k]);
-    stages[k].resize(q->P[k]);
-    for (int i = 0; i < q->P[k]; ++i) stages[k][i] = i;
-  }
+  for (int k = 0; k < n; ++k) part[k].assign(q->p0 + prow[k], q->p0 + prow[k] + q->P[k]);
+  all_fresh();
   const bool resolve_all = (flags & GBMW_FLAG_RESOLVE_ALL) != 0;
   for (int it = 0; it < q->max_iter; ++it) {
-    TRY(run_round(part, stages, 1));
+    TRY(run_round(1));
+    std::fill(mode.begin(), mode.end(), (int)kSkip);
     bool any = false;
     for (int k = 0; k < n; ++k) {
-      stages[k].clear();
       if (!live[k]) continue;
       live[k] = (char)(h_flags[k] != 0);
       if (!live[k]) continue;
       const int i = h_flags[n + 2 * k], j = h_flags[n + 2 * k + 1];
-      if (i < 0 || i >= q->P[k] || j < 0 || j >= q->P[k] || part[k][i] < 2)
+      if (i < 0 || i >= q->P[k] || j < 0 || j >= q->P[k] || (j != i - 1 && j != i + 1) || part[k][i] < 2)
         return bail(fail(GBMW_ERR_DEVICE, "pair %d: inconsistent adjustment (%d -> %d)", k, i, j));
       part[k][i] -= 1;
       part[k][j] += 1;
-      if (resolve_all) {
-        for (int x = 0; x < q->P[k]; ++x) stages[k].push_back(x);
-      } else {
-        stages[k].push_back(std::min(i, j));
-        stages[k].push_back(std::max(i, j));
-      }
       any = true;
+      const int bi = prow[k] + i, bj = prow[k] + j;
+      slotL[bi] -= 1;
+      slotL[bj] += 1;
+      if (resolve_all) {
+        for (int x = 0; x < q->P[k]; ++x) mode[prow[k] + x] = kFresh;
+      } else if (j == i - 1) {
+        // the earlier stage takes the first layer of stage i: one more step at its end
+        const int need = slotL[bj] - 2;              // the table the new last layer is computed from
+        mode[bj] = (need == c_hi[bj] || need == c_lo[bj]) ? kAppend : kFresh;
+        mode[bi] = kFresh;
+      } else {
+        // the later stage takes the last layer of stage i: stage i's table is a prefix of itself
+        const int need = slotL[bi] - 1;
+        mode[bi] = (need == c_hi[bi] || need == c_lo[bi]) ? kFinalOnly : kFresh;
+        mode[bj] = kFresh;
+      }
+      if (j == i - 1) slot_first[bi] += 1; else slot_first[bj] -= 1;
     }
     if (!any) break;
   }
@@ -533,11 +678,6 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
     HIP_TRY_B(hipMemcpyAsync(h_strat.data(), s.strat, d.sumLm, D2H, st));
   }
   HIP_TRY_B(hipStreamSynchronize(st));
-  {
-    int status = 0;
-    HIP_TRY_B(hipMemcpy(&status, c->t.status, sizeof(int), hipMemcpyDeviceToHost));
-    if (status) return bail(fail(GBMW_ERR_INVALID_ARG, "device-side input check failed (0x%x)", status));
-  }
   if (out->strat) {
     memset(out->strat, 0xFF, (size_t)n * Lmmax);
     for (int k = 0; k < n; ++k)
@@ -553,6 +693,8 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
   (void)hipEventDestroy(ev1);
 #undef TRY
 #undef HIP_TRY_B
+  // the context's layout now belongs to this search: an ordinary solve re-creates its own
+  c->B = 0; c->L.clear(); c->off.clear(); c->perm.clear();
   *ctxp = c;
   return GBMW_OK;
 }

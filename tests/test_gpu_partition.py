@@ -85,6 +85,32 @@ def test_random_models(g, S, E, with_pt, flags):
     g.gbmw_destroy(ctx)
 
 
+def test_kept_tables_are_extended_not_recomputed(g):
+    """Layer steps actually executed (cell_updates / ((E+1) S^2)) on closed-form traces:
+    a stage that gains a layer at its end costs one step, a stage that loses its last
+    layer costs none, a stage whose first layer changes is solved again."""
+    two = gi.uniform_pipeline_model(10, 2, 1000, [1, 9])
+    res, ctx = _search(g, [two])
+    assert [list(x) for x in res["p"][0, :5]] == [[1, 9], [2, 8], [3, 7], [4, 6], [5, 5]]
+    # [1,9]: 0+8; then each round: 1 step for stage 0 plus all of stage 1: 7, 6, 5, 4
+    assert res["cell_updates"] == (8 + 8 + 7 + 6 + 5) * 1001 and res["stage_solves"] == 2 * 5
+    res, ctx = _search(g, [two], flags=g.GBMW_FLAG_RESOLVE_ALL, ctx=ctx)
+    assert res["cell_updates"] == 5 * 8 * 1001
+    three = gi.uniform_pipeline_model(10, 3, 1000, [2, 6, 2])
+    res, ctx = _search(g, [three], ctx=ctx)
+    assert [list(x) for x in res["p"][0, :4]] == [[2, 6, 2], [3, 5, 2], [3, 4, 3], [4, 3, 3]]
+    # [2,6,2]: 1+5+1; -> [3,5,2]: stage 0 one step, stage 1 again (4); -> [3,4,3]: stage 1 lost its
+    # last layer (0), stage 2 again (2); -> [4,3,3]: stage 0 one step, stage 1 again (2)
+    assert res["cell_updates"] == (7 + 5 + 2 + 3) * 1001
+    # with a time-balanced partition searched first: 10 - 3 more steps; its largest stage
+    # memory (4) then rejects [3,5,2] by limit 3, so the trace ends after [2,6,2]
+    three.p_t = np.array([4, 3, 3], np.int32)
+    res, ctx = _search(g, [three], ctx=ctx)
+    check_partition_search(res, [three], 64)
+    assert res["cell_updates"] == (7 + 7) * 1001 and res["n_iter"][0] == 1
+    g.gbmw_destroy(ctx)
+
+
 def test_changed_stage_reuse_solves_less_and_agrees(g):
     models = [gi.random_pipeline_model(9500 + k, 24, 22, 4, 600, M_rng=(1, 40)) for k in range(6)]
     a, ctx = _search(g, models, max_iter=32)

@@ -105,3 +105,34 @@ def test_argument_errors(g):
     bad = strat.copy(); bad[-1]["kind"][1] = bad[-1]["kind"][0]
     with pytest.raises(g.GbmwError):
         g.gbmw_cost_model(layers, bad, hw, 8.0, 2)
+
+
+@pytest.mark.parametrize("P", [1, 2, 4, 8])
+def test_shapes_to_partition_search(g, P):
+    """The whole planner path for one (batch size, PP degree) pair of a Table-1 model
+    on 8 devices: strategies of the 8/P-device group, cost model, Algorithm 2's
+    partition loop -- library against oracle, each on its own cost model output."""
+    import oracle.bmw as bmw
+    layers = gi.table1_layers("BERT-Huge-32")
+    layers[:, 1] *= np.linspace(0.7, 1.4, len(layers))           # deeper layers cost more time
+    hw = gi.default_hardware(unit_mb=16.0)
+    group, Bm, m, E = 8 // P, 4.0, 8, 384                         # 6 GiB in 16 MiB units: the budget binds
+    strat = g.gbmw_enumerate_strategies(group)
+    S, Lm = len(strat), len(layers)
+    got = g.gbmw_cost_model(layers, strat, hw, Bm, P)
+    ref = ost.cost_model(_layers_as_dicts(layers), ost.enumerate_strategies(group), hw, Bm, P, hw["unit_bytes"])
+    _compare(got, ref)
+    p0 = gi.proportional_partition(Lm, 1.0 / np.arange(P, 0, -1))
+    p_t = gi.proportional_partition(Lm, np.ones(P))
+    res, ctx = g.gbmw_partition_search([P], [Lm], [m], got["c"], got["c_nosync"], got["R"],
+                                       got["M"].reshape(P * Lm, S), p0, p_t, S, E, max_iter=16)
+    want = bmw.partition_search(dict(c=ref["c"], c_ns=ref["c_ns"], R=ref["R"], M=ref["M"]), p0, E, m, p_t=p_t,
+                                max_iter=16)
+    n = len(want["trace"])
+    assert int(res["n_iter"][0]) == n and int(res["O_t"][0]) == want["O_t"]
+    for j, t in enumerate(want["trace"]):
+        assert list(res["p"][0, j, :P]) == t["p"] and pins.bits(res["cost"][0, j]) == pins.bits(t["cost"])
+        assert [int(x) for x in res["O"][0, j, :P]] == [int(x) for x in t["O"]]
+    assert np.array_equal(res["strat"][0], want["strat"])
+    assert np.isfinite(res["cost"][0, n - 1]), "the budget must admit a plan"
+    g.gbmw_destroy(ctx)
