@@ -52,11 +52,19 @@ SHAPES = [  # (S, E, list of L): ragged tails, tile boundaries, every kernel var
     (7, 255, [5, 2]),
     (8, 256, [2, 7]),
     (13, 257, [4]),
+    (10, 520, [3, 5]),       # S = 10 .. 58: the remaining register-blocked instantiations
+    (18, 777, [4, 2]),
     (22, 1000, [6, 3, 9]),
     (24, 1023, [3]),
     (31, 2049, [4, 2]),
+    (27, 640, [3, 4]),
+    (35, 900, [2, 5]),
+    (38, 511, [4, 3]),
     (44, 3000, [5, 8, 2]),
     (45, 700, [3, 3]),
+    (50, 650, [3, 4]),
+    (55, 1025, [2, 4]),
+    (58, 800, [4, 2]),
     (64, 1500, [4, 6]),
     (65, 500, [3, 2]),       # above 64: LDS-staged generic kernel
     (100, 300, [3]),
@@ -75,6 +83,33 @@ def test_ragged_batches_all_shapes(g, S, E, Ls, device_inputs):
     ctx = solve_gpu(p, flags=g.GBMW_FLAG_KEEP_ALL_C, device_inputs=device_inputs)
     for b in range(p.B):
         check_instance(g, ctx, p, b, full_C=True, q_es=list(range(0, E + 1, max(1, E // 40))) + [E])
+    g.gbmw_destroy(ctx)
+
+
+@pytest.mark.parametrize("S", [3, 7, 11, 15, 19, 23, 26, 30, 34, 39, 43, 47, 51, 54, 59, 62])
+def test_wide_launches_every_instantiation(g, S):
+    """Launches of 1024 workgroups and more take the kernel's other path (each wave owns
+    its own 64 budgets instead of sharing a tile with the other waves of its workgroup):
+    ten instances of E = 32805 for every register-blocked instantiation, with
+    integer-valued costs so that ties are everywhere."""
+    E = 32805
+    _log(f"wide S={S}")
+    st = gi.Stream(6000 + S)
+    parts = []
+    for i, L in enumerate([3, 3, 3, 3, 3, 3, 3, 3, 3, 2]):
+        c = st.integers(L * S, 1, 4).astype(np.float32).reshape(L, S)
+        M = st.integers(L * S, 0, E // 2).reshape(L, S)
+        R = st.integers(L * S * S, 0, 2).astype(np.float32).reshape(L, S, S)
+        parts.append(gi.Problem(1, S, E, np.array([L]), c, M, R))
+    p = gi.stack(parts, f"wide-S{S}")
+    ctx = solve_gpu(p, device_inputs=True)
+    best, best_s = g.gbmw_get_best(ctx)
+    for b in (0, 4, 9):
+        check_instance(g, ctx, p, b, full_C=False, q_es=[0, 1, E // 2, E - 1, E], best=best, best_s=best_s)
+    for b in range(p.B):
+        ref = oracle.solve_problem(p, b, keep_C=False, keep_A=False, nthreads=16)
+        pins.assert_same_f32(best[b], ref.best, f"wide-S{S}[{b}] best")
+        assert np.array_equal(best_s[b], ref.best_s)
     g.gbmw_destroy(ctx)
 
 
