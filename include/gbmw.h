@@ -233,6 +233,11 @@ typedef struct {
   const int32_t* p0;     /* [sum P]          p0[prow_k + i] >= 1, summing to Lm_k     */
   const int32_t* p_t;    /* [sum P] or NULL  the time-balanced partition              */
   void* stream;          /* hipStream_t or NULL                                       */
+  /* Outer loops of Algorithm 1 / 2 (optional, both or neither): the pairs of one batch
+   * size form a group (its PP degrees); groups are numbered 0, 1, ... in the order the
+   * batch sizes are tried and batch_group is non-decreasing over the pairs.           */
+  const float* batch_size;    /* [n_chain] global batch size B of the pair's group, > 0  */
+  const int32_t* batch_group; /* [n_chain] group of each pair                            */
 } gbmw_partition_problem;
 
 /* Outputs of gbmw_partition_search; HOST memory owned by the caller.  Pmax = max P_k,
@@ -255,6 +260,14 @@ typedef struct {
   int32_t stage_solves;  /* out: stage instances solved over all rounds               */
   int64_t cell_updates;  /* out: sum over them of (layers - 1) * (E + 1) * S * S      */
   float device_ms;       /* out: first launch to last kernel, HIP events on `stream`  */
+  /* With batch sizes given: per group C_opt = min over its pairs of the pair's value
+   * (the cost of its last trace entry); groups are visited in order, the visit ends at
+   * the first group whose C_opt is +inf (out of memory), and Tpt = max B / C_opt over
+   * the groups visited before it (fp32 division; the first group on a tie).           */
+  float tpt;             /* out: Tpt (0 if the first group is already infeasible, or no
+                            batch sizes were given)                                   */
+  int32_t tpt_group;     /* out: group that gave Tpt (-1: none)                       */
+  int32_t tpt_pair;      /* out: its pair with the smallest cost (lowest index among equals) */
 } gbmw_partition_result;
 
 /*

@@ -48,7 +48,8 @@ class gbmw_partition_problem(ct.Structure):
     _fields_ = [("n_chain", ct.c_int32), ("S", ct.c_int32), ("E", ct.c_int32), ("max_iter", ct.c_int32),
                 ("P", ct.c_void_p), ("Lm", ct.c_void_p), ("m", ct.c_void_p), ("c", ct.c_void_p),
                 ("c_nosync", ct.c_void_p), ("R", ct.c_void_p), ("M", ct.c_void_p), ("p0", ct.c_void_p),
-                ("p_t", ct.c_void_p), ("stream", ct.c_void_p)]
+                ("p_t", ct.c_void_p), ("stream", ct.c_void_p), ("batch_size", ct.c_void_p),
+                ("batch_group", ct.c_void_p)]
 
 
 class gbmw_partition_result(ct.Structure):
@@ -56,7 +57,8 @@ class gbmw_partition_result(ct.Structure):
                 ("C", ct.c_void_p), ("Cns", ct.c_void_p), ("O", ct.c_void_p), ("alpha_t", ct.c_void_p),
                 ("alpha_m", ct.c_void_p), ("strat", ct.c_void_p),
                 ("rounds", ct.c_int32), ("stage_solves", ct.c_int32), ("cell_updates", ct.c_int64),
-                ("device_ms", ct.c_float)]
+                ("device_ms", ct.c_float), ("tpt", ct.c_float), ("tpt_group", ct.c_int32),
+                ("tpt_pair", ct.c_int32)]
 
 
 class gbmw_strategy(ct.Structure):
@@ -249,7 +251,8 @@ def gbmw_pipeline_cost(ctx: Context, stage_begin, stage_instance, stage_e, micro
 
 
 def gbmw_partition_search(P, Lm, m, c, c_nosync, R, M, p0, p_t, S: int, E: int, max_iter: int = 64,
-                          flags: int = 0, ctx: Context | None = None, stream: int | None = None):
+                          flags: int = 0, ctx: Context | None = None, stream: int | None = None,
+                          batch_size=None, batch_group=None):
     """Algorithm 2's inner loop for n_chain = len(P) pairs (host numpy arrays, the
     pairs' rows concatenated; c_nosync and p_t may be None).  Returns (result dict,
     ctx): n_iter, O_t [n]; p, C, Cns, O [n][max_iter][Pmax]; cost, alpha_t, alpha_m
@@ -257,7 +260,8 @@ def gbmw_partition_search(P, Lm, m, c, c_nosync, R, M, p0, p_t, S: int, E: int, 
     i32 = lambda a: None if a is None else np.ascontiguousarray(a, dtype=np.int32)
     f32 = lambda a: None if a is None else np.ascontiguousarray(a, dtype=np.float32)
     P, Lm, m, M, p0, p_t = (i32(a) for a in (P, Lm, m, M, p0, p_t))
-    c, c_nosync, R = (f32(a) for a in (c, c_nosync, R))
+    c, c_nosync, R, batch_size = (f32(a) for a in (c, c_nosync, R, batch_size))
+    batch_group = i32(batch_group)
     n, sumLm, sumP = len(P), int(Lm.sum()), int(P.sum())
     sumPL = int((P.astype(np.int64) * Lm).sum())
     assert Lm.shape == m.shape == (n,) and c.shape == (sumLm, S) and R.shape == (sumLm, S, S)
@@ -269,7 +273,7 @@ def gbmw_partition_search(P, Lm, m, c, c_nosync, R, M, p0, p_t, S: int, E: int, 
         stream = torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else 0
     ptr = lambda a: None if a is None else a.ctypes.data
     q = gbmw_partition_problem(n, S, E, max_iter, ptr(P), ptr(Lm), ptr(m), ptr(c), ptr(c_nosync), ptr(R),
-                               ptr(M), ptr(p0), ptr(p_t), stream)
+                               ptr(M), ptr(p0), ptr(p_t), stream, ptr(batch_size), ptr(batch_group))
     mi = max(1, max_iter)
     res = dict(n_iter=np.zeros(n, np.int32), O_t=np.zeros(n, np.int32),
                p=np.zeros((n, mi, Pmax), np.int32), cost=np.zeros((n, mi), np.float32),
@@ -277,14 +281,14 @@ def gbmw_partition_search(P, Lm, m, c, c_nosync, R, M, p0, p_t, S: int, E: int, 
                O=np.zeros((n, mi, Pmax), np.int32), alpha_t=np.zeros((n, mi), np.float32),
                alpha_m=np.zeros((n, mi), np.float32), strat=np.zeros((n, Lmmax), np.uint8))
     out = gbmw_partition_result(*[res[k].ctypes.data for k in ("n_iter", "O_t", "p", "cost", "C", "Cns", "O",
-                                                               "alpha_t", "alpha_m", "strat")], 0, 0, 0, 0.0)
+                                                               "alpha_t", "alpha_m", "strat")], 0, 0, 0, 0.0, 0.0, -1, -1)
     if ctx is None:
         ctx = Context()
     _check(_lib.gbmw_partition_search(ct.byref(q), flags, ct.byref(out), ct.byref(ctx.handle)))
     ctx.B = ctx.S = ctx.E = 0
     ctx.L, ctx._keep = None, ()
     res.update(rounds=out.rounds, stage_solves=out.stage_solves, cell_updates=out.cell_updates,
-               device_ms=out.device_ms)
+               device_ms=out.device_ms, tpt=np.float32(out.tpt), tpt_group=out.tpt_group, tpt_pair=out.tpt_pair)
     return res, ctx
 
 

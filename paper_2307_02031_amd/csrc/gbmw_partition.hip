@@ -226,6 +226,31 @@ __global__ __launch_bounds__(64) void k_chain_step(Search s, int phase) {
   s.live[k] = 1;
 }
 
+// Outer loops of Algorithm 1 / 2 on the pairs' final costs (one lane): out[0] = Tpt,
+// out[1] = group, out[2] = pair (as int bits).
+__global__ void k_throughput(Search s, const float* __restrict__ batch, const int* __restrict__ group,
+                             float* __restrict__ out) {
+  float tpt = 0.0f;
+  int arg_g = -1, arg_k = -1;
+  int k = 0;
+  while (k < s.n_chain) {
+    const int g = group[k];
+    float c_opt = INFINITY;
+    int k_opt = k;
+    const float B = batch[k];
+    for (; k < s.n_chain && group[k] == g; ++k) {
+      const float cst = s.tr_cost[(size_t)k * s.max_iter + s.n_iter[k] - 1];
+      if (cst < c_opt) { c_opt = cst; k_opt = k; }
+    }
+    if (c_opt == INFINITY) break;                          // out of memory: larger batches are not tried
+    const float tp = B / c_opt;
+    if (tp > tpt) { tpt = tp; arg_g = g; arg_k = k_opt; }
+  }
+  out[0] = tpt;
+  out[1] = __int_as_float(arg_g);
+  out[2] = __int_as_float(arg_k);
+}
+
 }  // namespace gbmw
 
 using gbmw_detail::fail;
@@ -325,6 +350,17 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
     }
   }
   if (sumP > 65535) return fail(GBMW_ERR_INVALID_ARG, "more than 65535 stages");
+  if ((q->batch_size == nullptr) != (q->batch_group == nullptr))
+    return fail(GBMW_ERR_INVALID_ARG, "batch_size and batch_group go together");
+  if (q->batch_size)
+    for (int k = 0; k < n; ++k) {
+      if (!(q->batch_size[k] > 0.0f) || !std::isfinite(q->batch_size[k]))
+        return fail(GBMW_ERR_INVALID_ARG, "batch_size[%d] must be positive", k);
+      if (k > 0 && q->batch_group[k] < q->batch_group[k - 1])
+        return fail(GBMW_ERR_INVALID_ARG, "batch_group must be non-decreasing (pair %d)", k);
+      if (k > 0 && q->batch_group[k] == q->batch_group[k - 1] && q->batch_size[k] != q->batch_size[k - 1])
+        return fail(GBMW_ERR_INVALID_ARG, "pairs of group %d differ in batch size", q->batch_group[k]);
+    }
   const size_t tr = (size_t)n * q->max_iter, trP = tr * Pmax;
   if (trP > ((size_t)1 << 28)) return fail(GBMW_ERR_INVALID_ARG, "trace too large (n_chain * max_iter * Pmax)");
   for (size_t i = 0; i < (size_t)sumLm * S; ++i) {
@@ -410,7 +446,8 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
   const size_t rows = (size_t)rows_total;
   float *gc = nullptr, *gR = nullptr;
   int *gM = nullptr, *g_src = nullptr, *g_msrc = nullptr, *g_dst = nullptr, *g_touched = nullptr,
-      *g_chain = nullptr, *g_first = nullptr;
+      *g_chain = nullptr, *g_first = nullptr, *g_group = nullptr;
+  float *g_batch = nullptr, *g_tpt = nullptr;
   auto carve_gather = [&](Carver& w) {
     gc = w.take<float>(rows * d.S);
     gM = w.take<int>(rows * d.S);
@@ -421,6 +458,9 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
     g_touched = w.take<int>(d.sumP);
     g_chain = w.take<int>(d.sumP);
     g_first = w.take<int>(d.sumP);
+    g_group = w.take<int>(d.n);
+    g_batch = w.take<float>(d.n);
+    g_tpt = w.take<float>(4);
     return w.used;
   };
   {
@@ -659,6 +699,17 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
     }
     if (!any) break;
   }
+  float h_tpt[3] = {0.0f, 0.0f, 0.0f};
+  if (q->batch_size) {
+    float* d_batch = g_batch;
+    int* d_group = g_group;
+    float* d_out = g_tpt;
+    HIP_TRY_B(hipMemcpyAsync(d_batch, q->batch_size, sizeof(float) * n, H2D, st));
+    HIP_TRY_B(hipMemcpyAsync(d_group, q->batch_group, sizeof(int) * n, H2D, st));
+    hipLaunchKernelGGL(gbmw::k_throughput, dim3(1), dim3(1), 0, st, s, d_batch, d_group, d_out);
+    HIP_TRY_B(hipGetLastError());
+    HIP_TRY_B(hipMemcpyAsync(h_tpt, d_out, sizeof(h_tpt), hipMemcpyDeviceToHost, st));
+  }
   HIP_TRY_B(hipEventRecord(ev1, st));
 
   // ---- results ------------------------------------------------------------
@@ -689,6 +740,13 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
   out->stage_solves = stage_solves;
   out->cell_updates = cell_updates;
   out->device_ms = ms;
+  out->tpt = h_tpt[0];
+  out->tpt_group = -1;
+  out->tpt_pair = -1;
+  if (q->batch_size) {
+    memcpy(&out->tpt_group, &h_tpt[1], sizeof(int));
+    memcpy(&out->tpt_pair, &h_tpt[2], sizeof(int));
+  }
   (void)hipEventDestroy(ev0);
   (void)hipEventDestroy(ev1);
 #undef TRY

@@ -134,3 +134,25 @@ def test_structured_models(g):
     res, ctx = _search(g, models, max_iter=12)
     check_partition_search(res, models, 12)
     g.gbmw_destroy(ctx)
+
+
+def test_outer_loops_throughput(g):
+    """Algorithm 2 end to end for three batch sizes x PP degrees 2 and 4: the pairs' values,
+    the best degree per batch size, the stop at the first batch size that fits nowhere, Tpt."""
+    import oracle.bmw as bmw
+    models, batch, group = [], [], []
+    for gi_, (B, act) in enumerate([(16.0, 0.5), (32.0, 1.0), (64.0, 40.0), (128.0, 1.5)]):
+        for P in (2, 4):
+            models.append(gi.structured_pipeline_model(300 + gi_, 16, P, 3000, m=4, act_scale=act, S=22))
+            batch.append(B); group.append(gi_)
+    a = pack_models(models)
+    res, ctx = g.gbmw_partition_search(a["P"], a["Lm"], a["m"], a["c"], a["c_nosync"], a["R"], a["M"], a["p0"],
+                                       a["p_t"], a["S"], a["E"], max_iter=8, batch_size=batch, batch_group=group)
+    check_partition_search(res, models, 8)
+    last = [res["cost"][k, res["n_iter"][k] - 1] for k in range(len(models))]
+    want, want_g = bmw.throughput([16.0, 32.0, 64.0, 128.0], [last[0:2], last[2:4], last[4:6], last[6:8]])
+    assert pins.bits(res["tpt"]) == pins.bits(want) and res["tpt_group"] == want_g
+    assert np.isinf(last[4]) and np.isinf(last[5]), "the third batch size must be out of memory"
+    assert np.isfinite(last[6]) or np.isfinite(last[7]), "... although the fourth would fit"
+    assert want_g in (0, 1) and res["tpt_pair"] == 2 * want_g + int(np.argmin(last[2 * want_g:2 * want_g + 2]))
+    g.gbmw_destroy(ctx)
