@@ -60,8 +60,16 @@ enum {
                                   priority that fork from and join back into p->stream
                                   with events, so the call is still ordered on p->stream
                                   as a whole                                             */
-  GBMW_FLAG_RESOLVE_ALL = 8u   /* gbmw_partition_search only: solve every stage of every
+  GBMW_FLAG_RESOLVE_ALL = 8u,  /* gbmw_partition_search only: solve every stage of every
                                   live pair in every round                               */
+  GBMW_FLAG_LAZY_ARGMIN = 16u  /* do not write the argmin records while the tables are
+                                  filled; keep every layer's fp32 table instead (implies
+                                  GBMW_FLAG_KEEP_ALL_C: 4 bytes per cell instead of 1) and
+                                  let gbmw_backtrack and the other plan walkers recompute
+                                  the one record they need per layer, with the same
+                                  arithmetic and tie rule, so every result is identical.
+                                  The fill then costs one add and half a three-input min
+                                  per candidate and nothing else                         */
 };
 
 #define GBMW_MAX_S 256

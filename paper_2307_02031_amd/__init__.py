@@ -27,6 +27,7 @@ GBMW_FLAG_KEEP_ALL_C = 1
 GBMW_FLAG_TIME_KERNELS = 2
 GBMW_FLAG_ONE_STREAM = 4
 GBMW_FLAG_RESOLVE_ALL = 8
+GBMW_FLAG_LAZY_ARGMIN = 16
 GBMW_MAX_S = 256
 
 EXPORTS = [

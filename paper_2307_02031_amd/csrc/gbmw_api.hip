@@ -145,7 +145,8 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
   if (p->E < 0 || p->E > (1 << 28)) return fail(GBMW_ERR_INVALID_ARG, "E=%d out of range", p->E);
   if (p->ptr_space != GBMW_PTR_HOST && p->ptr_space != GBMW_PTR_DEVICE)
     return fail(GBMW_ERR_INVALID_ARG, "ptr_space=%d", p->ptr_space);
-  if (flags & ~(uint32_t)(GBMW_FLAG_KEEP_ALL_C | GBMW_FLAG_TIME_KERNELS | GBMW_FLAG_ONE_STREAM))
+  if (flags & ~(uint32_t)(GBMW_FLAG_KEEP_ALL_C | GBMW_FLAG_TIME_KERNELS | GBMW_FLAG_ONE_STREAM |
+                          GBMW_FLAG_LAZY_ARGMIN))
     return fail(GBMW_ERR_INVALID_ARG, "unknown flag bits 0x%x", flags);
 
   const int B = p->B, S = p->S, E = p->E;
@@ -225,7 +226,8 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
   const bool same_layout = !fresh && c->index_on_device && c->L == L && c->off == off && c->perm == perm;
   c->L = L; c->off = off; c->perm = perm;
   const int SP = c->SP, EP = c->EP;
-  const bool keep = (flags & GBMW_FLAG_KEEP_ALL_C) != 0;
+  const bool lazy = (flags & GBMW_FLAG_LAZY_ARGMIN) != 0;
+  const bool keep = lazy || (flags & GBMW_FLAG_KEEP_ALL_C) != 0;
   const size_t slab = (size_t)S * EP;
 
   TRY(c->d_L.reserve(sizeof(int) * B));
@@ -235,7 +237,7 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
   const int RS = (SP + 2 + 3) / 4 * 4;
   TRY(c->d_Rt.reserve(sizeof(float) * (size_t)sumL * S * RS));
   TRY(c->d_C.reserve(sizeof(float) * slab * (keep ? (size_t)sumL : (size_t)2 * B)));
-  TRY(c->d_A.reserve(slab * (size_t)sumL));
+  if (!lazy) TRY(c->d_A.reserve(slab * (size_t)sumL));
   TRY(c->d_best.reserve(sizeof(float) * (size_t)B * EP));
   TRY(c->d_best_s.reserve((size_t)B * EP));
   if (!c->ev0) {
@@ -271,7 +273,7 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
   t.final_from = std::min(std::max(final_from, 0), E);
   t.L = (const int*)c->d_L.p; t.off = (const int*)c->d_off.p; t.perm = (const int*)c->d_perm.p;
   t.c = dc; t.M = dM; t.Rt = (const float*)c->d_Rt.p;
-  t.Cbuf = (float*)c->d_C.p; t.A = (uint8_t*)c->d_A.p;
+  t.Cbuf = (float*)c->d_C.p; t.A = lazy ? nullptr : (uint8_t*)c->d_A.p;
   t.best = (float*)c->d_best.p; t.best_s = (uint8_t*)c->d_best_s.p;
   t.status = (int*)c->d_status.p;
 
@@ -508,7 +510,8 @@ gbmw_status gbmw_export_tables(gbmw_ctx* c, int32_t inst, int32_t l0, int32_t l1
   const int Lb = c->L[inst];
   if (l0 < 0 || l1 > Lb || l0 > l1) return fail(GBMW_ERR_INVALID_ARG, "layers [%d,%d) of %d", l0, l1, Lb);
   if (l0 == l1) return GBMW_OK;
-  const bool keep = (c->flags & GBMW_FLAG_KEEP_ALL_C) != 0;
+  const bool lazy = (c->flags & GBMW_FLAG_LAZY_ARGMIN) != 0;
+  const bool keep = lazy || (c->flags & GBMW_FLAG_KEEP_ALL_C) != 0;
   if (C && !keep && l0 < Lb - 2)
     return fail(GBMW_ERR_UNSUPPORTED, "only the last two layers of C were kept (asked for layer %d of %d)", l0, Lb);
   const size_t rows = (size_t)c->E + 1, S = (size_t)c->S, slab = S * c->EP;
@@ -531,8 +534,14 @@ gbmw_status gbmw_export_tables(gbmw_ctx* c, int32_t inst, int32_t l0, int32_t l1
       if (l == 0) {
         memset(dst, 0, rows * S);
       } else {
-        gbmw::launch_export_u8((const uint8_t*)c->d_A.p + (size_t)(row0 + l) * slab,
-                               (uint8_t*)c->d_stage.p, 1, c->S, c->E, c->EP, c->stream);
+        const uint8_t* src = (const uint8_t*)c->d_A.p + (size_t)(row0 + l) * slab;
+        if (lazy) {                                      // the records of this row, recomputed
+          st = c->d_q.reserve(slab);
+          if (st != GBMW_OK) return st;
+          gbmw::launch_argmin_row(c->t, row0 + l, (uint8_t*)c->d_q.p, c->stream);
+          src = (const uint8_t*)c->d_q.p;
+        }
+        gbmw::launch_export_u8(src, (uint8_t*)c->d_stage.p, 1, c->S, c->E, c->EP, c->stream);
         HIP_TRY(hipGetLastError());
         HIP_TRY(hipMemcpyAsync(dst, c->d_stage.p, rows * S, hipMemcpyDeviceToHost, c->stream));
         HIP_TRY(hipStreamSynchronize(c->stream));

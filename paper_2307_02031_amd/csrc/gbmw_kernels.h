@@ -30,11 +30,31 @@ struct Tables {
   const int* M;        // [sumL][S]
   const float* Rt;     // [sumL][S][RS]
   float* Cbuf;         // keep_all ? [sumL][S][EP] : [2][B][S][EP]
-  uint8_t* A;          // [sumL][S][EP]
+  uint8_t* A;          // [sumL][S][EP]; null: records are not kept (needs keep_all), the
+                       // walkers recompute the one they need from the kept tables
   float* best;         // [B][EP]
   uint8_t* best_s;     // [B][EP]
   int* status;         // device word; bit 0: bad c, bit 1: bad M, bit 2: bad R
 };
+
+#if defined(__HIPCC__)
+// Predecessor strategy of table row `row` (layer l >= 1 of some instance) under strategy s
+// when e units are left for the layers below: the recorded one, or, where records are not
+// kept, recomputed from the kept table of layer l - 1 with the recurrence's own arithmetic
+// ((C + R), lowest index among equals, 0 if every candidate is +inf).
+__device__ __forceinline__ int pred_strategy(const Tables& t, int row, int s, int e) {
+  if (t.A) return t.A[((size_t)row * t.S + s) * t.EP + e];
+  const float* __restrict__ Cp = t.Cbuf + (size_t)(row - 1) * t.S * t.EP + e;
+  const float* __restrict__ Rr = t.Rt + ((size_t)row * t.S + s) * t.RS;
+  float best = INFINITY;
+  int a = 0;
+  for (int sp = 0; sp < t.S; ++sp) {
+    const float x = Cp[(size_t)sp * t.EP] + Rr[sp];
+    if (x < best) { best = x; a = sp; }
+  }
+  return a;
+}
+#endif
 
 // R -> Rt (transpose + pad) and validation of device-resident inputs.
 void launch_prepare(const Tables& t, const float* R, int sumL, bool validate, hipStream_t st);
@@ -68,6 +88,8 @@ void launch_pipeline_cost(const Tables& t, int n_stage, const int* st_inst, cons
 // [S][EP] -> [E+1][S] for rows [row0, row0+n) of C (fp32; base pointer given) or A (bytes).
 void launch_export_f32(const float* src, float* dst, int n, int S, int E, int EP, hipStream_t st);
 void launch_export_u8(const uint8_t* src, uint8_t* dst, int n, int S, int E, int EP, hipStream_t st);
+// The argmin records of one table row, [S][EP] bytes, recomputed from the kept tables.
+void launch_argmin_row(const Tables& t, int row, uint8_t* dst, hipStream_t st);
 
 const char* minplus_variant(int S);
 

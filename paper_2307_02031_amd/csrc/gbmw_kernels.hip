@@ -130,7 +130,7 @@ __device__ __forceinline__ float fmin3(float a, float b, float c) {
   return __builtin_fminf(__builtin_fminf(a, b), c);
 }
 
-template <int SP, int K, int NW, int CH, int MINW, bool SAVE_X, bool FIRST>
+template <int SP, int K, int NW, int CH, int MINW, bool SAVE_X, bool FIRST, bool ARG>
 __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int tiles, int first,
                                                            int split) {
   constexpr int NC = (SP + CH - 1) / CH;                 // chunks (last may be short)
@@ -162,7 +162,7 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
   const int s_end = split ? ((wave + 1) * S) / NW : S;
   const float* __restrict__ Cp = c_table(t, inst, row - 1, l - 1);
   float* __restrict__ Cn = c_table(t, inst, row, l);
-  uint8_t* __restrict__ An = t.A + (size_t)row * S * EP;
+  uint8_t* __restrict__ An = ARG ? t.A + (size_t)row * S * EP : nullptr;
   const int e0 = wbase + lane;
 
   // EP is a multiple of 64*K and wbase <= E < EP, so rows e0 + 64*j < EP are
@@ -192,6 +192,42 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
       for (int j = 0; j < K; ++j)
         cp[j][sp] = (sp < SP - 3 || sp < S) ? Cp[(size_t)sp * EP + e0 + 64 * j] : INFINITY;
     }
+  }
+
+  if (!ARG) {
+    // Values only: the argmin records are not materialised (the walkers recompute the
+    // one record they need per layer from the kept tables).  One add and half a
+    // three-input min per candidate; the R row is consumed quad by quad as it arrives.
+    static_assert(K == 1 || ARG, "the values-only path handles one budget per lane");
+    for (int s = s_begin; s < s_end; ++s) {
+      float acc = INFINITY, cs = 0.0f;
+      int m_raw = 0;
+#pragma unroll
+      for (int q = 0; q < RQ; ++q) {
+        const float4 v = rt_lds[s * RQ + q];
+        const float rq[4] = {v.x, v.y, v.z, v.w};
+        float xq[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) xq[i] = (4 * q + i < SP) ? cp[0][(4 * q + i < SP) ? 4 * q + i : 0] + rq[i] : INFINITY;
+        if (4 * q + 3 < SP) {
+          acc = fmin3(acc, xq[0], xq[1]);
+          acc = fmin3(acc, xq[2], xq[3]);
+        }
+        // SP is a multiple of 4: c(l,s) and M(l,s) sit in the quad after the last candidates
+        if (4 * q == SP) {
+          cs = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(rq[0])));
+          m_raw = __builtin_amdgcn_readfirstlane(__float_as_int(rq[1]));
+        }
+      }
+      const int m = (m_raw < 0 || m_raw > E + 1) ? E + 1 : m_raw;
+      float* Cs = Cn + (size_t)s * EP;
+      const __amdgpu_buffer_rsrc_t bc = __builtin_amdgcn_make_buffer_rsrc(Cs, 0, (E + 1) * 4, kBufWord3);
+      const __amdgpu_buffer_rsrc_t binf = __builtin_amdgcn_make_buffer_rsrc(Cs, 0, m * 4, kBufWord3);
+      __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc + cs), bc, (e0 + m) * 4, 0, 0);
+      if (wbase < m)                                       // wave-uniform: some lane is below M
+        __builtin_amdgcn_raw_buffer_store_b32(0x7f800000u, binf, e0 * 4, 0, 0);
+    }
+    return;
   }
 
   for (int s = s_begin; s < s_end; ++s) {
@@ -300,7 +336,7 @@ __global__ __launch_bounds__(256) void k_minplus_generic(Tables t, int l, int ti
   const int row = t.off[inst] + l;
   const float* __restrict__ Cp = c_table(t, inst, row - 1, l - 1);
   float* __restrict__ Cn = c_table(t, inst, row, l);
-  uint8_t* __restrict__ An = t.A + (size_t)row * S * EP;
+  uint8_t* __restrict__ An = t.A ? t.A + (size_t)row * S * EP : nullptr;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int e = tile * 64 + lane;
 
@@ -319,7 +355,7 @@ __global__ __launch_bounds__(256) void k_minplus_generic(Tables t, int l, int ti
     const int m = t.M[(size_t)row * S + s];
     const float cs = t.c[(size_t)row * S + s];
     if (e <= E) {
-      An[(size_t)s * EP + e] = (uint8_t)arg;
+      if (An) An[(size_t)s * EP + e] = (uint8_t)arg;
       if (m >= 0 && m <= E - e) Cn[(size_t)s * EP + e + m] = tmin + cs;
       if (m < 0 || e < m) Cn[(size_t)s * EP + e] = INFINITY;
     }
@@ -337,6 +373,8 @@ struct Blocking {                       // budgets per lane for a given strategy
   // it only pays where dropping them would not buy another wave per SIMD.
   static constexpr bool SAVE_X = (SP >= 60);
   static constexpr int MINW = (SP <= 24) ? 8 : (SP <= 32) ? 7 : (SP <= 36) ? 6 : (SP <= 44) ? 5 : (SP <= 56) ? 4 : 3;
+  // without the argmin pass: the SP table values plus about 16 working registers
+  static constexpr int MINW_VALUES = (SP <= 44) ? 8 : (SP <= 52) ? 7 : (SP <= 60) ? 6 : 5;
 };
 
 template <int SP>
@@ -349,12 +387,19 @@ static void launch_minplus_sp(const Tables& t, int l, int first, int n_active, h
   const int split = ((long long)tiles * n_active < 1024) ? 1 : 0;
   if (split) tiles = (t.E + 1 + 64 * K - 1) / (64 * K);
   constexpr int RS = (SP + 2 + 3) / 4 * 4;
-  if (l == 1)
-    hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, MINW, SAVE_X, true>), dim3((unsigned)tiles * n_active),
-                       dim3(64 * NW), (size_t)t.S * RS * sizeof(float), st, t, l, tiles, first, split);
-  else
-    hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, MINW, SAVE_X, false>), dim3((unsigned)tiles * n_active),
-                       dim3(64 * NW), (size_t)t.S * RS * sizeof(float), st, t, l, tiles, first, split);
+  const dim3 grid((unsigned)tiles * n_active), block(64 * NW);
+  const size_t lds = (size_t)t.S * RS * sizeof(float);
+  if (t.A == nullptr) {
+    constexpr int MW = Blocking<SP>::MINW_VALUES;
+    if (l == 1)
+      hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, MW, false, true, false>), grid, block, lds, st, t, l, tiles, first, split);
+    else
+      hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, MW, false, false, false>), grid, block, lds, st, t, l, tiles, first, split);
+  } else if (l == 1) {
+    hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, MINW, SAVE_X, true, true>), grid, block, lds, st, t, l, tiles, first, split);
+  } else {
+    hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, MINW, SAVE_X, false, true>), grid, block, lds, st, t, l, tiles, first, split);
+  }
 }
 
 void launch_minplus(const Tables& t, int l, int first, int n_active, hipStream_t st) {
@@ -435,7 +480,7 @@ __global__ __launch_bounds__(64) void k_backtrack(Tables t, int nq, const int* _
     mem += m;
     e -= m;                                            // budget left for layers < l
     if (m < 0 || e < 0) { mem = -2; break; }           // only reachable with invalid inputs
-    s = t.A[((size_t)(row0 + l) * t.S + s) * t.EP + e];
+    s = pred_strategy(t, row0 + l, s, e);
   }
   if (mem != -2) {
     p[0] = (uint8_t)s;
@@ -475,7 +520,7 @@ __device__ long long walk_plan(const Tables& t, int inst, int e, const int* __re
       const int m = t.M[cell];
       e -= m;                                            // budget left for layers < l
       if (m < 0 || e < 0) return -2;                     // only reachable with invalid inputs
-      s = t.A[((size_t)(row0 + l) * S + s) * t.EP + e];
+      s = pred_strategy(t, row0 + l, s, e);
     }
   }
   return suf + mx + ms;
@@ -575,7 +620,7 @@ __global__ __launch_bounds__(64) void k_stage_cost(Tables t, int n_stage,
         plan[l] = (uint8_t)s;
         e -= t.M[(size_t)(row0 + l) * S + s];
         if (e < 0) { ok = false; break; }                // only reachable with invalid inputs
-        s = t.A[((size_t)(row0 + l) * S + s) * t.EP + e];
+        s = pred_strategy(t, row0 + l, s, e);
       }
       if (ok) {
         plan[0] = (uint8_t)s;
@@ -646,6 +691,16 @@ __global__ __launch_bounds__(256) void k_export(const T* __restrict__ src, T* __
     const int e = e0 + i, s = s0 + tx;
     if (s < S && e <= E) out[(size_t)e * S + s] = tile[tx][i];
   }
+}
+
+__global__ __launch_bounds__(256) void k_argmin_row(Tables t, int row, uint8_t* __restrict__ dst) {
+  const int e = blockIdx.x * 256 + threadIdx.x, s = blockIdx.y;
+  if (e >= t.EP) return;
+  dst[(size_t)s * t.EP + e] = (e <= t.E) ? (uint8_t)pred_strategy(t, row, s, e) : 0;
+}
+
+void launch_argmin_row(const Tables& t, int row, uint8_t* dst, hipStream_t st) {
+  hipLaunchKernelGGL(k_argmin_row, dim3(t.EP / 256, t.S), dim3(256), 0, st, t, row, dst);
 }
 
 void launch_export_f32(const float* src, float* dst, int n, int S, int E, int EP, hipStream_t st) {

@@ -93,7 +93,7 @@ __global__ __launch_bounds__(64) void k_stage_result(Tables t, Search s,
       mem += m;
       e -= m;                                            // budget left for layers < l
       if (m < 0 || e < 0) { C = INFINITY; break; }       // only reachable with invalid inputs
-      sx = t.A[((size_t)(row0 + l) * S + sx) * t.EP + e];
+      sx = pred_strategy(t, row0 + l, sx, e);
     }
     if (C != INFINITY) {
       st[0] = (uint8_t)sx;
@@ -322,7 +322,8 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
   if (q->S < 1 || q->S > GBMW_MAX_S) return fail(GBMW_ERR_INVALID_ARG, "S=%d not in 1..256", q->S);
   if (q->E < 0 || q->E > (1 << 28)) return fail(GBMW_ERR_INVALID_ARG, "E=%d out of range", q->E);
   if (q->max_iter < 1 || q->max_iter > 4096) return fail(GBMW_ERR_INVALID_ARG, "max_iter=%d not in 1..4096", q->max_iter);
-  if (flags & ~(uint32_t)GBMW_FLAG_RESOLVE_ALL) return fail(GBMW_ERR_INVALID_ARG, "unknown flag bits 0x%x", flags);
+  if (flags & ~(uint32_t)(GBMW_FLAG_RESOLVE_ALL | GBMW_FLAG_LAZY_ARGMIN))
+    return fail(GBMW_ERR_INVALID_ARG, "unknown flag bits 0x%x", flags);
 
   const int n = q->n_chain, S = q->S, E = q->E;
   std::vector<int> lrow(n), prow(n), mrow(n);
@@ -474,18 +475,25 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
   TRY(c->d_perm.reserve(sizeof(int) * B));
   TRY(c->d_status.reserve(sizeof(int)));
   TRY(c->d_Rt.reserve(sizeof(float) * rows * S * RS));
-  TRY(c->d_C.reserve(sizeof(float) * slab * 2 * B));
-  TRY(c->d_A.reserve(slab * rows));
+  // with argmin records: a rolling pair of fp32 layer tables per slot and one byte per cell of
+  // every layer; without: the fp32 tables of all layers
+  const bool lazy = (flags & GBMW_FLAG_LAZY_ARGMIN) != 0;
+  if (lazy) {
+    TRY(c->d_C.reserve(sizeof(float) * slab * rows));
+  } else {
+    TRY(c->d_C.reserve(sizeof(float) * slab * 2 * B));
+    TRY(c->d_A.reserve(slab * rows));
+  }
   TRY(c->d_best.reserve(sizeof(float) * (size_t)B * EP));
   TRY(c->d_best_s.reserve((size_t)B * EP));
   constexpr int kFreshGroups = 2;
   TRY(gbmw_detail::ensure_streams(c, kFreshGroups));
 
   gbmw::Tables& t = c->t;
-  t.B = B; t.S = S; t.SP = SP; t.RS = RS; t.E = E; t.EP = EP; t.keep_all = 0; t.final_from = E;
+  t.B = B; t.S = S; t.SP = SP; t.RS = RS; t.E = E; t.EP = EP; t.keep_all = lazy ? 1 : 0; t.final_from = E;
   t.L = (const int*)c->d_L.p; t.off = (const int*)c->d_off.p; t.perm = (const int*)c->d_perm.p;
   t.c = gc; t.M = gM; t.Rt = (const float*)c->d_Rt.p;
-  t.Cbuf = (float*)c->d_C.p; t.A = (uint8_t*)c->d_A.p;
+  t.Cbuf = (float*)c->d_C.p; t.A = lazy ? nullptr : (uint8_t*)c->d_A.p;
   t.best = (float*)c->d_best.p; t.best_s = (uint8_t*)c->d_best_s.p;
   t.status = (int*)c->d_status.p;
 
@@ -551,13 +559,14 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
         // was written to memory (stages of one or two layers, or S > 64)
         c_hi[b] = L - 1;
         c_lo[b] = (L >= 2 && (L - 2 >= 1 || L <= 2 || !l0_in_regs)) ? L - 2 : -1;
+        if (lazy) c_lo[b] = 0;                       // every layer's table is kept: [c_lo, c_hi]
       } else if (mode[b] == kAppend) {
         append.push_back(b);
         h_src.push_back(lrow[k] + slot_first[b] + L - 1);
         h_msrc.push_back(mrow[k] + i * q->Lm[k] + slot_first[b] + L - 1);
         h_dst.push_back(off[b] + L - 1);
         cell_updates += (long long)(E + 1) * S * S;
-        c_lo[b] = L - 2;
+        if (!lazy) c_lo[b] = L - 2;
         c_hi[b] = L - 1;
       } else {
         final_only.push_back(b);
@@ -601,7 +610,7 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
     // layer 0 goes to memory where something reads it from there
     for (int g = 0; g < G; ++g) {
       int n_init = gfirst[g + 1] - gfirst[g];
-      if (l0_in_regs) {
+      if (l0_in_regs && !lazy) {
         n_init = 0;
         for (int x = gfirst[g + 1] - 1; x >= gfirst[g] && slotL[h_perm[x]] <= 2; --x) ++n_init;
       }
@@ -665,6 +674,10 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
   for (int k = 0; k < n; ++k) part[k].assign(q->p0 + prow[k], q->p0 + prow[k] + q->P[k]);
   all_fresh();
   const bool resolve_all = (flags & GBMW_FLAG_RESOLVE_ALL) != 0;
+  // is the fp32 table of layer `layer` of slot b still in memory?
+  auto in_memory = [&](int b, int layer) {
+    return lazy ? (c_lo[b] <= layer && layer <= c_hi[b]) : (layer == c_hi[b] || layer == c_lo[b]);
+  };
   for (int it = 0; it < q->max_iter; ++it) {
     TRY(run_round(1));
     std::fill(mode.begin(), mode.end(), (int)kSkip);
@@ -687,12 +700,12 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
       } else if (j == i - 1) {
         // the earlier stage takes the first layer of stage i: one more step at its end
         const int need = slotL[bj] - 2;              // the table the new last layer is computed from
-        mode[bj] = (need == c_hi[bj] || need == c_lo[bj]) ? kAppend : kFresh;
+        mode[bj] = in_memory(bj, need) ? kAppend : kFresh;
         mode[bi] = kFresh;
       } else {
         // the later stage takes the last layer of stage i: stage i's table is a prefix of itself
         const int need = slotL[bi] - 1;
-        mode[bi] = (need == c_hi[bi] || need == c_lo[bi]) ? kFinalOnly : kFresh;
+        mode[bi] = in_memory(bi, need) ? kFinalOnly : kFresh;
         mode[bj] = kFresh;
       }
       if (j == i - 1) slot_first[bi] += 1; else slot_first[bj] -= 1;

@@ -54,10 +54,11 @@ def test_worked_example(g):
 @pytest.mark.parametrize("S,E,Ls,Mhi", [(4, 120, [4, 2, 6, 1], 30), (7, 300, [5, 3], 60), (22, 1000, [6, 9, 3], 200),
                                         (44, 2500, [8, 5], 400), (64, 900, [4, 6], 150), (70, 400, [3, 4], 100),
                                         (3, 10, [4, 3], 12)])
-def test_batches_against_the_oracle(g, S, E, Ls, Mhi):
+@pytest.mark.parametrize("lazy", [False, True], ids=["records", "lazy-argmin"])
+def test_batches_against_the_oracle(g, S, E, Ls, Mhi, lazy):
     parts = [gi.random_instance(2000 + 13 * S + i, L, S, E, M_rng=(1, Mhi)) for i, L in enumerate(Ls)]
     p = gi.stack(parts, f"alg3-S{S}")
-    ctx = solve_gpu(p, device_inputs=True)
+    ctx = solve_gpu(p, flags=g.GBMW_FLAG_LAZY_ARGMIN if lazy else 0, device_inputs=True)
     for variant in range(5):
         Of, Ob, Oms = gi.split_memory(p, 3000 + variant)
         if variant == 1:

@@ -73,21 +73,24 @@ SHAPES = [  # (S, E, list of L): ragged tails, tile boundaries, every kernel var
 
 
 @pytest.mark.parametrize("S,E,Ls", SHAPES, ids=[f"S{s}-E{e}" for s, e, _ in SHAPES])
-@pytest.mark.parametrize("device_inputs", [False, True], ids=["host", "device"])
-def test_ragged_batches_all_shapes(g, S, E, Ls, device_inputs):
-    _log(f"S={S} E={E} L={Ls} device_inputs={device_inputs}")
+@pytest.mark.parametrize("device_inputs,lazy", [(False, False), (True, False), (True, True)],
+                         ids=["host", "device", "device-lazy-argmin"])
+def test_ragged_batches_all_shapes(g, S, E, Ls, device_inputs, lazy):
+    _log(f"S={S} E={E} L={Ls} device_inputs={device_inputs} lazy={lazy}")
     Mhi = max(2, E // 3 + 1)
     parts = [gi.random_instance(1000 + 17 * S + i, L, S, E, M_rng=(0 if E == 0 else 1, Mhi),
                                 R_rng=(0.0, 4.0)) for i, L in enumerate(Ls)]
     p = gi.stack(parts, f"S{S}E{E}")
-    ctx = solve_gpu(p, flags=g.GBMW_FLAG_KEEP_ALL_C, device_inputs=device_inputs)
+    ctx = solve_gpu(p, flags=g.GBMW_FLAG_LAZY_ARGMIN if lazy else g.GBMW_FLAG_KEEP_ALL_C,
+                    device_inputs=device_inputs)
     for b in range(p.B):
         check_instance(g, ctx, p, b, full_C=True, q_es=list(range(0, E + 1, max(1, E // 40))) + [E])
     g.gbmw_destroy(ctx)
 
 
+@pytest.mark.parametrize("lazy", [False, True], ids=["records", "lazy-argmin"])
 @pytest.mark.parametrize("S", [3, 7, 11, 15, 19, 23, 26, 30, 34, 39, 43, 47, 51, 54, 59, 62])
-def test_wide_launches_every_instantiation(g, S):
+def test_wide_launches_every_instantiation(g, S, lazy):
     """Launches of 1024 workgroups and more take the kernel's other path (each wave owns
     its own 64 budgets instead of sharing a tile with the other waves of its workgroup):
     ten instances of E = 32805 for every register-blocked instantiation, with
@@ -102,7 +105,7 @@ def test_wide_launches_every_instantiation(g, S):
         R = st.integers(L * S * S, 0, 2).astype(np.float32).reshape(L, S, S)
         parts.append(gi.Problem(1, S, E, np.array([L]), c, M, R))
     p = gi.stack(parts, f"wide-S{S}")
-    ctx = solve_gpu(p, device_inputs=True)
+    ctx = solve_gpu(p, flags=g.GBMW_FLAG_LAZY_ARGMIN if lazy else 0, device_inputs=True)
     best, best_s = g.gbmw_get_best(ctx)
     for b in (0, 4, 9):
         check_instance(g, ctx, p, b, full_C=False, q_es=[0, 1, E // 2, E - 1, E], best=best, best_s=best_s)
@@ -219,6 +222,21 @@ def test_config4_batched_full_size(g):
     for b in range(p.B):
         _log(f"cfg4 instance {b} L={p.L[b]}")
         check_instance(g, ctx, p, b, full_C=False, best=best, best_s=best_s)
+    g.gbmw_destroy(ctx)
+
+
+def test_config4_lazy_argmin_full_size(g):
+    """The same batch without argmin records: tables, recomputed records, best and plans
+    of every seventh instance against the oracle, plan properties for all."""
+    p = gi.make_config(4)
+    ctx = solve_gpu(p, flags=g.GBMW_FLAG_LAZY_ARGMIN, device_inputs=True)
+    best, best_s = g.gbmw_get_best(ctx)
+    for b in range(0, p.B, 7):
+        _log(f"cfg4 lazy instance {b} L={p.L[b]}")
+        check_instance(g, ctx, p, b, full_C=False, best=best, best_s=best_s)
+    q = sorted(set(list(range(0, p.E + 1, 1013)) + [p.E, p.E - 1]))
+    for b in range(p.B):
+        check_plans_by_definition(g, ctx, p, b, q, best)
     g.gbmw_destroy(ctx)
 
 

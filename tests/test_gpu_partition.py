@@ -44,7 +44,7 @@ def test_worked_example(g):
         g.gbmw_destroy(ctx)
 
 
-@pytest.mark.parametrize("flags", [0, 8], ids=["changed-stages", "resolve-all"])
+@pytest.mark.parametrize("flags", [0, 8, 16, 24], ids=["changed-stages", "resolve-all", "lazy-argmin", "lazy-resolve-all"])
 def test_uniform_models(g, flags):
     """Closed-form models (S = 1): neighbour choice, ties, the searched-before
     rule, memory limits, an infeasible start, single-stage and one-layer-per-stage
@@ -65,7 +65,7 @@ def test_uniform_models(g, flags):
     g.gbmw_destroy(ctx)
 
 
-@pytest.mark.parametrize("flags", [0, 8], ids=["changed-stages", "resolve-all"])
+@pytest.mark.parametrize("flags", [0, 8, 16], ids=["changed-stages", "resolve-all", "lazy-argmin"])
 @pytest.mark.parametrize("S,E,with_pt", [(3, 60, True), (5, 90, False), (22, 400, True), (44, 700, True),
                                          (70, 500, False)])
 def test_random_models(g, S, E, with_pt, flags):
@@ -96,6 +96,10 @@ def test_kept_tables_are_extended_not_recomputed(g):
     assert res["cell_updates"] == (8 + 8 + 7 + 6 + 5) * 1001 and res["stage_solves"] == 2 * 5
     res, ctx = _search(g, [two], flags=g.GBMW_FLAG_RESOLVE_ALL, ctx=ctx)
     assert res["cell_updates"] == 5 * 8 * 1001
+    # without argmin records every layer's table is kept, so a stage may lose its last layer
+    # any number of times in a row for free: [2,2,8] -> [2,3,7] -> ... costs 7 + (1 + 6) + (1 + 5) + ...
+    res, ctx = _search(g, [two], flags=g.GBMW_FLAG_LAZY_ARGMIN, ctx=ctx)
+    assert res["cell_updates"] == (8 + 8 + 7 + 6 + 5) * 1001
     three = gi.uniform_pipeline_model(10, 3, 1000, [2, 6, 2])
     res, ctx = _search(g, [three], ctx=ctx)
     assert [list(x) for x in res["p"][0, :4]] == [[2, 6, 2], [3, 5, 2], [3, 4, 3], [4, 3, 3]]
@@ -127,11 +131,12 @@ def test_changed_stage_reuse_solves_less_and_agrees(g):
     g.gbmw_destroy(ctx)
 
 
-def test_structured_models(g):
+@pytest.mark.parametrize("flags", [0, 16], ids=["records", "lazy-argmin"])
+def test_structured_models(g, flags):
     """Paper-shaped pairs: 44 strategies, 24-32 layers, PP degrees 2, 4 and 8."""
     models = [gi.structured_pipeline_model(70 + k, Lm, P, 3072, m=8)
               for k, (Lm, P) in enumerate([(24, 2), (24, 4), (32, 4), (32, 8)])]
-    res, ctx = _search(g, models, max_iter=12)
+    res, ctx = _search(g, models, max_iter=12, flags=flags)
     check_partition_search(res, models, 12)
     g.gbmw_destroy(ctx)
 

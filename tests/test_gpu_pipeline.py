@@ -51,10 +51,11 @@ def test_worked_example(g):
 
 @pytest.mark.parametrize("S,E,Ls", [(5, 200, [4, 6, 3, 5, 2, 7, 1, 4]), (22, 900, [6, 6, 5, 7]),
                                     (44, 1500, [3, 4, 5, 6, 2, 8]), (70, 300, [3, 4, 2])])
-def test_random_pipelines_against_the_oracle(g, S, E, Ls):
+@pytest.mark.parametrize("lazy", [False, True], ids=["records", "lazy-argmin"])
+def test_random_pipelines_against_the_oracle(g, S, E, Ls, lazy):
     parts = [gi.random_instance(4000 + 7 * S + i, L, S, E, M_rng=(1, max(2, E // 8))) for i, L in enumerate(Ls)]
     p = gi.stack(parts, f"pipe-S{S}")
-    ctx = solve_gpu(p, device_inputs=True)
+    ctx = solve_gpu(p, flags=g.GBMW_FLAG_LAZY_ARGMIN if lazy else 0, device_inputs=True)
     refs = [oracle.solve_problem(p, b, keep_C=False) for b in range(p.B)]
     st = gi.Stream(5000 + S)
     c_ns = (p.c * st.uniform(p.c.size, 0.3, 1.0).reshape(p.c.shape)).astype(np.float32)
