@@ -54,6 +54,27 @@ __device__ __forceinline__ int pred_strategy(const Tables& t, int row, int s, in
   }
   return a;
 }
+
+// The same for a whole wave walking ONE plan (all 64 lanes hold the same row, s, e and get
+// the same answer): without records the lanes take the candidates s' = lane, lane + 64, ...
+// and the minimum with its lowest index is found by a butterfly over the wave.
+__device__ __forceinline__ int pred_strategy_wave(const Tables& t, int row, int s, int e, int lane) {
+  if (t.A) return t.A[((size_t)row * t.S + s) * t.EP + e];
+  const float* __restrict__ Cp = t.Cbuf + (size_t)(row - 1) * t.S * t.EP + e;
+  const float* __restrict__ Rr = t.Rt + ((size_t)row * t.S + s) * t.RS;
+  float best = INFINITY;
+  int a = 0x7fffffff;
+  for (int sp = lane; sp < t.S; sp += 64) {
+    const float x = Cp[(size_t)sp * t.EP] + Rr[sp];
+    if (x < best) { best = x; a = sp; }
+  }
+  for (int d = 32; d >= 1; d >>= 1) {
+    const float ob = __shfl_xor(best, d, 64);
+    const int oa = __shfl_xor(a, d, 64);
+    if (ob < best || (ob == best && oa < a)) { best = ob; a = oa; }
+  }
+  return best == INFINITY ? 0 : a;
+}
 #endif
 
 // R -> Rt (transpose + pad) and validation of device-resident inputs.

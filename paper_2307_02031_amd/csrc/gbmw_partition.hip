@@ -68,16 +68,16 @@ __global__ __launch_bounds__(256) void k_gather(const float* __restrict__ c,
   for (int i = threadIdx.x; i < SS; i += 256) R_g[dst * SS + i] = R[src * SS + i];
 }
 
-// One lane per solved stage: walk its plan at e = E down the argmin records,
+// One wave per solved stage: walk its plan at e = E down the argmin records (every lane
+// walks the same plan; without records the lanes share each step's recomputation),
 // leave the strategies in the model-wide array, the stage's time, memory and
 // time without gradient synchronisation in the pair's stage slots.
 __global__ __launch_bounds__(64) void k_stage_result(Tables t, Search s,
                                                      const int* __restrict__ touched, int nt,
                                                      const int* __restrict__ slot_chain,
                                                      const int* __restrict__ slot_first) {
-  const int q = blockIdx.x * 64 + threadIdx.x;
-  if (q >= nt) return;
-  const int b = touched[q];                                // slot = instance of the table solve
+  const int lane = threadIdx.x;
+  const int b = touched[blockIdx.x];                       // slot = instance of the table solve
   const int k = slot_chain[b], a = slot_first[b], n = t.L[b], S = t.S;
   const size_t lrow = (size_t)s.lrow[k] + a;
   const int slot = b;
@@ -93,7 +93,7 @@ __global__ __launch_bounds__(64) void k_stage_result(Tables t, Search s,
       mem += m;
       e -= m;                                            // budget left for layers < l
       if (m < 0 || e < 0) { C = INFINITY; break; }       // only reachable with invalid inputs
-      sx = pred_strategy(t, row0 + l, sx, e);
+      sx = pred_strategy_wave(t, row0 + l, sx, e, lane);
     }
     if (C != INFINITY) {
       st[0] = (uint8_t)sx;
@@ -644,7 +644,7 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
         HIP_TRY(hipStreamWaitEvent(st, c->ev_join[g - 1], 0));
       }
     }
-    hipLaunchKernelGGL(gbmw::k_stage_result, dim3((nt + 63) / 64), dim3(64), 0, st, t, s, g_touched, nt,
+    hipLaunchKernelGGL(gbmw::k_stage_result, dim3(nt), dim3(64), 0, st, t, s, g_touched, nt,
                        g_chain, g_first);
     hipLaunchKernelGGL(gbmw::k_chain_step, dim3((n + 63) / 64), dim3(64), 0, st, s, phase);
     HIP_TRY(hipGetLastError());
