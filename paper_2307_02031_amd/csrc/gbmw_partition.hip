@@ -124,19 +124,19 @@ __global__ __launch_bounds__(64) void k_stage_result(Tables t, Search s,
   s.stO[slot] = mem;
 }
 
-// One lane per pair.  phase 0: the searched partition was p_t, keep its largest
-// stage memory as limit 3.  phase 1: trace entry for the searched partition,
-// then adjust and validate; the accepted partition replaces s.part.
+// One wave per pair; lane i works on stage i (P <= 64).  phase 0: the searched partition
+// was p_t, keep its largest stage memory as limit 3.  phase 1: trace entry for the searched
+// partition, then adjust and validate; the accepted partition replaces s.part.
 __global__ __launch_bounds__(64) void k_chain_step(Search s, int phase) {
-  const int k = blockIdx.x * 64 + threadIdx.x;
-  if (k >= s.n_chain) return;
+  const int k = blockIdx.x, lane = threadIdx.x;
   if (phase == 1 && !s.live[k]) return;
   const int P = s.P[k], pr = s.prow[k], S = s.S;
   const float* C = s.stC + pr;
   const float* Cns = s.stCns + pr;
   const int* O = s.stO + pr;
 
-  // Eq. 8 and the slowest stage (lowest index among equals)
+  // Eq. 8 and the slowest stage (lowest index among equals): a left fold in stage order,
+  // done by every lane alike
   float total = C[0], mx = Cns[0], cmax = C[0];
   int imax = 0, omax = O[0];
   long long osum = O[0];
@@ -154,7 +154,7 @@ __global__ __launch_bounds__(64) void k_chain_step(Search s, int phase) {
   }
   const bool feasible = cost != INFINITY;
   if (phase == 0) {
-    s.Ot[k] = feasible ? omax : INT_MAX;
+    if (lane == 0) s.Ot[k] = feasible ? omax : INT_MAX;
     return;
   }
 
@@ -166,17 +166,21 @@ __global__ __launch_bounds__(64) void k_chain_step(Search s, int phase) {
     if (total != 0.0f) a_t = 1.0f - cmax / total;
     if (osum != 0) a_m = (float)(1.0 - (double)omax / (double)osum);
   }
-  for (int i = 0; i < P; ++i) {
-    s.tr_p[eP + i] = p[i];
-    s.tr_C[eP + i] = C[i];
-    s.tr_Cns[eP + i] = Cns[i];
-    s.tr_O[eP + i] = O[i];
+  const bool mine = lane < P;
+  const int p_own = mine ? p[lane] : 0;
+  if (mine) {
+    s.tr_p[eP + lane] = p_own;
+    s.tr_C[eP + lane] = C[lane];
+    s.tr_Cns[eP + lane] = Cns[lane];
+    s.tr_O[eP + lane] = O[lane];
   }
-  s.tr_cost[e1] = cost;
-  s.tr_at[e1] = a_t;
-  s.tr_am[e1] = a_m;
-  s.n_iter[k] = it + 1;
-  s.live[k] = 0;
+  if (lane == 0) {
+    s.tr_cost[e1] = cost;
+    s.tr_at[e1] = a_t;
+    s.tr_am[e1] = a_m;
+    s.n_iter[k] = it + 1;
+    s.live[k] = 0;
+  }
   if (!feasible || it + 1 >= s.max_iter) return;
 
   // PP_Partition_Adjust
@@ -185,45 +189,42 @@ __global__ __launch_bounds__(64) void k_chain_step(Search s, int phase) {
   if (imax == 0) j = 1;
   else if (imax == P - 1) j = P - 2;
   else j = (C[imax + 1] < C[imax - 1]) ? imax + 1 : imax - 1;
-  auto q = [&](int i) { return p[i] - (i == imax ? 1 : 0) + (i == j ? 1 : 0); };
+  const int q_own = p_own - (lane == imax ? 1 : 0) + (lane == j ? 1 : 0);   // this lane's stage under p'
 
-  // searched before?
-  for (int tt = 0; tt <= it; ++tt) {
+  // searched before?  (entry `it` is p itself, written above by these same lanes)
+  for (int tt = 0; tt < it; ++tt) {
     const int* old = s.tr_p + ((size_t)k * s.max_iter + tt) * s.Pmax;
-    bool same = true;
-    for (int i = 0; i < P; ++i) same = same && (old[i] == q(i));
-    if (same) return;
+    const bool differs = mine && old[lane] != q_own;
+    if (__ballot(differs) == 0) return;
   }
 
-  // Validate: every stage of the new partition under the strategies just found
-  const int Lm = s.Lm[k];
-  const size_t lrow = (size_t)s.lrow[k], mrow = (size_t)s.mrow[k];
-  const uint8_t* st = s.strat + lrow;
-  const long long Ot = s.Ot[k];
-  int a = 0;
-  for (int kk = 0; kk < P; ++kk) {
-    const int n = q(kk);
-    const size_t mr = mrow + (size_t)kk * Lm;
+  // Validate: lane kk evaluates stage kk of the new partition under the strategies just found
+  bool ok = true;
+  if (mine) {
+    int a = 0;                                               // first layer of this lane's stage under p'
+    for (int i = 0; i < lane; ++i) a += p[i] - (i == imax ? 1 : 0) + (i == j ? 1 : 0);
+    const int Lm = s.Lm[k];
+    const size_t lrow = (size_t)s.lrow[k], mr = (size_t)s.mrow[k] + (size_t)lane * Lm;
+    const uint8_t* st = s.strat + lrow;
     int sp = st[a];
     float v = s.c[(lrow + a) * S + sp];
     long long mem = s.M[(mr + a) * S + sp];
-    for (int l = a + 1; l < a + n; ++l) {
+    for (int l = a + 1; l < a + q_own; ++l) {
       const int sn = st[l];
       const float r = s.R[((lrow + l) * S + sp) * S + sn];
       v = (v + r) + s.c[(lrow + l) * S + sn];
       mem += s.M[(mr + l) * S + sn];
       sp = sn;
     }
-    if (!(v <= cmax && mem <= (long long)s.E && mem <= Ot)) return;
-    a += n;
+    ok = v <= cmax && mem <= (long long)s.E && mem <= (long long)s.Ot[k];
   }
-  for (int i = 0; i < P; ++i) {
-    const int qi = q(i);
-    p[i] = qi;
+  if (__ballot(!ok) != 0) return;
+  if (mine) p[lane] = q_own;
+  if (lane == 0) {
+    s.moved[2 * k] = imax;
+    s.moved[2 * k + 1] = j;
+    s.live[k] = 1;
   }
-  s.moved[2 * k] = imax;
-  s.moved[2 * k + 1] = j;
-  s.live[k] = 1;
 }
 
 // Outer loops of Algorithm 1 / 2 on the pairs' final costs (one lane): out[0] = Tpt,
@@ -646,7 +647,7 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
     }
     hipLaunchKernelGGL(gbmw::k_stage_result, dim3(nt), dim3(64), 0, st, t, s, g_touched, nt,
                        g_chain, g_first);
-    hipLaunchKernelGGL(gbmw::k_chain_step, dim3((n + 63) / 64), dim3(64), 0, st, s, phase);
+    hipLaunchKernelGGL(gbmw::k_chain_step, dim3(n), dim3(64), 0, st, s, phase);
     HIP_TRY(hipGetLastError());
     // accept flags: live | moved (two per pair); the wait also ends the round for the host vectors
     HIP_TRY(hipMemcpyAsync(h_flags.data(), s.live, sizeof(int) * n, hipMemcpyDeviceToHost, st));
