@@ -304,6 +304,10 @@ def main():
             others[f"cfg{k}"] = {"ms_per_step": s2 * 1e3, "value": q.nominal_updates() / s2,
                                  "value_executed": q.executed_updates() / s2}
             g.gbmw_destroy(c2)
+            c3, s3 = solve_steps(g, torch, q, dq, 5 if k == 5 else 20, 2, flags=base_flags | g.GBMW_FLAG_LAZY_ARGMIN)
+            others[f"cfg{k}"]["lazy_argmin_ms_per_step"] = s3 * 1e3
+            others[f"cfg{k}"]["lazy_argmin_value_executed"] = q.executed_updates() / s3
+            g.gbmw_destroy(c3)
             del dq
         out["other_configs"] = others
 
