@@ -116,12 +116,15 @@ void launch_init_layer0(const Tables& t, int first, int count, hipStream_t st) {
 //   Value pass: the SP candidates x = C + R are folded into chunk minima of CH
 //   candidates (3-input min), and the chunk minima into a running prefix
 //   minimum P[k] = min(P[k-1], chunk 2k-1, chunk 2k); T is the last prefix.
-//   One add and half a min per candidate, no compare in the chain.
+//   One add and half a min per candidate, no compare in the chain.  The R row is
+//   consumed quad by quad as it arrives and only the prefix minima stay live.
 //   Argmin: P[k] == T is monotone in k, so the lowest-index minimiser lies in
-//   the first block k whose prefix equals T (re-comparing the stored x gives
-//   the same bits, so equality is exact).  The block tests are independent
+//   the first block k whose prefix equals T.  The block tests are independent
 //   compares into wave masks; a block is re-scanned only when some lane of
-//   the wave first hits it, which for neighbouring budgets is usually one.
+//   the wave first hits it, which for neighbouring budgets is usually one; the
+//   re-scan redoes the block's sums from the LDS row (same operands, same bits,
+//   so equality with T is exact).
+//   ARG = false leaves the argmin out altogether (values-only fill).
 // ---------------------------------------------------------------------------
 // Word 3 of a gfx9-family raw buffer descriptor: 32-bit data format, no swizzle.
 constexpr int kBufWord3 = 0x00020000;
@@ -130,9 +133,9 @@ __device__ __forceinline__ float fmin3(float a, float b, float c) {
   return __builtin_fminf(__builtin_fminf(a, b), c);
 }
 
-template <int SP, int K, int NW, int CH, int MINW, bool SAVE_X, bool FIRST, bool ARG>
-__global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int tiles, int first,
-                                                           int split) {
+template <int SP, int K, int NW, int CH, int MINW, bool FIRST, bool ARG, bool SPLIT>
+__global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int tiles, int first) {
+  constexpr bool split = SPLIT;
   constexpr int NC = (SP + CH - 1) / CH;                 // chunks (last may be short)
   constexpr int NP = NC / 2 + 1;                         // prefix minima / blocks
   constexpr int RS = (SP + 2 + 3) / 4 * 4;               // row: SP x R, c, M, padding
@@ -230,16 +233,47 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
     return;
   }
 
+  static_assert(K == 1, "one budget per lane");
   for (int s = s_begin; s < s_end; ++s) {
-    float r[RS];
+    // ---- value pass, streaming: the R row is consumed quad by quad as it arrives from LDS,
+    // candidates fold into chunk minima and those into the prefix minima at once, so that
+    // only the prefix minima stay live (the sums are not kept: the rescan redoes the few it
+    // needs).  c(l,s) and M(l,s) sit in the quad after the last candidates (SP % 4 == 0).
+    float P[NP];
+    float xs[CH], cm_odd = INFINITY;
+    float cs = 0.0f;
+    int m_raw = 0;
 #pragma unroll
     for (int q = 0; q < RQ; ++q) {
       const float4 v = rt_lds[s * RQ + q];
-      r[4 * q] = v.x; r[4 * q + 1] = v.y; r[4 * q + 2] = v.z; r[4 * q + 3] = v.w;
+      const float rq[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const int i = 4 * q + i4;
+        if (i < SP) {
+          const int c = i / CH, pos = i % CH;
+          xs[pos] = cp[0][i] + rq[i4];
+          const int hi = ((c + 1) * CH < SP) ? (c + 1) * CH : SP;     // end of chunk c
+          if (i == hi - 1) {                                          // chunk c complete
+            const int len = hi - c * CH;
+            const float cmv = len == 3 ? fmin3(xs[0], xs[1], xs[2])
+                              : len == 2 ? __builtin_fminf(xs[0], xs[1]) : xs[0];
+            if (c == 0) P[0] = cmv;
+            else if (c % 2 == 1) {
+              cm_odd = cmv;
+              if (c == NC - 1) P[(c + 1) / 2] = __builtin_fminf(P[(c - 1) / 2], cm_odd);
+            } else {
+              P[c / 2] = fmin3(P[c / 2 - 1], cm_odd, cmv);
+            }
+          }
+        }
+      }
+      if (4 * q == SP) {
+        cs = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(rq[0])));
+        m_raw = __builtin_amdgcn_readfirstlane(__float_as_int(rq[1]));
+      }
     }
-    // c(l,s) and M(l,s) are the same in every lane: move them to scalar registers.
-    const float cs = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(r[SP])));
-    const int m_raw = __builtin_amdgcn_readfirstlane(__float_as_int(r[SP + 1]));
+    const float T = P[NP - 1];
     // invalid (negative) M: the column is infeasible; beyond E + 1 nothing changes
     const int m = (m_raw < 0 || m_raw > E + 1) ? E + 1 : m_raw;
     // Stores go through buffer descriptors of column s: the address is a scalar base
@@ -253,32 +287,8 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
     const __amdgpu_buffer_rsrc_t bc = __builtin_amdgcn_make_buffer_rsrc(Cs, 0, (E + 1) * 4, kBufWord3);
     const __amdgpu_buffer_rsrc_t binf = __builtin_amdgcn_make_buffer_rsrc(Cs, 0, m * 4, kBufWord3);
     const __amdgpu_buffer_rsrc_t ba = __builtin_amdgcn_make_buffer_rsrc(An + (size_t)s * EP, 0, EP, kBufWord3);
-
-#pragma unroll
-    for (int j = 0; j < K; ++j) {
-      // ---- value pass
-      float x[SP];
-#pragma unroll
-      for (int i = 0; i < SP; ++i) x[i] = cp[j][i] + r[i];
-      float cm[NC];
-#pragma unroll
-      for (int c = 0; c < NC; ++c) {
-        const int lo = c * CH, hi = (lo + CH < SP) ? lo + CH : SP;
-        float acc = x[lo];
-        int i = lo + 1;
-#pragma unroll
-        for (; i + 1 < hi; i += 2) acc = fmin3(acc, x[i], x[i + 1]);
-        if (i < hi) acc = __builtin_fminf(acc, x[i]);
-        cm[c] = acc;
-      }
-      float P[NP];
-      P[0] = cm[0];
-#pragma unroll
-      for (int k = 1; k < NP; ++k)
-        P[k] = (2 * k < NC) ? fmin3(P[k - 1], cm[2 * k - 1], cm[2 * k])
-                            : __builtin_fminf(P[k - 1], cm[2 * k - 1]);
-      const float T = P[NP - 1];
-
+    {
+      constexpr int j = 0;
       // ---- argmin: first block whose prefix minimum reaches T
       int arg = 0;
       bool prev = false;
@@ -293,10 +303,7 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
             const int chi = (k == 0) ? 1 : ((2 * k + 1 < NC) ? 2 * k + 1 : NC);
             const int lo = clo * CH, hi = (chi * CH < SP) ? chi * CH : SP;
             int a = hi - 1;                              // implied when no earlier one matches
-            if (SAVE_X) {
-#pragma unroll
-              for (int i = hi - 2; i >= lo; --i) a = (x[i] == T) ? i : a;
-            } else {
+            {
               // The sums are not kept: redo them from the R row (same operands, same
               // bits).  The row offset goes through an opaque register so that these
               // reads are not merged with the value pass's (which would keep the whole
@@ -367,12 +374,13 @@ struct Blocking {                       // budgets per lane for a given strategy
   static constexpr int K = 1;
   static constexpr int NW = 4;
   static constexpr int CH = 3;          // candidates per chunk minimum
-  // waves per SIMD the register allocation must allow: SP live table values
-  // plus about 30 working registers out of 512
-  // Keeping the S candidate sums live for the argmin rescan costs S registers;
-  // it only pays where dropping them would not buy another wave per SIMD.
-  static constexpr bool SAVE_X = (SP >= 60);
-  static constexpr int MINW = (SP <= 24) ? 8 : (SP <= 32) ? 7 : (SP <= 36) ? 6 : (SP <= 44) ? 5 : (SP <= 56) ? 4 : 3;
+  // waves per SIMD the register allocation must allow: SP live table values plus about 20
+  // working registers out of 512 (the value pass streams the R row and keeps only the
+  // prefix minima; the candidate sums are not kept)
+  static constexpr int MINW = (SP <= 44) ? 8 : (SP <= 56) ? 6 : 5;
+  static constexpr int MINW_SPLIT = 4;
+  // the layer-1 variant builds layer 0 from c and M and needs a few registers more
+  static constexpr int MINW_FIRST = (SP > 40 && SP <= 44) ? 7 : MINW;
   // without the argmin pass: the SP table values plus about 16 working registers
   static constexpr int MINW_VALUES = (SP <= 44) ? 8 : (SP <= 52) ? 7 : (SP <= 60) ? 6 : 5;
 };
@@ -381,25 +389,30 @@ template <int SP>
 static void launch_minplus_sp(const Tables& t, int l, int first, int n_active, hipStream_t st) {
   constexpr int K = Blocking<SP>::K, NW = Blocking<SP>::NW, CH = Blocking<SP>::CH,
                 MINW = Blocking<SP>::MINW;
-  constexpr bool SAVE_X = Blocking<SP>::SAVE_X;
   int tiles = (t.E + 1 + 64 * K * NW - 1) / (64 * K * NW);
   // fewer than four workgroups per compute unit: split the strategies over the waves
-  const int split = ((long long)tiles * n_active < 1024) ? 1 : 0;
+  static const long long thr = getenv("GBMW_SPLIT_WGS") ? atoll(getenv("GBMW_SPLIT_WGS")) : 1024;
+  const int split = ((long long)tiles * n_active < thr) ? 1 : 0;
   if (split) tiles = (t.E + 1 + 64 * K - 1) / (64 * K);
   constexpr int RS = (SP + 2 + 3) / 4 * 4;
   const dim3 grid((unsigned)tiles * n_active), block(64 * NW);
   const size_t lds = (size_t)t.S * RS * sizeof(float);
+  // Split launches are the small ones, where a wave's own latency counts and registers are
+  // plentiful: a low occupancy target lets the compiler keep the whole R row in flight.
+  constexpr int MS = Blocking<SP>::MINW_SPLIT;
+#define GBMW_LAUNCH(MW, FIRST_, ARG_, SPLIT_)                                                        \
+  hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, MW, FIRST_, ARG_, SPLIT_>), grid, block, lds, st, t, l, \
+                     tiles, first)
   if (t.A == nullptr) {
     constexpr int MW = Blocking<SP>::MINW_VALUES;
-    if (l == 1)
-      hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, MW, false, true, false>), grid, block, lds, st, t, l, tiles, first, split);
-    else
-      hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, MW, false, false, false>), grid, block, lds, st, t, l, tiles, first, split);
-  } else if (l == 1) {
-    hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, MINW, SAVE_X, true, true>), grid, block, lds, st, t, l, tiles, first, split);
+    if (l == 1) { if (split) GBMW_LAUNCH(MS, true, false, true); else GBMW_LAUNCH(MW, true, false, false); }
+    else        { if (split) GBMW_LAUNCH(MS, false, false, true); else GBMW_LAUNCH(MW, false, false, false); }
   } else {
-    hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, MINW, SAVE_X, false, true>), grid, block, lds, st, t, l, tiles, first, split);
+    constexpr int M1 = Blocking<SP>::MINW_FIRST;
+    if (l == 1) { if (split) GBMW_LAUNCH(MS, true, true, true); else GBMW_LAUNCH(M1, true, true, false); }
+    else        { if (split) GBMW_LAUNCH(MS, false, true, true); else GBMW_LAUNCH(MINW, false, true, false); }
   }
+#undef GBMW_LAUNCH
 }
 
 void launch_minplus(const Tables& t, int l, int first, int n_active, hipStream_t st) {
