@@ -275,16 +275,22 @@ struct Dims {
   size_t n, sumP, sumLm, sumPL, S, tr, trP;
 };
 
+// The resident copy of the model and of the pairs' descriptions.
+struct ModelOnDevice {
+  int *P, *Lm, *m, *lrow, *prow, *mrow, *M;
+  float *c, *cns, *R;
+  uint32_t* zero_begin;      // the part of the state that starts as zero
+  size_t zero_words;
+};
+
 // One layout for sizing (base == nullptr) and for carving.
-size_t carve_search(Carver& cv, const Dims& d, bool with_cns, gbmw::Search& s, int*& dP, int*& dLm,
-                    int*& dm, int*& dlrow, int*& dprow, int*& dmrow, float*& dc, float*& dcns,
-                    float*& dR, int*& dM, uint32_t*& zero_begin, size_t& zero_words) {
-  dP = cv.take<int>(d.n); dLm = cv.take<int>(d.n); dm = cv.take<int>(d.n);
-  dlrow = cv.take<int>(d.n); dprow = cv.take<int>(d.n); dmrow = cv.take<int>(d.n);
-  dc = cv.take<float>(d.sumLm * d.S);
-  dcns = with_cns ? cv.take<float>(d.sumLm * d.S) : nullptr;
-  dR = cv.take<float>(d.sumLm * d.S * d.S);
-  dM = cv.take<int>(d.sumPL * d.S);
+size_t carve_search(Carver& cv, const Dims& d, bool with_cns, gbmw::Search& s, ModelOnDevice& md) {
+  md.P = cv.take<int>(d.n); md.Lm = cv.take<int>(d.n); md.m = cv.take<int>(d.n);
+  md.lrow = cv.take<int>(d.n); md.prow = cv.take<int>(d.n); md.mrow = cv.take<int>(d.n);
+  md.c = cv.take<float>(d.sumLm * d.S);
+  md.cns = with_cns ? cv.take<float>(d.sumLm * d.S) : nullptr;
+  md.R = cv.take<float>(d.sumLm * d.S * d.S);
+  md.M = cv.take<int>(d.sumPL * d.S);
   s.part = cv.take<int>(d.sumP);
   s.stC = cv.take<float>(d.sumP);
   s.stCns = cv.take<float>(d.sumP);
@@ -295,7 +301,7 @@ size_t carve_search(Carver& cv, const Dims& d, bool with_cns, gbmw::Search& s, i
   // everything from here on starts as zero
   cv.used = (cv.used + 255) / 256 * 256;
   const size_t z0 = cv.used;
-  zero_begin = cv.base ? (uint32_t*)(cv.base + z0) : nullptr;
+  md.zero_begin = cv.base ? (uint32_t*)(cv.base + z0) : nullptr;
   s.n_iter = cv.take<int>(d.n);
   s.Ot = cv.take<int>(d.n);
   s.tr_p = cv.take<int>(d.trP);
@@ -306,7 +312,7 @@ size_t carve_search(Carver& cv, const Dims& d, bool with_cns, gbmw::Search& s, i
   s.tr_at = cv.take<float>(d.tr);
   s.tr_am = cv.take<float>(d.tr);
   cv.used = (cv.used + 255) / 256 * 256;
-  zero_words = (cv.used - z0) / 4;
+  md.zero_words = (cv.used - z0) / 4;
   return cv.used;
 }
 
@@ -428,21 +434,19 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
   const Dims d{(size_t)n, (size_t)sumP, (size_t)sumLm, (size_t)sumPL, (size_t)S, tr, trP};
   gbmw::Search s{};
   s.n_chain = n; s.S = S; s.E = E; s.Pmax = Pmax; s.max_iter = q->max_iter;
-  int *dP, *dLm, *dm, *dlrow, *dprow, *dmrow, *dM;
-  float *dc, *dcns, *dR;
-  uint32_t* zero_begin;
-  size_t zero_words;
+  ModelOnDevice md{};
   {
     Carver sizing(nullptr);
-    const size_t bytes = carve_search(sizing, d, q->c_nosync != nullptr, s, dP, dLm, dm, dlrow, dprow,
-                                      dmrow, dc, dcns, dR, dM, zero_begin, zero_words);
-    TRY(c->d_search.reserve(bytes));
+    TRY(c->d_search.reserve(carve_search(sizing, d, q->c_nosync != nullptr, s, md)));
     Carver cv(c->d_search.p);
-    carve_search(cv, d, q->c_nosync != nullptr, s, dP, dLm, dm, dlrow, dprow, dmrow, dc, dcns, dR, dM,
-                 zero_begin, zero_words);
+    carve_search(cv, d, q->c_nosync != nullptr, s, md);
   }
-  s.P = dP; s.Lm = dLm; s.m = dm; s.lrow = dlrow; s.prow = dprow; s.mrow = dmrow;
-  s.c = dc; s.cns = dcns; s.R = dR; s.M = dM;
+  s.P = md.P; s.Lm = md.Lm; s.m = md.m; s.lrow = md.lrow; s.prow = md.prow; s.mrow = md.mrow;
+  s.c = md.c; s.cns = md.cns; s.R = md.R; s.M = md.M;
+  int *dP = md.P, *dLm = md.Lm, *dm = md.m, *dlrow = md.lrow, *dprow = md.prow, *dmrow = md.mrow, *dM = md.M;
+  float *dc = md.c, *dcns = md.cns, *dR = md.R;
+  uint32_t* zero_begin = md.zero_begin;
+  const size_t zero_words = md.zero_words;
 
   // rows of the slots (what the layer kernels read) and the per-round index arrays
   const size_t rows = (size_t)rows_total;
