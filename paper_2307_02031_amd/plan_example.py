@@ -1,0 +1,117 @@
+"""End-to-end planning example on one MI355X: layer shapes -> candidate strategies
+(Section 3.2) -> analytic cost model -> Algorithm 2's partition search for every
+PP degree and a range of batch sizes -> the plan with the highest estimated
+throughput.
+
+    python -m paper_2307_02031_amd.plan_example --model BERT-Huge-32 --devices 8 --mem-gb 16
+
+Every number comes from the library's kernels; this file only arranges the calls
+and prints.  The layer shapes are rows of the paper's model table cut into equal
+layers and the hardware figures are round A100-class numbers (gbmw_inputs), so
+the output illustrates the planner, it does not predict a real cluster.
+"""
+from __future__ import annotations
+
+import argparse
+import os
+import sys
+
+import numpy as np
+
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+
+KIND = {1: "DP", 2: "SDP", 3: "TP"}
+
+
+def strategy_name(s) -> str:
+    lv = "-".join(f"{KIND[int(k)]}{int(d)}" for k, d in zip(s["kind"][:s["n_levels"]], s["degree"][:s["n_levels"]]))
+    return (lv or "single") + ("+CKPT" if s["ckpt"] else "")
+
+
+def main():
+    import gbmw_inputs as gi
+    import paper_2307_02031_amd as g
+
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("--model", default="BERT-Huge-32", choices=sorted(gi.TABLE1))
+    ap.add_argument("--devices", type=int, default=8)
+    ap.add_argument("--mem-gb", type=float, default=16.0, help="memory budget per device")
+    ap.add_argument("--unit-mb", type=float, default=8.0, help="granularity of the budget axis")
+    ap.add_argument("--batches", default="8,16,32,64,128", help="global batch sizes to try, in order")
+    ap.add_argument("--microbatches", type=int, default=8)
+    ap.add_argument("--lazy-argmin", action="store_true", help="GBMW_FLAG_LAZY_ARGMIN for the searches")
+    args = ap.parse_args()
+
+    layers = gi.table1_layers(args.model)
+    Lm = len(layers)
+    hw = gi.default_hardware(unit_mb=args.unit_mb)
+    hw["island"] = min(hw["island"], args.devices)
+    E = int(args.mem_gb * 1024 / args.unit_mb)
+    batches = [float(b) for b in args.batches.split(",")]
+    degrees = [p for p in (1, 2, 4, 8, 16, 32, 64) if p <= args.devices and p <= Lm]
+    flags = g.GBMW_FLAG_LAZY_ARGMIN if args.lazy_argmin else 0
+    print(f"{args.model}: {Lm} layers on {args.devices} devices, {args.mem_gb:g} GB each "
+          f"({E} units of {args.unit_mb:g} MB), micro-batches {args.microbatches}")
+
+    # one call of the partition search per PP degree (pairs of one call share the strategy
+    # set, which depends on the group size devices / P), all batch sizes in lockstep
+    found = {}                                   # (batch, P) -> result of that pair
+    ctx = None
+    for P in degrees:
+        strat = g.gbmw_enumerate_strategies(args.devices // P)
+        S = len(strat)
+        cs, cns, Rs, Ms = [], [], [], []
+        for B in batches:
+            cm = g.gbmw_cost_model(layers, strat, hw, B / args.microbatches, P)
+            cs.append(cm["c"]); cns.append(cm["c_nosync"]); Rs.append(cm["R"]); Ms.append(cm["M"].reshape(P * Lm, S))
+        n = len(batches)
+        p0 = np.tile(gi.proportional_partition(Lm, 1.0 / np.arange(P, 0, -1)), n)
+        p_t = np.tile(gi.proportional_partition(Lm, np.ones(P)), n)
+        res, ctx = g.gbmw_partition_search([P] * n, [Lm] * n, [args.microbatches] * n, np.concatenate(cs),
+                                           np.concatenate(cns), np.concatenate(Rs), np.concatenate(Ms), p0, p_t,
+                                           S, E, max_iter=32, flags=flags, ctx=ctx)
+        last = [int(x) - 1 for x in res["n_iter"]]
+        for k, B in enumerate(batches):
+            j = last[k]
+            found[(B, P)] = dict(B=B, P=P, cost=float(res["cost"][k, j]), part=[int(x) for x in res["p"][k, j, :P]],
+                                 plan=[strategy_name(strat[int(s)]) if s != 255 else "-" for s in res["strat"][k, :Lm]],
+                                 searched=j + 1, alpha_t=float(res["alpha_t"][k, j]),
+                                 alpha_m=float(res["alpha_m"][k, j]), mem=[int(x) for x in res["O"][k, j, :P]])
+        print(f"  PP={P:<2d} group of {args.devices // P:<2d} devices, {S:2d} strategies: " +
+              "  ".join(f"B={int(B)}: " + (f"{found[(B, P)]['cost']:.4g}s" if np.isfinite(found[(B, P)]['cost']) else "OOM")
+                        for B in batches) +
+              f"   [{res['device_ms']:.2f} ms on the GPU, {int(res['n_iter'].sum())} partitions searched]")
+    g.gbmw_destroy(ctx)
+
+    # Algorithm 2's outer loop: batch sizes in order, the best PP degree for each, stop at the
+    # first batch size that fits under no PP degree
+    best = None
+    for B in batches:
+        c_opt = min((found[(B, P)] for P in degrees), key=lambda r: r["cost"])
+        if not np.isfinite(c_opt["cost"]):
+            print(f"batch size {int(B)} does not fit under any PP degree: larger ones are not considered")
+            break
+        if best is None or B / c_opt["cost"] > best["tpt"]:
+            best = dict(c_opt, tpt=B / c_opt["cost"])
+    if best is None:
+        print("no feasible plan")
+        return
+    print(f"best: batch {int(best['B'])}, PP={best['P']}, partition {best['part']}, estimated iteration "
+          f"{best['cost']:.4g} s, throughput {best['tpt']:.4g} samples/s")
+    print(f"      balance degrees alpha_t={best['alpha_t']:.3f} alpha_m={best['alpha_m']:.3f}, stage memory "
+          f"{best['mem']} of {E} units, {best['searched']} partitions searched for this pair")
+    a = 0
+    for i, cnt in enumerate(best["part"]):
+        names = best["plan"][a:a + cnt]
+        runs, prev = [], None
+        for nm in names:
+            if nm == prev:
+                runs[-1][1] += 1
+            else:
+                runs.append([nm, 1]); prev = nm
+        print(f"      stage {i}: layers {a}..{a + cnt - 1}: " + ", ".join(f"{c} x {nm}" for nm, c in runs))
+        a += cnt
+
+
+if __name__ == "__main__":
+    main()
