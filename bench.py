@@ -140,6 +140,32 @@ def partition_leg(g, gi, cpu: bool, budget_s=10.0):
     return out
 
 
+def whole_search_leg(g, gi):
+    """The whole search the paper times in its search-time figure (Fig. 5a: 8 GPUs, the
+    checkpointing strategy set, 16 GB budget, depth 24..96): batch-size sweep x PP degrees x
+    partition loop x stages, here from layer shapes through the library's entry points
+    (strategy enumeration, cost model, Algorithm 2), host to host.  Context beside the
+    paper's seconds, on different hardware and with this build's own cost model."""
+    from paper_2307_02031_amd.plan_example import plan
+    hw = gi.default_hardware(unit_mb=1.0)                 # the budget axis in MB: 16 GB = 16384 units
+    batches = [8.0, 16.0, 24.0, 32.0, 40.0, 48.0, 56.0, 64.0]
+    paper_s = {24: 280.59, 48: 537.91, 72: 825.86, 96: 1104.92}
+    out = {"setup": "BERT-Huge layer repeated L times, 8 devices, E = 16384 units of 1 MB, 8 batch sizes "
+                    "x PP 1/2/4/8, 8 micro-batches, max_iter 32",
+           "paper_fig5a_16G_seconds": paper_s, "ours": {}}
+    for L in (24, 48, 72, 96):
+        layers = gi.table1_layers("BERT-Huge-32", layers=L)
+        plan(g, gi, layers, 8, 16384, hw, batches[:2], 8)                 # warm-up: allocations
+        t0 = time.perf_counter()
+        best, _, st = plan(g, gi, layers, 8, 16384, hw, batches, 8)
+        dt = time.perf_counter() - t0
+        out["ours"][L] = {"seconds": dt, "device_ms": st["device_ms"], "partitions_searched": st["partitions"],
+                          "stage_solves": st["stage_solves"], "cell_updates": st["cell_updates"],
+                          "best": None if best is None else {"batch": best["B"], "P": best["P"],
+                                                             "partition": best["part"], "tpt": best["tpt"]}}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -184,7 +210,8 @@ def main():
         return
 
     if args.only_partition:
-        print(json.dumps({"partition_search": partition_leg(g, gi, cpu=not args.no_cpu_baseline)}), flush=True)
+        print(json.dumps({"partition_search": partition_leg(g, gi, cpu=not args.no_cpu_baseline),
+                          "whole_search": whole_search_leg(g, gi)}), flush=True)
         return
 
     p = gi.make_config(args.config)
@@ -313,6 +340,7 @@ def main():
 
     if not args.no_partition:
         out["partition_search"] = partition_leg(g, gi, cpu=not args.no_cpu_baseline)
+        out["whole_search"] = whole_search_leg(g, gi)
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(p)

@@ -385,18 +385,20 @@ TABLE1 = {
 }
 
 
-def table1_layers(name: str) -> np.ndarray:
+def table1_layers(name: str, layers: int | None = None) -> np.ndarray:
     """float64 [L][4]: parameters, forward FLOPs per sample, boundary and
     intermediate activation bytes per sample of each layer.  A layer holds
     1/L of the parameters and of the activations; forward FLOPs = 2 x parameters
-    x tokens; the boundary activation is tokens x hidden x 2 bytes."""
+    x tokens; the boundary activation is tokens x hidden x 2 bytes.  ``layers``
+    repeats the model's layer that many times instead (the paper's search-time
+    figure varies the depth of one architecture)."""
     L, hidden, params, act_mb, tokens = TABLE1[name]
     p = params / L
     act = act_mb * 2.0 ** 20 / L
     bnd = float(tokens * hidden * 2)
     assert bnd < act
     row = [p, 2.0 * p * tokens, bnd, act - bnd]
-    return np.ascontiguousarray(np.tile(np.array(row, np.float64), (L, 1)))
+    return np.ascontiguousarray(np.tile(np.array(row, np.float64), (L if layers is None else layers, 1)))
 
 
 def default_hardware(unit_mb: float = 8.0) -> dict:

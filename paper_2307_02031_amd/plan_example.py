@@ -28,6 +28,57 @@ def strategy_name(s) -> str:
     return (lv or "single") + ("+CKPT" if s["ckpt"] else "")
 
 
+def plan(g, gi, layers, devices, E, hw, batches, microbatches, flags=0, max_iter=32, log=None):
+    """Algorithm 2 over the given batch sizes (in order) and every PP degree 1, 2, 4, ... that
+    fits: returns (best pair or None, results per (batch, P), stats).  One call of the
+    partition search per PP degree (the pairs of one call share the strategy set, which
+    depends on the group size devices / P), all batch sizes in lockstep."""
+    Lm = len(layers)
+    degrees = [p for p in (1, 2, 4, 8, 16, 32, 64) if p <= devices and p <= Lm]
+    found = {}
+    stats = dict(device_ms=0.0, partitions=0, cell_updates=0, stage_solves=0)
+    ctx = None
+    for P in degrees:
+        strat = g.gbmw_enumerate_strategies(devices // P)
+        S = len(strat)
+        cs, cns, Rs, Ms = [], [], [], []
+        for B in batches:
+            cm = g.gbmw_cost_model(layers, strat, hw, B / microbatches, P)
+            cs.append(cm["c"]); cns.append(cm["c_nosync"]); Rs.append(cm["R"]); Ms.append(cm["M"].reshape(P * Lm, S))
+        n = len(batches)
+        p0 = np.tile(gi.proportional_partition(Lm, 1.0 / np.arange(P, 0, -1)), n)
+        p_t = np.tile(gi.proportional_partition(Lm, np.ones(P)), n)
+        res, ctx = g.gbmw_partition_search([P] * n, [Lm] * n, [microbatches] * n, np.concatenate(cs),
+                                           np.concatenate(cns), np.concatenate(Rs), np.concatenate(Ms), p0, p_t,
+                                           S, E, max_iter=max_iter, flags=flags, ctx=ctx)
+        stats["device_ms"] += res["device_ms"]; stats["partitions"] += int(res["n_iter"].sum())
+        stats["cell_updates"] += int(res["cell_updates"]); stats["stage_solves"] += int(res["stage_solves"])
+        for k, B in enumerate(batches):
+            j = int(res["n_iter"][k]) - 1
+            found[(B, P)] = dict(B=B, P=P, cost=float(res["cost"][k, j]), part=[int(x) for x in res["p"][k, j, :P]],
+                                 plan=[strategy_name(strat[int(s)]) if s != 255 else "-" for s in res["strat"][k, :Lm]],
+                                 searched=j + 1, alpha_t=float(res["alpha_t"][k, j]),
+                                 alpha_m=float(res["alpha_m"][k, j]), mem=[int(x) for x in res["O"][k, j, :P]])
+        if log:
+            log(f"  PP={P:<2d} group of {devices // P:<2d} devices, {S:2d} strategies: " +
+                "  ".join(f"B={int(B)}: " + (f"{found[(B, P)]['cost']:.4g}s" if np.isfinite(found[(B, P)]['cost']) else "OOM")
+                          for B in batches) +
+                f"   [{res['device_ms']:.2f} ms on the GPU, {int(res['n_iter'].sum())} partitions searched]")
+    g.gbmw_destroy(ctx)
+    # outer loop: batch sizes in order, the best PP degree for each, stop at the first batch
+    # size that fits under no PP degree
+    best = None
+    for B in batches:
+        c_opt = min((found[(B, P)] for P in degrees), key=lambda r: r["cost"])
+        if not np.isfinite(c_opt["cost"]):
+            if log:
+                log(f"batch size {int(B)} does not fit under any PP degree: larger ones are not considered")
+            break
+        if best is None or B / c_opt["cost"] > best["tpt"]:
+            best = dict(c_opt, tpt=B / c_opt["cost"])
+    return best, found, stats
+
+
 def main():
     import gbmw_inputs as gi
     import paper_2307_02031_amd as g
@@ -48,51 +99,11 @@ def main():
     hw["island"] = min(hw["island"], args.devices)
     E = int(args.mem_gb * 1024 / args.unit_mb)
     batches = [float(b) for b in args.batches.split(",")]
-    degrees = [p for p in (1, 2, 4, 8, 16, 32, 64) if p <= args.devices and p <= Lm]
     flags = g.GBMW_FLAG_LAZY_ARGMIN if args.lazy_argmin else 0
     print(f"{args.model}: {Lm} layers on {args.devices} devices, {args.mem_gb:g} GB each "
           f"({E} units of {args.unit_mb:g} MB), micro-batches {args.microbatches}")
 
-    # one call of the partition search per PP degree (pairs of one call share the strategy
-    # set, which depends on the group size devices / P), all batch sizes in lockstep
-    found = {}                                   # (batch, P) -> result of that pair
-    ctx = None
-    for P in degrees:
-        strat = g.gbmw_enumerate_strategies(args.devices // P)
-        S = len(strat)
-        cs, cns, Rs, Ms = [], [], [], []
-        for B in batches:
-            cm = g.gbmw_cost_model(layers, strat, hw, B / args.microbatches, P)
-            cs.append(cm["c"]); cns.append(cm["c_nosync"]); Rs.append(cm["R"]); Ms.append(cm["M"].reshape(P * Lm, S))
-        n = len(batches)
-        p0 = np.tile(gi.proportional_partition(Lm, 1.0 / np.arange(P, 0, -1)), n)
-        p_t = np.tile(gi.proportional_partition(Lm, np.ones(P)), n)
-        res, ctx = g.gbmw_partition_search([P] * n, [Lm] * n, [args.microbatches] * n, np.concatenate(cs),
-                                           np.concatenate(cns), np.concatenate(Rs), np.concatenate(Ms), p0, p_t,
-                                           S, E, max_iter=32, flags=flags, ctx=ctx)
-        last = [int(x) - 1 for x in res["n_iter"]]
-        for k, B in enumerate(batches):
-            j = last[k]
-            found[(B, P)] = dict(B=B, P=P, cost=float(res["cost"][k, j]), part=[int(x) for x in res["p"][k, j, :P]],
-                                 plan=[strategy_name(strat[int(s)]) if s != 255 else "-" for s in res["strat"][k, :Lm]],
-                                 searched=j + 1, alpha_t=float(res["alpha_t"][k, j]),
-                                 alpha_m=float(res["alpha_m"][k, j]), mem=[int(x) for x in res["O"][k, j, :P]])
-        print(f"  PP={P:<2d} group of {args.devices // P:<2d} devices, {S:2d} strategies: " +
-              "  ".join(f"B={int(B)}: " + (f"{found[(B, P)]['cost']:.4g}s" if np.isfinite(found[(B, P)]['cost']) else "OOM")
-                        for B in batches) +
-              f"   [{res['device_ms']:.2f} ms on the GPU, {int(res['n_iter'].sum())} partitions searched]")
-    g.gbmw_destroy(ctx)
-
-    # Algorithm 2's outer loop: batch sizes in order, the best PP degree for each, stop at the
-    # first batch size that fits under no PP degree
-    best = None
-    for B in batches:
-        c_opt = min((found[(B, P)] for P in degrees), key=lambda r: r["cost"])
-        if not np.isfinite(c_opt["cost"]):
-            print(f"batch size {int(B)} does not fit under any PP degree: larger ones are not considered")
-            break
-        if best is None or B / c_opt["cost"] > best["tpt"]:
-            best = dict(c_opt, tpt=B / c_opt["cost"])
+    best, _, _ = plan(g, gi, layers, args.devices, E, hw, batches, args.microbatches, flags=flags, log=print)
     if best is None:
         print("no feasible plan")
         return
