@@ -18,9 +18,9 @@ What the paper fixes and this file follows:
     intermediate ones during backward (Section 3.1);
   * O_f, O_b, O_ms and E_all as in Eq. 2.
 Everything else (which tensors TP replicates, the transformation cost, the
-bandwidth a level sees, bytes per parameter) is this build's choice; the design doc
-lists each.  All arithmetic is fp64 in the order written; times are rounded to
-fp32 and memories to integer units at the end.
+bandwidth a level sees, bytes per parameter) is this build's choice, stated in
+the functions below.  All arithmetic is fp64 in the order written; times are
+rounded to fp32 and memories to integer units at the end.
 """
 from __future__ import annotations
 
