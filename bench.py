@@ -161,6 +161,7 @@ def whole_search_leg(g, gi):
         dt = time.perf_counter() - t0
         out["ours"][L] = {"seconds": dt, "device_ms": st["device_ms"], "partitions_searched": st["partitions"],
                           "stage_solves": st["stage_solves"], "cell_updates": st["cell_updates"],
+                          "pairs": st["pairs"], "rounds": st["rounds"],
                           "best": None if best is None else {"batch": best["B"], "P": best["P"],
                                                              "partition": best["part"], "tpt": best["tpt"]}}
     return out

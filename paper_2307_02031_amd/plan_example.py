@@ -30,52 +30,54 @@ def strategy_name(s) -> str:
 
 def plan(g, gi, layers, devices, E, hw, batches, microbatches, flags=0, max_iter=32, log=None):
     """Algorithm 2 over the given batch sizes (in order) and every PP degree 1, 2, 4, ... that
-    fits: returns (best pair or None, results per (batch, P), stats).  One call of the
-    partition search per PP degree (the pairs of one call share the strategy set, which
-    depends on the group size devices / P), all batch sizes in lockstep."""
+    fits, as ONE call of the partition search: a pair per (batch size, PP degree), grouped by
+    batch size, so that the library also runs the outer loops (best degree per batch size,
+    stop at the first batch size that fits nowhere, Tpt).  The strategy set depends on the
+    group size devices / P; the smaller sets are padded to the largest with forbidden
+    strategies (c = +inf), which no plan ever picks.
+    Returns (best pair or None, results per (batch, P), stats)."""
     Lm = len(layers)
     degrees = [p for p in (1, 2, 4, 8, 16, 32, 64) if p <= devices and p <= Lm]
-    found = {}
-    stats = dict(device_ms=0.0, partitions=0, cell_updates=0, stage_solves=0)
-    ctx = None
-    for P in degrees:
-        strat = g.gbmw_enumerate_strategies(devices // P)
-        S = len(strat)
-        cs, cns, Rs, Ms = [], [], [], []
-        for B in batches:
-            cm = g.gbmw_cost_model(layers, strat, hw, B / microbatches, P)
-            cs.append(cm["c"]); cns.append(cm["c_nosync"]); Rs.append(cm["R"]); Ms.append(cm["M"].reshape(P * Lm, S))
-        n = len(batches)
-        p0 = np.tile(gi.proportional_partition(Lm, 1.0 / np.arange(P, 0, -1)), n)
-        p_t = np.tile(gi.proportional_partition(Lm, np.ones(P)), n)
-        res, ctx = g.gbmw_partition_search([P] * n, [Lm] * n, [microbatches] * n, np.concatenate(cs),
-                                           np.concatenate(cns), np.concatenate(Rs), np.concatenate(Ms), p0, p_t,
-                                           S, E, max_iter=max_iter, flags=flags, ctx=ctx)
-        stats["device_ms"] += res["device_ms"]; stats["partitions"] += int(res["n_iter"].sum())
-        stats["cell_updates"] += int(res["cell_updates"]); stats["stage_solves"] += int(res["stage_solves"])
-        for k, B in enumerate(batches):
-            j = int(res["n_iter"][k]) - 1
-            found[(B, P)] = dict(B=B, P=P, cost=float(res["cost"][k, j]), part=[int(x) for x in res["p"][k, j, :P]],
-                                 plan=[strategy_name(strat[int(s)]) if s != 255 else "-" for s in res["strat"][k, :Lm]],
-                                 searched=j + 1, alpha_t=float(res["alpha_t"][k, j]),
-                                 alpha_m=float(res["alpha_m"][k, j]), mem=[int(x) for x in res["O"][k, j, :P]])
-        if log:
-            log(f"  PP={P:<2d} group of {devices // P:<2d} devices, {S:2d} strategies: " +
-                "  ".join(f"B={int(B)}: " + (f"{found[(B, P)]['cost']:.4g}s" if np.isfinite(found[(B, P)]['cost']) else "OOM")
-                          for B in batches) +
-                f"   [{res['device_ms']:.2f} ms on the GPU, {int(res['n_iter'].sum())} partitions searched]")
+    sets = {P: g.gbmw_enumerate_strategies(devices // P) for P in degrees}
+    S = max(len(v) for v in sets.values())
+    Ps, cs, cns, Rs, Ms, p0s, pts, bsz, grp, key = [], [], [], [], [], [], [], [], [], []
+    for gi_, B in enumerate(batches):
+        for P in degrees:
+            n_s = len(sets[P])
+            cm = g.gbmw_cost_model(layers, sets[P], hw, B / microbatches, P)
+            c = np.full((Lm, S), np.inf, np.float32); c[:, :n_s] = cm["c"]
+            cn = np.full((Lm, S), np.inf, np.float32); cn[:, :n_s] = cm["c_nosync"]
+            R = np.zeros((Lm, S, S), np.float32); R[:, :n_s, :n_s] = cm["R"]
+            M = np.zeros((P, Lm, S), np.int32); M[:, :, :n_s] = cm["M"]
+            Ps.append(P); cs.append(c); cns.append(cn); Rs.append(R); Ms.append(M.reshape(P * Lm, S))
+            p0s.append(gi.proportional_partition(Lm, 1.0 / np.arange(P, 0, -1)))
+            pts.append(gi.proportional_partition(Lm, np.ones(P)))
+            bsz.append(B); grp.append(gi_); key.append((B, P))
+    n = len(Ps)
+    res, ctx = g.gbmw_partition_search(Ps, [Lm] * n, [microbatches] * n, np.concatenate(cs), np.concatenate(cns),
+                                       np.concatenate(Rs), np.concatenate(Ms), np.concatenate(p0s),
+                                       np.concatenate(pts), S, E, max_iter=max_iter, flags=flags,
+                                       batch_size=bsz, batch_group=grp)
     g.gbmw_destroy(ctx)
-    # outer loop: batch sizes in order, the best PP degree for each, stop at the first batch
-    # size that fits under no PP degree
-    best = None
-    for B in batches:
-        c_opt = min((found[(B, P)] for P in degrees), key=lambda r: r["cost"])
-        if not np.isfinite(c_opt["cost"]):
-            if log:
-                log(f"batch size {int(B)} does not fit under any PP degree: larger ones are not considered")
-            break
-        if best is None or B / c_opt["cost"] > best["tpt"]:
-            best = dict(c_opt, tpt=B / c_opt["cost"])
+    stats = dict(device_ms=res["device_ms"], partitions=int(res["n_iter"].sum()), rounds=res["rounds"],
+                 cell_updates=int(res["cell_updates"]), stage_solves=int(res["stage_solves"]), pairs=n, S=S)
+    found = {}
+    for k, (B, P) in enumerate(key):
+        j = int(res["n_iter"][k]) - 1
+        found[(B, P)] = dict(B=B, P=P, cost=float(res["cost"][k, j]), part=[int(x) for x in res["p"][k, j, :P]],
+                             plan=[strategy_name(sets[P][int(s)]) if s != 255 else "-" for s in res["strat"][k, :Lm]],
+                             searched=j + 1, alpha_t=float(res["alpha_t"][k, j]),
+                             alpha_m=float(res["alpha_m"][k, j]), mem=[int(x) for x in res["O"][k, j, :P]])
+    if log:
+        for P in degrees:
+            log(f"  PP={P:<2d} group of {devices // P:<2d} devices, {len(sets[P]):2d} strategies: " +
+                "  ".join(f"B={int(B)}: " + (f"{found[(B, P)]['cost']:.4g}s" if np.isfinite(found[(B, P)]['cost']) else "OOM")
+                          for B in batches))
+        log(f"  {n} pairs, {stats['partitions']} partitions searched in {stats['rounds']} lockstep rounds, "
+            f"{stats['device_ms']:.2f} ms on the GPU")
+    if res["tpt_pair"] < 0:
+        return None, found, stats
+    best = dict(found[key[res["tpt_pair"]]], tpt=float(res["tpt"]))
     return best, found, stats
 
 
