@@ -136,3 +136,32 @@ def test_shapes_to_partition_search(g, P):
     assert np.array_equal(res["strat"][0], want["strat"])
     assert np.isfinite(res["cost"][0, n - 1]), "the budget must admit a plan"
     g.gbmw_destroy(ctx)
+
+
+def test_forbidden_padding_changes_nothing(g):
+    """A strategy set padded with forbidden strategies (c = +inf) gives the same trace,
+    costs and plan: how pairs with different strategy sets share one call."""
+    import oracle.bmw as bmw
+    layers = gi.table1_layers("BERT-Huge-32")[:16]
+    hw = gi.default_hardware(unit_mb=16.0)
+    P, Bm, m, E, Lm = 2, 4.0, 8, 384, 16
+    strat = g.gbmw_enumerate_strategies(4)
+    n_s, S = len(strat), 22
+    cm = g.gbmw_cost_model(layers, strat, hw, Bm, P)
+    c = np.full((Lm, S), np.inf, np.float32); c[:, :n_s] = cm["c"]
+    cn = np.full((Lm, S), np.inf, np.float32); cn[:, :n_s] = cm["c_nosync"]
+    R = np.zeros((Lm, S, S), np.float32); R[:, :n_s, :n_s] = cm["R"]
+    M = np.zeros((P, Lm, S), np.int32); M[:, :, :n_s] = cm["M"]
+    p0, p_t = np.array([5, 11], np.int32), np.array([8, 8], np.int32)
+    a, ctx = g.gbmw_partition_search([P], [Lm], [m], cm["c"], cm["c_nosync"], cm["R"], cm["M"].reshape(P * Lm, n_s),
+                                     p0, p_t, n_s, E, max_iter=16)
+    b, ctx = g.gbmw_partition_search([P], [Lm], [m], c, cn, R, M.reshape(P * Lm, S), p0, p_t, S, E, max_iter=16,
+                                     ctx=ctx)
+    for key in ("n_iter", "O_t", "p", "cost", "C", "Cns", "O", "alpha_t", "alpha_m", "strat"):
+        assert np.array_equal(a[key].view(np.uint8), b[key].view(np.uint8)), key
+    assert a["n_iter"][0] > 1 and np.isfinite(a["cost"][0, a["n_iter"][0] - 1])
+    want = bmw.partition_search(dict(c=c, c_ns=cn, R=R, M=M), p0, E, m, p_t=p_t, max_iter=16)
+    assert int(b["n_iter"][0]) == len(want["trace"])
+    assert pins.bits(b["cost"][0, len(want["trace"]) - 1]) == pins.bits(want["trace"][-1]["cost"])
+    assert np.array_equal(b["strat"][0], want["strat"])
+    g.gbmw_destroy(ctx)
