@@ -161,3 +161,23 @@ def test_outer_loops_throughput(g):
     assert np.isfinite(last[6]) or np.isfinite(last[7]), "... although the fourth would fit"
     assert want_g in (0, 1) and res["tpt_pair"] == 2 * want_g + int(np.argmin(last[2 * want_g:2 * want_g + 2]))
     g.gbmw_destroy(ctx)
+
+
+def test_benchmark_workload_all_modes_agree(g):
+    """The workload bench.py times (16 pairs, 48 layers, S = 44, E = 32768): kept tables,
+    every stage re-solved, and no argmin records give the same traces bit for bit; the
+    first pair is also checked against the oracle."""
+    import importlib.util
+    import os
+    spec = importlib.util.spec_from_file_location("bench", os.path.join(os.path.dirname(pins.GOLDEN), "..", "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    models = bench.partition_workload(gi)
+    ref, ctx = _search(g, models, max_iter=32)
+    for flags in (g.GBMW_FLAG_RESOLVE_ALL, g.GBMW_FLAG_LAZY_ARGMIN):
+        res, ctx = _search(g, models, max_iter=32, flags=flags, ctx=ctx)
+        for key in ("n_iter", "O_t", "p", "cost", "C", "Cns", "O", "alpha_t", "alpha_m", "strat"):
+            assert np.array_equal(ref[key].view(np.uint8), res[key].view(np.uint8)), (flags, key)
+    g.gbmw_destroy(ctx)
+    first = {k: (v[:1] if isinstance(v, np.ndarray) else v) for k, v in ref.items()}
+    check_partition_search(first, models[:1], 32)
