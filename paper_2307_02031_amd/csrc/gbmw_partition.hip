@@ -49,23 +49,33 @@ __global__ void k_fill_u32(uint32_t* p, size_t n, uint32_t v) {
   if (i < n) p[i] = v;
 }
 
-// one workgroup per row: c, M and the S x S slab of R of a model layer -> a slot row
+// One workgroup per row: c and M of a model layer -> a slot row, and the layer's R straight
+// into the row's transposed table (Rt[s][s'] = R[s'][s], zero padding, then c(s) and the bits
+// of M(s): the layout the layer kernels read), so that only touched rows are prepared.
 __global__ __launch_bounds__(256) void k_gather(const float* __restrict__ c,
                                                 const int* __restrict__ M,
                                                 const float* __restrict__ R,
                                                 const int* __restrict__ row_src,
                                                 const int* __restrict__ row_msrc,
-                                                const int* __restrict__ row_dst, int S,
+                                                const int* __restrict__ row_dst, int S, int SP, int RS,
                                                 float* __restrict__ c_g, int* __restrict__ M_g,
-                                                float* __restrict__ R_g) {
+                                                float* __restrict__ Rt) {
   const size_t src = (size_t)row_src[blockIdx.x], msrc = (size_t)row_msrc[blockIdx.x];
   const size_t dst = (size_t)row_dst[blockIdx.x];
   for (int i = threadIdx.x; i < S; i += 256) {
     c_g[dst * S + i] = c[src * S + i];
     M_g[dst * S + i] = M[msrc * S + i];
   }
-  const int SS = S * S;
-  for (int i = threadIdx.x; i < SS; i += 256) R_g[dst * SS + i] = R[src * SS + i];
+  const float* __restrict__ Rl = R + src * S * S;
+  float* __restrict__ out = Rt + dst * S * RS;
+  for (int i = threadIdx.x; i < S * RS; i += 256) {
+    const int s = i / RS, sp = i % RS;
+    float v = 0.0f;
+    if (sp < S) v = Rl[(size_t)sp * S + s];
+    else if (sp == SP) v = c[src * S + s];
+    else if (sp == SP + 1) v = __int_as_float(M[msrc * S + s]);
+    out[i] = v;
+  }
 }
 
 // One wave per solved stage: walk its plan at e = E down the argmin records (every lane
@@ -450,14 +460,13 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
 
   // rows of the slots (what the layer kernels read) and the per-round index arrays
   const size_t rows = (size_t)rows_total;
-  float *gc = nullptr, *gR = nullptr;
+  float* gc = nullptr;
   int *gM = nullptr, *g_src = nullptr, *g_msrc = nullptr, *g_dst = nullptr, *g_touched = nullptr,
       *g_chain = nullptr, *g_first = nullptr, *g_group = nullptr;
   float *g_batch = nullptr, *g_tpt = nullptr;
   auto carve_gather = [&](Carver& w) {
     gc = w.take<float>(rows * d.S);
     gM = w.take<int>(rows * d.S);
-    gR = w.take<float>(rows * d.S * d.S);
     g_src = w.take<int>(rows);
     g_msrc = w.take<int>(rows);
     g_dst = w.take<int>(rows);
@@ -525,8 +534,10 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
                      (uint32_t*)s.live, d.n, 1u);
   hipLaunchKernelGGL(gbmw::k_fill_u32, dim3((unsigned)((d.n + 255) / 256)), dim3(256), 0, st,
                      (uint32_t*)s.Ot, d.n, (uint32_t)INT_MAX);      // no limit 3 until p_t is searched
+  hipLaunchKernelGGL(gbmw::k_fill_u32, dim3(1), dim3(256), 0, st, (uint32_t*)c->d_status.p, (size_t)1, 0u);
   // every row of the slots is readable from the start (rows beyond a stage's layers are never used)
-  for (auto [ptr, words] : {std::pair<void*, size_t>{gc, rows * d.S}, {gM, rows * d.S}, {gR, rows * d.S * d.S}})
+  for (auto [ptr, words] : {std::pair<void*, size_t>{gc, rows * d.S}, {gM, rows * d.S},
+                            {c->d_Rt.p, rows * d.S * (size_t)RS}})
     hipLaunchKernelGGL(gbmw::k_fill_u32, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st,
                        (uint32_t*)ptr, words, 0u);
   HIP_TRY_B(hipGetLastError());
@@ -608,9 +619,7 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
       HIP_TRY(hipMemcpyAsync(g_msrc, h_msrc.data(), sizeof(int) * nrows, H2D, st));
       HIP_TRY(hipMemcpyAsync(g_dst, h_dst.data(), sizeof(int) * nrows, H2D, st));
       hipLaunchKernelGGL(gbmw::k_gather, dim3(nrows), dim3(256), 0, st, dc, dM, dR, g_src, g_msrc, g_dst, S,
-                         gc, gM, gR);
-      // inputs were validated on the host; rows outside the stages hold zeros
-      gbmw::launch_prepare(t, gR, (int)rows, false, st);
+                         SP, RS, gc, gM, (float*)c->d_Rt.p);
     }
     // layer 0 goes to memory where something reads it from there
     for (int g = 0; g < G; ++g) {
