@@ -20,6 +20,7 @@ Memory layout of a :class:`Problem` (all C-contiguous):
 """
 from __future__ import annotations
 
+import dataclasses
 from dataclasses import dataclass
 
 import numpy as np
@@ -27,7 +28,7 @@ import numpy as np
 __all__ = [
     "Problem", "Stream", "make_config", "random_instance", "stack", "split_memory",
     "CONFIG_NAMES", "PipelineModel", "random_pipeline_model", "structured_pipeline_model",
-    "uniform_pipeline_model", "proportional_partition", "TABLE1", "table1_layers", "default_hardware",
+    "uniform_pipeline_model", "with_memory_split", "proportional_partition", "TABLE1", "table1_layers", "default_hardware",
 ]
 
 _MASK = np.uint64(0xFFFFFFFFFFFFFFFF)
@@ -260,7 +261,10 @@ def split_memory(p: Problem, seed: int, ob_max: int | None = None):
 class PipelineModel:
     """One (batch size, PP degree) pair: Lm layers, P stages, m micro-batches.
     c, c_ns float32 [Lm][S]; R float32 [Lm][S][S]; M int32 [P][Lm][S];
-    p0, p_t int32 [P] (initial and time-balanced partition: layers per stage)."""
+    p0, p_t int32 [P] (initial and time-balanced partition: layers per stage).
+    Ob, Oms: optional int32 [P][Lm][S] (backward activations and model states,
+    the latter a part of M) for stage searches with the overall-memory check of
+    Appendix A."""
     S: int
     E: int
     P: int
@@ -272,6 +276,8 @@ class PipelineModel:
     p0: np.ndarray
     p_t: np.ndarray | None
     name: str = ""
+    Ob: np.ndarray | None = None
+    Oms: np.ndarray | None = None
 
     def __post_init__(self):
         self.c = np.ascontiguousarray(self.c, dtype=np.float32)
@@ -292,7 +298,24 @@ class PipelineModel:
         return self.c.shape[0]
 
     def as_dict(self) -> dict:
-        return dict(c=self.c, c_ns=self.c_ns, R=self.R, M=self.M)
+        d = dict(c=self.c, c_ns=self.c_ns, R=self.R, M=self.M)
+        if self.Ob is not None:
+            d.update(Ob=self.Ob, Oms=self.Oms)
+        return d
+
+
+def with_memory_split(mod: PipelineModel, seed: int, ob_max: int | None = None) -> PipelineModel:
+    """The same model with synthetic O_b and O_ms tables [P][Lm][S]: the
+    model-state share of every M entry is a uniform fraction of it (so that
+    0 <= O_ms <= M), O_b ~ U{0..ob_max} (default: the largest M of the last
+    stage), drawn per stage as well so that no two stages share a table."""
+    st = Stream(seed, lane=78)
+    frac = st.unit(mod.M.size).reshape(mod.M.shape)
+    Oms = np.floor(mod.M.astype(np.float64) * frac).astype(np.int32)
+    hi = max(1, int(mod.M[-1].max())) if ob_max is None else ob_max
+    Ob = st.integers(mod.M.size, 0, hi).reshape(mod.M.shape).astype(np.int32)
+    return dataclasses.replace(mod, Ob=np.ascontiguousarray(Ob), Oms=np.ascontiguousarray(Oms),
+                               name=mod.name + "+split")
 
 
 def proportional_partition(Lm: int, weights) -> np.ndarray:

@@ -15,13 +15,18 @@ R [Lm][S][S] (R[l][s'][s]: layer l-1 under s' to layer l under s; not charged
 for the first layer of a stage), M [P][Lm][S] (memory of layer l under s when
 it sits in stage i: under 1F1B a shallower stage stashes more activations).
 
+With the optional tables O_b and O_ms [P][Lm][S] in the model (O_f = M - O_ms;
+Eq. 2) a stage is searched as Appendix A, Algorithm 3 does it: the plan is read
+at the largest forward budget whose overall memory E_all fits E, and the memory
+of a stage, in the balance degrees and in limits 2 and 3, is E_all of its plan.
+
 Where the paper leaves a choice open, the reading taken is marked READING.
 """
 from __future__ import annotations
 
 import numpy as np
 
-from . import pipeline_cost, plan_cost, solve
+from . import e_all, pipeline_cost, plan_cost, select_budget, solve
 
 INT_MAX = 2**31 - 1
 
@@ -41,7 +46,18 @@ def stage_under_plan(model, i, a, n, strat):
     M = np.ascontiguousarray(model["M"][i][sl])
     C, O = plan_cost(np.ascontiguousarray(model["c"][sl]), M, np.ascontiguousarray(model["R"][sl]), strat[sl])
     Cns, _ = plan_cost(np.ascontiguousarray(model["c_ns"][sl]), M, np.ascontiguousarray(model["R"][sl]), strat[sl])
+    if "Ob" in model:                                      # overall memory of the plan (Eq. 2)
+        Of, Ob, Oms = stage_memory_tables(model, i, sl)
+        O = e_all(Of, Ob, Oms, strat[sl])
     return C, Cns, O
+
+
+def stage_memory_tables(model, i, sl):
+    """O_f, O_b, O_ms of layers sl placed in stage i, with O_f = M - O_ms."""
+    Oms = np.ascontiguousarray(model["Oms"][i][sl])
+    Ob = np.ascontiguousarray(model["Ob"][i][sl])
+    Of = np.ascontiguousarray(model["M"][i][sl] - Oms)
+    return Of, Ob, Oms
 
 
 def galvatron_search(model, p, E, m):
@@ -58,7 +74,11 @@ def galvatron_search(model, p, E, m):
         sl = slice(a, a + n)
         sol = solve(np.ascontiguousarray(model["c"][sl]), np.ascontiguousarray(model["M"][i][sl]),
                     np.ascontiguousarray(model["R"][sl]), E, keep_C=False)
-        plan, cost, mem = sol.backtrack(E)
+        if "Ob" in model:                                  # Algorithm 3: largest valid forward budget
+            Of, Ob, Oms = stage_memory_tables(model, i, sl)
+            _, cost, plan, mem = select_budget(sol, Of, Ob, Oms)
+        else:
+            plan, cost, mem = sol.backtrack(E)
         if np.isinf(cost):
             continue
         strat[sl] = plan

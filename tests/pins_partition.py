@@ -26,7 +26,11 @@ def fixture_model(g, case):
     R[:, np.arange(S), np.arange(S)] = 0.0
     Ms = case.get("M_stage", mo["M_stage"])
     M = np.array([[Ms[i]] * Lm for i in range(P)], np.int32)
-    return dict(c=np.array(mo["c"], np.float32), c_ns=np.array(mo["c_ns"], np.float32), R=R, M=M), mo["m"]
+    model = dict(c=np.array(mo["c"], np.float32), c_ns=np.array(mo["c_ns"], np.float32), R=R, M=M)
+    if "Ob_stage" in case:                       # Algorithm 3 stage searches (Eq. 2's memory split)
+        model["Ob"] = np.array([[case["Ob_stage"][i]] * Lm for i in range(P)], np.int32)
+        model["Oms"] = np.array([[case["Oms_stage"][i]] * Lm for i in range(P)], np.int32)
+    return model, mo["m"]
 
 
 def check_trace_against(case, res):
@@ -208,6 +212,103 @@ def pin_properties(bmw, seeds=range(12)):
     assert n_multi >= 4, "the random models must exercise the adjustment"
 
 
+def _stage_alg3_bruteforce(mod, i, a, n):
+    """Appendix A, Algorithm 3 for layers [a, a+n) in stage i from the list of
+    optimal plans per budget (brute force): (cost, E_all, plan), or None where
+    some budget in the walk has several optimal plans (the result then depends
+    on the tie rule, which other pins cover)."""
+    E = mod.E
+    sl = slice(a, a + n)
+    Oms, Ob = mod.Oms[i][sl], mod.Ob[i][sl]
+    Of = mod.M[i][sl] - Oms
+    opt, argopt = pins.py_bruteforce(mod.c[sl], mod.M[i][sl], mod.R[sl], E)
+    b_up = int(Ob.max())
+    e_opt = E - b_up if E >= b_up else -1
+    for e in range(e_opt + 1, E + 1):
+        if np.isinf(opt[e]):
+            continue
+        if len(argopt[e]) != 1:
+            return None
+        if pins.py_e_all(Of, Ob, Oms, argopt[e][0]) <= E:
+            e_opt = e
+        else:
+            break
+    if e_opt < 0 or np.isinf(opt[e_opt]):
+        return pins.INF, -1, None
+    if len(argopt[e_opt]) != 1:
+        return None
+    plan = argopt[e_opt][0]
+    return opt[e_opt], pins.py_e_all(Of, Ob, Oms, plan), plan
+
+
+def pin_alg3_in_loop(bmw, seeds=range(14)):
+    """Stage searches with the overall-memory check (Appendix A, Algorithm 3;
+    Eq. 2).  (1) With O_b = 0 the overall memory of a plan is its forward
+    memory, every budget is valid and the trace is that of the plain search.
+    (2) With random O_b every stage's (time, memory, plan) is what the
+    algorithm gives on the brute-force list of optimal plans, the memory is
+    E_all <= E, and an accepted move keeps E_all of every stage under the kept
+    strategies within E and O_t."""
+    n_checked = n_bound = n_multi = 0
+    for seed in seeds:
+        st = gi.Stream(7100 + seed)
+        P = int(st.integers(1, 2, 4)[0])
+        Lm = int(st.integers(1, P + 2, 8)[0])
+        S = int(st.integers(1, 2, 3)[0])
+        E = int(st.integers(1, 25, 60)[0])
+        base = gi.random_pipeline_model(100 + seed, Lm, S, P, E=E, m=int(st.integers(1, 1, 6)[0]),
+                                        R_rng=(0.0, 0.5), skew=bool(seed % 2))
+        plain = bmw.partition_search(base.as_dict(), base.p0, E, base.m, p_t=base.p_t, max_iter=32)
+        zero = gi.with_memory_split(base, 40 + seed)
+        zero.Ob[:] = 0
+        res = bmw.partition_search(zero.as_dict(), zero.p0, E, zero.m, p_t=zero.p_t, max_iter=32)
+        assert res["O_t"] == plain["O_t"] and len(res["trace"]) == len(plain["trace"])
+        for t, u in zip(res["trace"], plain["trace"]):
+            assert list(t["p"]) == list(u["p"]) and pins.bits(t["cost"]) == pins.bits(u["cost"])
+            pins.assert_same_f32(t["C"], u["C"]); pins.assert_same_f32(t["Cns"], u["Cns"])
+            assert [int(x) for x in t["O"]] == [int(x) for x in u["O"]]
+        assert np.array_equal(res["strat"], plain["strat"])
+
+        mod = gi.with_memory_split(base, 60 + seed, ob_max=int(st.integers(1, 2, 12)[0]))
+        res = bmw.partition_search(mod.as_dict(), mod.p0, E, mod.m, p_t=mod.p_t, max_iter=32)
+        tr = res["trace"]
+        n_multi += len(tr) > 1
+        for k, t in enumerate(tr):
+            a = 0
+            for i, n in enumerate(t["p"]):
+                want = _stage_alg3_bruteforce(mod, i, a, n)
+                if want is not None:
+                    v, mem, plan = want
+                    n_checked += 1
+                    assert pins.bits(t["C"][i]) == pins.bits(v), (seed, k, i)
+                    assert int(t["O"][i]) == mem and mem <= E
+                    if plan is not None:
+                        plain_best, _ = _stage_bruteforce(mod, i, a, n, E)
+                        n_bound += plain_best[0] < v          # the check made the stage slower
+                        if k == len(tr) - 1:
+                            assert [int(x) for x in res["strat"][a:a + n]] == list(plan)
+                a += n
+        # accepted moves: E_all under the kept strategies within the limits (needs the
+        # strategies of every round: recompute them stage by stage from the brute force)
+        for k in range(1, len(tr)):
+            q, p = tr[k]["p"], tr[k - 1]["p"]
+            kept, a, ok = [], 0, True
+            for i, n in enumerate(p):
+                want = _stage_alg3_bruteforce(mod, i, a, n)
+                ok = ok and want is not None and want[2] is not None
+                kept += list(want[2]) if ok else []
+                a += n
+            if not ok:
+                continue
+            a = 0
+            for i, n in enumerate(q):
+                sl = slice(a, a + n)
+                ea = pins.py_e_all(mod.M[i][sl] - mod.Oms[i][sl], mod.Ob[i][sl], mod.Oms[i][sl], kept[sl])
+                assert ea <= E and ea <= res["O_t"], (seed, k, i)
+                a += n
+    assert n_checked >= 30 and n_bound >= 3 and n_multi >= 3, (n_checked, n_bound, n_multi)
+
+
 def pin_throughput(bmw):
     """Outer loops: best pipeline time over the PP degrees per batch size, the
     best batch/time, stopping at the first batch size with no feasible degree."""
@@ -228,4 +329,5 @@ def run_all(bmw):
     pin_uniform_memory_limits(bmw)
     pin_uniform_three_stages(bmw)
     pin_properties(bmw)
+    pin_alg3_in_loop(bmw)
     pin_throughput(bmw)

@@ -27,6 +27,10 @@ def test_properties_and_stage_bruteforce():
     pp.pin_properties(oracle.bmw)
 
 
+def test_alg3_stage_searches_in_the_loop():
+    pp.pin_alg3_in_loop(oracle.bmw)
+
+
 def test_throughput():
     pp.pin_throughput(oracle.bmw)
 
@@ -59,6 +63,18 @@ MUTANTS = [
     ("loop goes on after an infeasible search", [("        if not feasible:\n            break\n", "")]),
     ("max_iter ignored", [("while Q and len(trace) < max_iter:", "while Q:")]),
     ("throughput keeps going after out-of-memory", [("        if np.isinf(c_opt):\n            break", "        if np.isinf(c_opt):\n            continue")]),
+    ("Algorithm 3: plan read at e = E although its overall memory does not fit",
+     [("_, cost, plan, mem = select_budget(sol, Of, Ob, Oms)", "plan, cost, mem = sol.backtrack(E)")]),
+    ("Algorithm 3: stage memory is the forward memory, not E_all",
+     [("_, cost, plan, mem = select_budget(sol, Of, Ob, Oms)", "_, cost, plan, _ = select_budget(sol, Of, Ob, Oms); mem = int(sum(model[\"M\"][i][a + k][plan[k]] for k in range(n)))")]),
+    ("Algorithm 3: validate checks the forward memory only",
+     [("        O = e_all(Of, Ob, Oms, strat[sl])\n", "        O = O\n")]),
+    ("Algorithm 3: backward activations of stage 0",
+     [('Ob = np.ascontiguousarray(model["Ob"][i][sl])', 'Ob = np.ascontiguousarray(model["Ob"][0][sl])')]),
+    ("Algorithm 3: model states of stage 0",
+     [('Oms = np.ascontiguousarray(model["Oms"][i][sl])', 'Oms = np.ascontiguousarray(model["Oms"][0][sl])')]),
+    ("Algorithm 3: O_f taken as all of M",
+     [('Of = np.ascontiguousarray(model["M"][i][sl] - Oms)', 'Of = np.ascontiguousarray(model["M"][i][sl])')]),
     ("throughput takes the worst degree", [("c_opt = np.float32(min(", "c_opt = np.float32(max(")]),
 ]
 
