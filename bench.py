@@ -107,15 +107,23 @@ def partition_leg(g, gi, cpu: bool, budget_s=10.0):
              cns=np.concatenate([m.c_ns for m in models]), R=np.concatenate([m.R for m in models]),
              M=np.concatenate([m.M.reshape(m.P * m.Lm, S) for m in models]),
              p0=np.concatenate([m.p0 for m in models]), p_t=np.concatenate([m.p_t for m in models]))
+    # the same pairs with synthetic O_b / O_ms tables, for stage searches with Appendix A's check
+    split = [gi.with_memory_split(m, 900 + k) for k, m in enumerate(models)]
+    a["O_b"] = np.concatenate([m.Ob.reshape(m.P * m.Lm, S) for m in split])
+    a["O_ms"] = np.concatenate([m.Oms.reshape(m.P * m.Lm, S) for m in split])
     out = {"workload": "16 pairs: 48 layers, S=44, E=32768, PP 2/4/8/16 x 4 activation scales, max_iter 32"}
     ctx = None
-    for name, flags in (("changed_stages", 0), ("resolve_all", g.GBMW_FLAG_RESOLVE_ALL),
-                        ("changed_stages_lazy_argmin", g.GBMW_FLAG_LAZY_ARGMIN)):
+    for name, flags, overall in (("changed_stages", 0, False), ("resolve_all", g.GBMW_FLAG_RESOLVE_ALL, False),
+                                 ("changed_stages_lazy_argmin", g.GBMW_FLAG_LAZY_ARGMIN, False),
+                                 ("changed_stages_overall_memory", 0, True),
+                                 ("changed_stages_overall_memory_lazy_argmin", g.GBMW_FLAG_LAZY_ARGMIN, True)):
         best = None
         for _ in range(3):
             t0 = time.perf_counter()
             res, ctx = g.gbmw_partition_search(a["P"], a["Lm"], a["m"], a["c"], a["cns"], a["R"], a["M"], a["p0"],
-                                               a["p_t"], S, E, max_iter=32, flags=flags, ctx=ctx)
+                                               a["p_t"], S, E, max_iter=32, flags=flags, ctx=ctx,
+                                               O_b=a["O_b"] if overall else None,
+                                               O_ms=a["O_ms"] if overall else None)
             dt = time.perf_counter() - t0
             best = dt if best is None else min(best, dt)
         out[name] = {"ms": best * 1e3, "device_ms": res["device_ms"], "rounds": res["rounds"],
@@ -152,14 +160,18 @@ def whole_search_leg(g, gi):
     paper_s = {24: 280.59, 48: 537.91, 72: 825.86, 96: 1104.92}
     out = {"setup": "BERT-Huge layer repeated L times, 8 devices, E = 16384 units of 1 MB, 8 batch sizes "
                     "x PP 1/2/4/8, 8 micro-batches, max_iter 32",
+           "stage_searches": "Appendix A, Algorithm 3 (overall-memory check) with the cost model's O_b and O_ms",
            "paper_fig5a_16G_seconds": paper_s, "ours": {}}
     for L in (24, 48, 72, 96):
         layers = gi.table1_layers("BERT-Huge-32", layers=L)
         plan(g, gi, layers, 8, 16384, hw, batches[:2], 8)                 # warm-up: allocations
         t0 = time.perf_counter()
+        plan(g, gi, layers, 8, 16384, hw, batches, 8, overall=False)
+        dt_fwd = time.perf_counter() - t0
+        t0 = time.perf_counter()
         best, _, st = plan(g, gi, layers, 8, 16384, hw, batches, 8)
         dt = time.perf_counter() - t0
-        out["ours"][L] = {"seconds": dt, "device_ms": st["device_ms"], "partitions_searched": st["partitions"],
+        out["ours"][L] = {"seconds": dt, "seconds_without_overall_memory_check": dt_fwd, "device_ms": st["device_ms"], "partitions_searched": st["partitions"],
                           "stage_solves": st["stage_solves"], "cell_updates": st["cell_updates"],
                           "pairs": st["pairs"], "rounds": st["rounds"],
                           "best": None if best is None else {"batch": best["B"], "P": best["P"],

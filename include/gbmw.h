@@ -246,6 +246,16 @@ typedef struct {
    * batch sizes are tried and batch_group is non-decreasing over the pairs.           */
   const float* batch_size;    /* [n_chain] global batch size B of the pair's group, > 0  */
   const int32_t* batch_group; /* [n_chain] group of each pair                            */
+  /* Stage searches with the overall-memory check of Appendix A, Algorithm 3 (optional,
+   * both or neither; indexed like M).  M is then the forward memory O_f + O_ms of Eq. 2,
+   * O_ms its model-state part and O_b the backward activations.  Every stage's plan is
+   * read at the largest forward budget e <= E whose plan has E_all <= E (walking up
+   * from E - max O_b of the stage's layers; budgets without a plan are passed over, the
+   * walk stops at the first plan that does not fit), and the memory of a stage -- the
+   * O output, alpha_m, limits 2 and 3, O_t -- is E_all of its plan instead of its
+   * forward memory.                                                                   */
+  const int32_t* O_b;         /* [sum P*Lm][S] >= 0                                      */
+  const int32_t* O_ms;        /* [sum P*Lm][S] 0 <= O_ms <= M                            */
 } gbmw_partition_problem;
 
 /* Outputs of gbmw_partition_search; HOST memory owned by the caller.  Pmax = max P_k,
@@ -283,8 +293,8 @@ typedef struct {
  * buffers of the table solves and of the search state and can be handed to later
  * calls of either kind; after the call it holds no solution.  Inputs are
  * validated on the host first (GBMW_ERR_INVALID_ARG: NaN or negative c / c_nosync
- * / R, negative M, a partition with an empty stage or the wrong sum, sizes out of
- * range).
+ * / R, negative M, O_b or O_ms, O_ms above M, a partition with an empty stage or
+ * the wrong sum, sizes out of range).
  */
 gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, uint32_t flags,
                                   gbmw_partition_result* out, gbmw_ctx** ctx);

@@ -50,7 +50,7 @@ class gbmw_partition_problem(ct.Structure):
                 ("P", ct.c_void_p), ("Lm", ct.c_void_p), ("m", ct.c_void_p), ("c", ct.c_void_p),
                 ("c_nosync", ct.c_void_p), ("R", ct.c_void_p), ("M", ct.c_void_p), ("p0", ct.c_void_p),
                 ("p_t", ct.c_void_p), ("stream", ct.c_void_p), ("batch_size", ct.c_void_p),
-                ("batch_group", ct.c_void_p)]
+                ("batch_group", ct.c_void_p), ("O_b", ct.c_void_p), ("O_ms", ct.c_void_p)]
 
 
 class gbmw_partition_result(ct.Structure):
@@ -253,28 +253,31 @@ def gbmw_pipeline_cost(ctx: Context, stage_begin, stage_instance, stage_e, micro
 
 def gbmw_partition_search(P, Lm, m, c, c_nosync, R, M, p0, p_t, S: int, E: int, max_iter: int = 64,
                           flags: int = 0, ctx: Context | None = None, stream: int | None = None,
-                          batch_size=None, batch_group=None):
+                          batch_size=None, batch_group=None, O_b=None, O_ms=None):
     """Algorithm 2's inner loop for n_chain = len(P) pairs (host numpy arrays, the
-    pairs' rows concatenated; c_nosync and p_t may be None).  Returns (result dict,
+    pairs' rows concatenated; c_nosync and p_t may be None; O_b and O_ms, shaped like M,
+    switch the stage searches to Appendix A's forward-budget selection).  Returns (result dict,
     ctx): n_iter, O_t [n]; p, C, Cns, O [n][max_iter][Pmax]; cost, alpha_t, alpha_m
     [n][max_iter]; strat [n][Lmmax]; rounds, stage_solves, cell_updates, device_ms."""
     i32 = lambda a: None if a is None else np.ascontiguousarray(a, dtype=np.int32)
     f32 = lambda a: None if a is None else np.ascontiguousarray(a, dtype=np.float32)
     P, Lm, m, M, p0, p_t = (i32(a) for a in (P, Lm, m, M, p0, p_t))
     c, c_nosync, R, batch_size = (f32(a) for a in (c, c_nosync, R, batch_size))
-    batch_group = i32(batch_group)
+    batch_group, O_b, O_ms = i32(batch_group), i32(O_b), i32(O_ms)
     n, sumLm, sumP = len(P), int(Lm.sum()), int(P.sum())
     sumPL = int((P.astype(np.int64) * Lm).sum())
     assert Lm.shape == m.shape == (n,) and c.shape == (sumLm, S) and R.shape == (sumLm, S, S)
     assert M.shape == (sumPL, S) and p0.shape == (sumP,)
     assert c_nosync is None or c_nosync.shape == c.shape
     assert p_t is None or p_t.shape == p0.shape
+    assert (O_b is None or O_b.shape == M.shape) and (O_ms is None or O_ms.shape == M.shape)
     Pmax, Lmmax = int(P.max()), int(Lm.max())
     if stream is None:
         stream = torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else 0
     ptr = lambda a: None if a is None else a.ctypes.data
     q = gbmw_partition_problem(n, S, E, max_iter, ptr(P), ptr(Lm), ptr(m), ptr(c), ptr(c_nosync), ptr(R),
-                               ptr(M), ptr(p0), ptr(p_t), stream, ptr(batch_size), ptr(batch_group))
+                               ptr(M), ptr(p0), ptr(p_t), stream, ptr(batch_size), ptr(batch_group),
+                               ptr(O_b), ptr(O_ms))
     mi = max(1, max_iter)
     res = dict(n_iter=np.zeros(n, np.int32), O_t=np.zeros(n, np.int32),
                p=np.zeros((n, mi, Pmax), np.int32), cost=np.zeros((n, mi), np.float32),

@@ -15,7 +15,10 @@
 // value runs in kernels:
 //   k_gather        rows of the resident model -> the rows of the touched slots
 //   table solve     the layer kernels of gbmw_kernels.hip on the touched slots
-//   k_stage_result  plan at e = E of every touched stage -> strategies, C, Cns, O
+//   k_stage_bup / k_stage_check   with O_b / O_ms tables: Appendix A, Algorithm 3's walk over
+//                   the forward budgets (the first one whose plan's overall memory exceeds E)
+//   k_stage_result  plan at e = E (at the budget that walk chose) of every touched stage
+//                   -> strategies, C, Cns, O
 //   k_chain_step    Eq. 8, Eq. 6, PP_Partition_Adjust, Validate, trace entry
 #include <algorithm>
 #include <climits>
@@ -33,6 +36,10 @@ struct Search {
   const int *P, *Lm, *m, *lrow, *prow, *mrow;      // [n_chain]
   const float *c, *cns, *R;                        // resident model (cns may be null)
   const int* M;
+  const int *Ob, *Oms;                             // resident, indexed like M; null: plain search
+  int *Ob_g, *Oms_g;                               // rows of the slots, like Tables::M
+  int *bup, *first_bad;                            // [sumP] per slot: largest O_b of its layers; lowest
+                                                   // checked budget whose plan does not fit (INT_MAX: none)
   int* part;                                       // [sumP] partition being searched
   int* Ot;                                         // [n_chain]
   float *stC, *stCns;                              // [sumP] results of the current stages
@@ -59,12 +66,18 @@ __global__ __launch_bounds__(256) void k_gather(const float* __restrict__ c,
                                                 const int* __restrict__ row_msrc,
                                                 const int* __restrict__ row_dst, int S, int SP, int RS,
                                                 float* __restrict__ c_g, int* __restrict__ M_g,
-                                                float* __restrict__ Rt) {
+                                                float* __restrict__ Rt,
+                                                const int* __restrict__ Ob, const int* __restrict__ Oms,
+                                                int* __restrict__ Ob_g, int* __restrict__ Oms_g) {
   const size_t src = (size_t)row_src[blockIdx.x], msrc = (size_t)row_msrc[blockIdx.x];
   const size_t dst = (size_t)row_dst[blockIdx.x];
   for (int i = threadIdx.x; i < S; i += 256) {
     c_g[dst * S + i] = c[src * S + i];
     M_g[dst * S + i] = M[msrc * S + i];
+    if (Ob) {
+      Ob_g[dst * S + i] = Ob[msrc * S + i];
+      Oms_g[dst * S + i] = Oms[msrc * S + i];
+    }
   }
   const float* __restrict__ Rl = R + src * S * S;
   float* __restrict__ out = Rt + dst * S * RS;
@@ -78,10 +91,81 @@ __global__ __launch_bounds__(256) void k_gather(const float* __restrict__ c,
   }
 }
 
-// One wave per solved stage: walk its plan at e = E down the argmin records (every lane
-// walks the same plan; without records the lanes share each step's recomputation),
-// leave the strategies in the model-wide array, the stage's time, memory and
-// time without gradient synchronisation in the pair's stage slots.
+// Overall memory (Eq. 2) of the plan of slot b at forward budget e, one lane on its own.
+// Going from the last layer to the first, the forward prefix of layer i is F - suf_i with F
+// the sum of all O_f and suf_i the sum over the layers above i, so
+//   E_all = F + max_i (O_b(i) - suf_i) + sum O_ms.
+__device__ long long plan_e_all(const Tables& t, const Search& s, int b, int e) {
+  const int n = t.L[b], row0 = t.off[b], S = t.S;
+  int sx = t.best_s[(size_t)b * t.EP + e];
+  long long suf = 0, ms = 0, mx = 0;
+  for (int l = n - 1; l >= 0; --l) {
+    const size_t cell = (size_t)(row0 + l) * S + sx;
+    const int m = t.M[cell], oms = s.Oms_g[cell];
+    const long long here = (long long)s.Ob_g[cell] - suf;
+    mx = (l == n - 1 || here > mx) ? here : mx;
+    suf += m - oms;
+    ms += oms;
+    if (l > 0) {
+      e -= m;                                              // budget left for layers < l
+      if (m < 0 || e < 0) return -2;                       // only reachable with invalid inputs
+      sx = pred_strategy(t, row0 + l, sx, e);
+    }
+  }
+  return suf + mx + ms;
+}
+
+// Algorithm 3's walk over the forward budgets, in three launches per round.  Plans up to
+// E - b_up (b_up = the stage's largest O_b) fit without a check; above it every budget's plan
+// is walked and its overall memory compared with E, and the first one that does not fit ends
+// the walk.
+// k_stage_bup: one wave per touched stage: b_up, and no failing budget known yet.
+__global__ __launch_bounds__(64) void k_stage_bup(Tables t, Search s, const int* __restrict__ touched) {
+  const int lane = threadIdx.x;
+  const int b = touched[blockIdx.x];
+  const int n = t.L[b], S = t.S, row0 = t.off[b];
+  int bup = 0;
+  for (int i = lane; i < n * S; i += 64) {
+    const int v = s.Ob_g[(size_t)row0 * S + i];
+    bup = v > bup ? v : bup;
+  }
+  for (int d = 32; d >= 1; d >>= 1) {
+    const int o = __shfl_xor(bup, d, 64);
+    bup = o > bup ? o : bup;
+  }
+  if (lane == 0) {
+    s.bup[b] = bup;
+    s.first_bad[b] = INT_MAX;
+  }
+}
+
+// k_stage_check: one wave per (touched stage, 64 budgets of its window), one lane per budget.
+// The lowest failing budget of a stage is the minimum over its waves; a wave whose budgets lie
+// above a failure already recorded has nothing to add and leaves at once.
+__global__ __launch_bounds__(64) void k_stage_check(Tables t, Search s, const int* __restrict__ touched) {
+  const int lane = threadIdx.x;
+  const int b = touched[blockIdx.y];
+  const int bup = s.bup[b];
+  const int init = t.E >= bup ? t.E - bup : -1;
+  const int base = init + 1 + (int)blockIdx.x * 64;
+  if (base > t.E) return;
+  if (*(volatile const int*)&s.first_bad[b] < base) return;
+  const int e = base + lane;
+  bool bad = false;
+  if (e <= t.E && t.best[(size_t)b * t.EP + e] != INFINITY) {   // no plan: nothing to check
+    const long long ea = plan_e_all(t, s, b, e);
+    bad = ea > (long long)t.E || ea < 0;
+  }
+  const unsigned long long hit = __ballot(bad);
+  if (hit && lane == 0) atomicMin(&s.first_bad[b], base + __ffsll((long long)hit) - 1);
+}
+
+// One wave per solved stage.  The budget the plan is read at is E, or, with O_b / O_ms
+// tables, the last budget below the first failing one that has a plan (E - b_up if there is
+// none above it).  The wave walks that plan down the argmin records (every lane the same
+// plan; without records the lanes share each step's recomputation) and leaves the strategies
+// in the model-wide array, the stage's time, memory and time without gradient
+// synchronisation in the pair's stage slots.
 __global__ __launch_bounds__(64) void k_stage_result(Tables t, Search s,
                                                      const int* __restrict__ touched, int nt,
                                                      const int* __restrict__ slot_chain,
@@ -91,24 +175,41 @@ __global__ __launch_bounds__(64) void k_stage_result(Tables t, Search s,
   const int k = slot_chain[b], a = slot_first[b], n = t.L[b], S = t.S;
   const size_t lrow = (size_t)s.lrow[k] + a;
   const int slot = b;
+  const int row0 = t.off[b];
+  const float* best = t.best + (size_t)b * t.EP;
   uint8_t* st = s.strat + lrow;
-  float C = t.best[(size_t)b * t.EP + t.E];
-  int mem = 0;
+  int e_sel = t.E;
+  if (s.Ob_g) {
+    const int bup = s.bup[b], first_bad = s.first_bad[b];
+    const int init = t.E >= bup ? t.E - bup : -1;
+    const int last = first_bad == INT_MAX ? t.E : first_bad - 1;
+    e_sel = (last > init && best[last] != INFINITY) ? last : init;
+  }
+  float C = e_sel >= 0 ? best[e_sel] : INFINITY;
+  long long mem = 0;
   if (C != INFINITY) {
-    int sx = t.best_s[(size_t)b * t.EP + t.E], e = t.E;
-    const int row0 = t.off[b];
-    for (int l = n - 1; l >= 1; --l) {
+    int sx = t.best_s[(size_t)b * t.EP + e_sel], e = e_sel;
+    long long suf = 0, ms = 0, mx = 0;
+    for (int l = n - 1; l >= 0; --l) {
       st[l] = (uint8_t)sx;
-      const int m = t.M[(size_t)(row0 + l) * S + sx];
-      mem += m;
-      e -= m;                                            // budget left for layers < l
-      if (m < 0 || e < 0) { C = INFINITY; break; }       // only reachable with invalid inputs
-      sx = pred_strategy_wave(t, row0 + l, sx, e, lane);
+      const size_t cell = (size_t)(row0 + l) * S + sx;
+      const int m = t.M[cell];
+      if (s.Ob_g) {
+        const int oms = s.Oms_g[cell];
+        const long long here = (long long)s.Ob_g[cell] - suf;
+        mx = (l == n - 1 || here > mx) ? here : mx;
+        suf += m - oms;
+        ms += oms;
+      } else {
+        suf += m;
+      }
+      if (l > 0) {
+        e -= m;                                            // budget left for layers < l
+        if (m < 0 || e < 0) { C = INFINITY; break; }       // only reachable with invalid inputs
+        sx = pred_strategy_wave(t, row0 + l, sx, e, lane);
+      }
     }
-    if (C != INFINITY) {
-      st[0] = (uint8_t)sx;
-      mem += t.M[(size_t)row0 * S + sx];
-    }
+    mem = suf + mx + ms;
   }
   if (C == INFINITY) {
     for (int l = 0; l < n; ++l) st[l] = 0xFF;
@@ -131,7 +232,7 @@ __global__ __launch_bounds__(64) void k_stage_result(Tables t, Search s,
   }
   s.stC[slot] = C;
   s.stCns[slot] = Cns;
-  s.stO[slot] = mem;
+  s.stO[slot] = (int)mem;
 }
 
 // One wave per pair; lane i works on stage i (P <= 64).  phase 0: the searched partition
@@ -218,14 +319,26 @@ __global__ __launch_bounds__(64) void k_chain_step(Search s, int phase) {
     const uint8_t* st = s.strat + lrow;
     int sp = st[a];
     float v = s.c[(lrow + a) * S + sp];
-    long long mem = s.M[(mr + a) * S + sp];
+    // memory: the sum of M, or with O_b / O_ms tables the overall memory of Eq. 2:
+    // max over the layers of (forward activations so far + own backward) + all model states
+    long long fwd = 0, ms = 0, peak = 0;
+    auto account = [&](int l, int sx) {
+      const size_t cell = (mr + l) * S + sx;
+      const long long oms = s.Ob ? s.Oms[cell] : 0;
+      fwd += s.M[cell] - oms;
+      ms += oms;
+      const long long here = fwd + (s.Ob ? s.Ob[cell] : 0);
+      peak = here > peak ? here : peak;
+    };
+    account(a, sp);
     for (int l = a + 1; l < a + q_own; ++l) {
       const int sn = st[l];
       const float r = s.R[((lrow + l) * S + sp) * S + sn];
       v = (v + r) + s.c[(lrow + l) * S + sn];
-      mem += s.M[(mr + l) * S + sn];
+      account(l, sn);
       sp = sn;
     }
+    const long long mem = peak + ms;
     ok = v <= cmax && mem <= (long long)s.E && mem <= (long long)s.Ot[k];
   }
   if (__ballot(!ok) != 0) return;
@@ -287,20 +400,23 @@ struct Dims {
 
 // The resident copy of the model and of the pairs' descriptions.
 struct ModelOnDevice {
-  int *P, *Lm, *m, *lrow, *prow, *mrow, *M;
+  int *P, *Lm, *m, *lrow, *prow, *mrow, *M, *Ob, *Oms;
   float *c, *cns, *R;
   uint32_t* zero_begin;      // the part of the state that starts as zero
   size_t zero_words;
 };
 
 // One layout for sizing (base == nullptr) and for carving.
-size_t carve_search(Carver& cv, const Dims& d, bool with_cns, gbmw::Search& s, ModelOnDevice& md) {
+size_t carve_search(Carver& cv, const Dims& d, bool with_cns, bool with_split, gbmw::Search& s,
+                    ModelOnDevice& md) {
   md.P = cv.take<int>(d.n); md.Lm = cv.take<int>(d.n); md.m = cv.take<int>(d.n);
   md.lrow = cv.take<int>(d.n); md.prow = cv.take<int>(d.n); md.mrow = cv.take<int>(d.n);
   md.c = cv.take<float>(d.sumLm * d.S);
   md.cns = with_cns ? cv.take<float>(d.sumLm * d.S) : nullptr;
   md.R = cv.take<float>(d.sumLm * d.S * d.S);
   md.M = cv.take<int>(d.sumPL * d.S);
+  md.Ob = with_split ? cv.take<int>(d.sumPL * d.S) : nullptr;
+  md.Oms = with_split ? cv.take<int>(d.sumPL * d.S) : nullptr;
   s.part = cv.take<int>(d.sumP);
   s.stC = cv.take<float>(d.sumP);
   s.stCns = cv.take<float>(d.sumP);
@@ -308,6 +424,8 @@ size_t carve_search(Carver& cv, const Dims& d, bool with_cns, gbmw::Search& s, M
   s.strat = cv.take<uint8_t>(d.sumLm);
   s.moved = cv.take<int>(2 * d.n);
   s.live = cv.take<int>(d.n);
+  s.bup = with_split ? cv.take<int>(d.sumP) : nullptr;
+  s.first_bad = with_split ? cv.take<int>(d.sumP) : nullptr;
   // everything from here on starts as zero
   cv.used = (cv.used + 255) / 256 * 256;
   const size_t z0 = cv.used;
@@ -385,8 +503,19 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
     if (!(q->c[i] >= 0.0f)) return fail(GBMW_ERR_INVALID_ARG, "c[%zu] is NaN or negative", i);
     if (q->c_nosync && !(q->c_nosync[i] >= 0.0f)) return fail(GBMW_ERR_INVALID_ARG, "c_nosync[%zu] is NaN or negative", i);
   }
-  for (size_t i = 0; i < (size_t)sumPL * S; ++i)
+  if ((q->O_b == nullptr) != (q->O_ms == nullptr))
+    return fail(GBMW_ERR_INVALID_ARG, "O_b and O_ms go together");
+  const bool split = q->O_b != nullptr;
+  int ob_max = 0;                                    // sizes the range of budgets the final reduce fills
+  for (size_t i = 0; i < (size_t)sumPL * S; ++i) {
     if (q->M[i] < 0) return fail(GBMW_ERR_INVALID_ARG, "M[%zu] is negative", i);
+    if (split) {
+      if (q->O_b[i] < 0) return fail(GBMW_ERR_INVALID_ARG, "O_b[%zu] is negative", i);
+      if (q->O_ms[i] < 0 || q->O_ms[i] > q->M[i])
+        return fail(GBMW_ERR_INVALID_ARG, "O_ms[%zu] is not in 0..M", i);
+      ob_max = std::max(ob_max, q->O_b[i]);
+    }
+  }
   for (int k = 0; k < n; ++k)          // the slab of the model's first layer is never used
     for (size_t i = ((size_t)lrow[k] + 1) * S * S; i < ((size_t)lrow[k] + q->Lm[k]) * S * S; ++i)
       if (!(q->R[i] >= 0.0f)) return fail(GBMW_ERR_INVALID_ARG, "R[%zu] is NaN or negative", i);
@@ -447,12 +576,12 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
   ModelOnDevice md{};
   {
     Carver sizing(nullptr);
-    TRY(c->d_search.reserve(carve_search(sizing, d, q->c_nosync != nullptr, s, md)));
+    TRY(c->d_search.reserve(carve_search(sizing, d, q->c_nosync != nullptr, split, s, md)));
     Carver cv(c->d_search.p);
-    carve_search(cv, d, q->c_nosync != nullptr, s, md);
+    carve_search(cv, d, q->c_nosync != nullptr, split, s, md);
   }
   s.P = md.P; s.Lm = md.Lm; s.m = md.m; s.lrow = md.lrow; s.prow = md.prow; s.mrow = md.mrow;
-  s.c = md.c; s.cns = md.cns; s.R = md.R; s.M = md.M;
+  s.c = md.c; s.cns = md.cns; s.R = md.R; s.M = md.M; s.Ob = md.Ob; s.Oms = md.Oms;
   int *dP = md.P, *dLm = md.Lm, *dm = md.m, *dlrow = md.lrow, *dprow = md.prow, *dmrow = md.mrow, *dM = md.M;
   float *dc = md.c, *dcns = md.cns, *dR = md.R;
   uint32_t* zero_begin = md.zero_begin;
@@ -467,6 +596,8 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
   auto carve_gather = [&](Carver& w) {
     gc = w.take<float>(rows * d.S);
     gM = w.take<int>(rows * d.S);
+    s.Ob_g = split ? w.take<int>(rows * d.S) : nullptr;
+    s.Oms_g = split ? w.take<int>(rows * d.S) : nullptr;
     g_src = w.take<int>(rows);
     g_msrc = w.take<int>(rows);
     g_dst = w.take<int>(rows);
@@ -504,7 +635,8 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
   TRY(gbmw_detail::ensure_streams(c, kFreshGroups));
 
   gbmw::Tables& t = c->t;
-  t.B = B; t.S = S; t.SP = SP; t.RS = RS; t.E = E; t.EP = EP; t.keep_all = lazy ? 1 : 0; t.final_from = E;
+  t.B = B; t.S = S; t.SP = SP; t.RS = RS; t.E = E; t.EP = EP; t.keep_all = lazy ? 1 : 0;
+  t.final_from = std::max(0, E - ob_max);              // Algorithm 3 reads best(e) from E - b_up on
   t.L = (const int*)c->d_L.p; t.off = (const int*)c->d_off.p; t.perm = (const int*)c->d_perm.p;
   t.c = gc; t.M = gM; t.Rt = (const float*)c->d_Rt.p;
   t.Cbuf = (float*)c->d_C.p; t.A = lazy ? nullptr : (uint8_t*)c->d_A.p;
@@ -525,6 +657,10 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
   if (dcns) HIP_TRY_B(hipMemcpyAsync(dcns, q->c_nosync, sizeof(float) * d.sumLm * S, H2D, st));
   HIP_TRY_B(hipMemcpyAsync(dR, q->R, sizeof(float) * d.sumLm * S * S, H2D, st));
   HIP_TRY_B(hipMemcpyAsync(dM, q->M, sizeof(int) * d.sumPL * S, H2D, st));
+  if (split) {
+    HIP_TRY_B(hipMemcpyAsync(md.Ob, q->O_b, sizeof(int) * d.sumPL * S, H2D, st));
+    HIP_TRY_B(hipMemcpyAsync(md.Oms, q->O_ms, sizeof(int) * d.sumPL * S, H2D, st));
+  }
   HIP_TRY_B(hipMemcpyAsync(s.part, q->p0, sizeof(int) * d.sumP, H2D, st));
   HIP_TRY_B(hipMemcpyAsync(c->d_off.p, off.data(), sizeof(int) * B, H2D, st));
   HIP_TRY_B(hipMemcpyAsync(g_chain, slot_chain.data(), sizeof(int) * B, H2D, st));
@@ -537,9 +673,12 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
   hipLaunchKernelGGL(gbmw::k_fill_u32, dim3(1), dim3(256), 0, st, (uint32_t*)c->d_status.p, (size_t)1, 0u);
   // every row of the slots is readable from the start (rows beyond a stage's layers are never used)
   for (auto [ptr, words] : {std::pair<void*, size_t>{gc, rows * d.S}, {gM, rows * d.S},
+                            {s.Ob_g, split ? rows * d.S : 0}, {s.Oms_g, split ? rows * d.S : 0},
                             {c->d_Rt.p, rows * d.S * (size_t)RS}})
-    hipLaunchKernelGGL(gbmw::k_fill_u32, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st,
-                       (uint32_t*)ptr, words, 0u);
+    if (words) {
+      hipLaunchKernelGGL(gbmw::k_fill_u32, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st,
+                         (uint32_t*)ptr, words, 0u);
+    }
   HIP_TRY_B(hipGetLastError());
 
   // ---- rounds -------------------------------------------------------------
@@ -619,7 +758,7 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
       HIP_TRY(hipMemcpyAsync(g_msrc, h_msrc.data(), sizeof(int) * nrows, H2D, st));
       HIP_TRY(hipMemcpyAsync(g_dst, h_dst.data(), sizeof(int) * nrows, H2D, st));
       hipLaunchKernelGGL(gbmw::k_gather, dim3(nrows), dim3(256), 0, st, dc, dM, dR, g_src, g_msrc, g_dst, S,
-                         SP, RS, gc, gM, (float*)c->d_Rt.p);
+                         SP, RS, gc, gM, (float*)c->d_Rt.p, s.Ob, s.Oms, s.Ob_g, s.Oms_g);
     }
     // layer 0 goes to memory where something reads it from there
     for (int g = 0; g < G; ++g) {
@@ -656,6 +795,13 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
       if (g > 0) {
         HIP_TRY(hipEventRecord(c->ev_join[g - 1], sg));
         HIP_TRY(hipStreamWaitEvent(st, c->ev_join[g - 1], 0));
+      }
+    }
+    if (split) {
+      const int window = std::min(ob_max, E + 1);      // budgets above E - b_up, at most
+      hipLaunchKernelGGL(gbmw::k_stage_bup, dim3(nt), dim3(64), 0, st, t, s, g_touched);
+      if (window > 0) {
+        hipLaunchKernelGGL(gbmw::k_stage_check, dim3((window + 63) / 64, nt), dim3(64), 0, st, t, s, g_touched);
       }
     }
     hipLaunchKernelGGL(gbmw::k_stage_result, dim3(nt), dim3(64), 0, st, t, s, g_touched, nt,

@@ -28,19 +28,21 @@ def strategy_name(s) -> str:
     return (lv or "single") + ("+CKPT" if s["ckpt"] else "")
 
 
-def plan(g, gi, layers, devices, E, hw, batches, microbatches, flags=0, max_iter=32, log=None):
+def plan(g, gi, layers, devices, E, hw, batches, microbatches, flags=0, max_iter=32, log=None, overall=True):
     """Algorithm 2 over the given batch sizes (in order) and every PP degree 1, 2, 4, ... that
     fits, as ONE call of the partition search: a pair per (batch size, PP degree), grouped by
     batch size, so that the library also runs the outer loops (best degree per batch size,
     stop at the first batch size that fits nowhere, Tpt).  The strategy set depends on the
     group size devices / P; the smaller sets are padded to the largest with forbidden
-    strategies (c = +inf), which no plan ever picks.
+    strategies (c = +inf), which no plan ever picks.  overall: every stage search checks the
+    overall memory of Eq. 2 (Appendix A, Algorithm 3) with the cost model's O_b and O_ms;
+    otherwise a stage only has to fit its forward memory.
     Returns (best pair or None, results per (batch, P), stats)."""
     Lm = len(layers)
     degrees = [p for p in (1, 2, 4, 8, 16, 32, 64) if p <= devices and p <= Lm]
     sets = {P: g.gbmw_enumerate_strategies(devices // P) for P in degrees}
     S = max(len(v) for v in sets.values())
-    Ps, cs, cns, Rs, Ms, p0s, pts, bsz, grp, key = [], [], [], [], [], [], [], [], [], []
+    Ps, cs, cns, Rs, Ms, Obs, Omss, p0s, pts, bsz, grp, key = [], [], [], [], [], [], [], [], [], [], [], []
     for gi_, B in enumerate(batches):
         for P in degrees:
             n_s = len(sets[P])
@@ -49,7 +51,10 @@ def plan(g, gi, layers, devices, E, hw, batches, microbatches, flags=0, max_iter
             cn = np.full((Lm, S), np.inf, np.float32); cn[:, :n_s] = cm["c_nosync"]
             R = np.zeros((Lm, S, S), np.float32); R[:, :n_s, :n_s] = cm["R"]
             M = np.zeros((P, Lm, S), np.int32); M[:, :, :n_s] = cm["M"]
+            Ob = np.zeros((P, Lm, S), np.int32); Ob[:, :, :n_s] = cm["O_b"]      # one micro-batch in backward,
+            Oms = np.zeros((P, Lm, S), np.int32); Oms[:, :, :n_s] = cm["O_ms"]   # whatever the stage
             Ps.append(P); cs.append(c); cns.append(cn); Rs.append(R); Ms.append(M.reshape(P * Lm, S))
+            Obs.append(Ob.reshape(P * Lm, S)); Omss.append(Oms.reshape(P * Lm, S))
             p0s.append(gi.proportional_partition(Lm, 1.0 / np.arange(P, 0, -1)))
             pts.append(gi.proportional_partition(Lm, np.ones(P)))
             bsz.append(B); grp.append(gi_); key.append((B, P))
@@ -57,7 +62,9 @@ def plan(g, gi, layers, devices, E, hw, batches, microbatches, flags=0, max_iter
     res, ctx = g.gbmw_partition_search(Ps, [Lm] * n, [microbatches] * n, np.concatenate(cs), np.concatenate(cns),
                                        np.concatenate(Rs), np.concatenate(Ms), np.concatenate(p0s),
                                        np.concatenate(pts), S, E, max_iter=max_iter, flags=flags,
-                                       batch_size=bsz, batch_group=grp)
+                                       batch_size=bsz, batch_group=grp,
+                                       O_b=np.concatenate(Obs) if overall else None,
+                                       O_ms=np.concatenate(Omss) if overall else None)
     g.gbmw_destroy(ctx)
     stats = dict(device_ms=res["device_ms"], partitions=int(res["n_iter"].sum()), rounds=res["rounds"],
                  cell_updates=int(res["cell_updates"]), stage_solves=int(res["stage_solves"]), pairs=n, S=S)
@@ -93,6 +100,8 @@ def main():
     ap.add_argument("--batches", default="8,16,32,64,128", help="global batch sizes to try, in order")
     ap.add_argument("--microbatches", type=int, default=8)
     ap.add_argument("--lazy-argmin", action="store_true", help="GBMW_FLAG_LAZY_ARGMIN for the searches")
+    ap.add_argument("--forward-memory-only", action="store_true",
+                    help="stages need to fit their forward memory only (no overall-memory check)")
     args = ap.parse_args()
 
     layers = gi.table1_layers(args.model)
@@ -105,7 +114,8 @@ def main():
     print(f"{args.model}: {Lm} layers on {args.devices} devices, {args.mem_gb:g} GB each "
           f"({E} units of {args.unit_mb:g} MB), micro-batches {args.microbatches}")
 
-    best, _, _ = plan(g, gi, layers, args.devices, E, hw, batches, args.microbatches, flags=flags, log=print)
+    best, _, _ = plan(g, gi, layers, args.devices, E, hw, batches, args.microbatches, flags=flags, log=print,
+                      overall=not args.forward_memory_only)
     if best is None:
         print("no feasible plan")
         return

@@ -84,7 +84,11 @@ def pack_models(models):
     assert all(m.S == S and m.E == E for m in models)
     have_pt = [m.p_t is not None for m in models]
     assert all(have_pt) or not any(have_pt)
+    have_split = [m.Ob is not None for m in models]
+    assert all(have_split) or not any(have_split)
+    cat = lambda name: np.concatenate([getattr(m, name).reshape(m.P * m.Lm, S) for m in models])
     return dict(
+        O_b=cat("Ob") if all(have_split) else None, O_ms=cat("Oms") if all(have_split) else None,
         P=np.array([m.P for m in models], np.int32), Lm=np.array([m.Lm for m in models], np.int32),
         m=np.array([m.m for m in models], np.int32),
         c=np.concatenate([m.c for m in models]), c_nosync=np.concatenate([m.c_ns for m in models]),

@@ -109,11 +109,12 @@ def test_partition_search_rejects_bad_arguments_before_touching_the_device():
 
     def status(max_iter=8, flags=0, **over):
         a = dict(P=[2], Lm=[6], m=[2], c=mod.c, c_nosync=mod.c_ns, R=mod.R, M=mod.M.reshape(12, 1),
-                 p0=mod.p0, p_t=mod.p_t, S=1, E=100)
+                 p0=mod.p0, p_t=mod.p_t, S=1, E=100, O_b=None, O_ms=None)
         a.update(over)
         try:
             g.gbmw_partition_search(a["P"], a["Lm"], a["m"], a["c"], a["c_nosync"], a["R"], a["M"], a["p0"],
-                                    a["p_t"], a["S"], a["E"], max_iter=max_iter, flags=flags)
+                                    a["p_t"], a["S"], a["E"], max_iter=max_iter, flags=flags,
+                                    O_b=a["O_b"], O_ms=a["O_ms"])
         except g.GbmwError as e:
             return e.status, str(e)
         return g.GBMW_OK, ""
@@ -122,7 +123,11 @@ def test_partition_search_rejects_bad_arguments_before_touching_the_device():
                      (dict(p_t=np.array([6, 0])), "empty"), (dict(m=[0]), "m[0]"), (dict(E=-1), "E="),
                      (dict(max_iter=0), "max_iter"), (dict(flags=1), "flag"),
                      (dict(c=-mod.c), "c[0]"), (dict(c_nosync=mod.c_ns * np.nan), "c_nosync[0]"),
-                     (dict(M=-mod.M.reshape(12, 1)), "M[0]")]:
+                     (dict(M=-mod.M.reshape(12, 1)), "M[0]"),
+                     (dict(O_b=np.zeros((12, 1), np.int32)), "go together"),
+                     (dict(O_b=-np.ones((12, 1), np.int32), O_ms=np.zeros((12, 1), np.int32)), "O_b[0]"),
+                     (dict(O_b=np.zeros((12, 1), np.int32), O_ms=mod.M.reshape(12, 1) + 1), "O_ms[0]"),
+                     (dict(O_b=np.zeros((12, 1), np.int32), O_ms=-np.ones((12, 1), np.int32)), "O_ms[0]")]:
         st, msg = status(**kw)
         assert st == g.GBMW_ERR_INVALID_ARG and word in msg, (kw, st, msg)
     badR = mod.R.copy(); badR[1, 0, 0] = -1.0

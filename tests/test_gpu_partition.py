@@ -22,7 +22,8 @@ def g():
 def _search(g, models, max_iter=64, flags=0, ctx=None):
     a = pack_models(models)
     return g.gbmw_partition_search(a["P"], a["Lm"], a["m"], a["c"], a["c_nosync"], a["R"], a["M"], a["p0"],
-                                   a["p_t"], a["S"], a["E"], max_iter=max_iter, flags=flags, ctx=ctx)
+                                   a["p_t"], a["S"], a["E"], max_iter=max_iter, flags=flags, ctx=ctx,
+                                   O_b=a["O_b"], O_ms=a["O_ms"])
 
 
 def test_worked_example(g):
@@ -34,7 +35,9 @@ def test_worked_example(g):
         P, Lm = model["M"].shape[0], model["c"].shape[0]
         res, ctx = g.gbmw_partition_search([P], [Lm], [m], model["c"], model["c_ns"], model["R"],
                                            model["M"].reshape(P * Lm, -1), case["p0"], case["p_t"],
-                                           model["c"].shape[1], case["E"], max_iter=16)
+                                           model["c"].shape[1], case["E"], max_iter=16,
+                                           O_b=model["Ob"].reshape(P * Lm, -1) if "Ob" in model else None,
+                                           O_ms=model["Oms"].reshape(P * Lm, -1) if "Ob" in model else None)
         n = int(res["n_iter"][0])
         got = dict(O_t=int(res["O_t"][0]), strat=res["strat"][0],
                    trace=[dict(p=list(res["p"][0, j]), cost=res["cost"][0, j], C=res["C"][0, j],
@@ -138,6 +141,42 @@ def test_structured_models(g, flags):
               for k, (Lm, P) in enumerate([(24, 2), (24, 4), (32, 4), (32, 8)])]
     res, ctx = _search(g, models, max_iter=12, flags=flags)
     check_partition_search(res, models, 12)
+    g.gbmw_destroy(ctx)
+
+
+@pytest.mark.parametrize("flags", [0, 8, 16], ids=["changed-stages", "resolve-all", "lazy-argmin"])
+def test_alg3_stage_searches(g, flags):
+    """Stage searches with the overall-memory check (Appendix A, Algorithm 3) inside the
+    partition loop: random and structured models with O_b / O_ms tables, among them
+    O_b = 0 (every budget valid), a window wider than a wave, b_up above E (the walk
+    starts at budget 0) and budgets so tight that some searches are infeasible."""
+    models = []
+    special = [(8, 2, 6, 1), (12, 3, 20, 2), (16, 4, 150, 3), (9, 1, 40, 4), (10, 5, 3, 1), (14, 2, 700, 2),
+               (12, 4, 0, 3), (20, 3, 90, 5)]
+    for seed, (Lm, P, ob_max, f) in enumerate(special):
+        base = gi.random_pipeline_model(300 + seed, Lm, 5, P, E=260, m=4, R_rng=(0.0, 0.5), skew=bool(seed % 2))
+        models.append(gi.with_memory_split(base, 400 + seed, ob_max=ob_max))
+        models[-1].M *= f; models[-1].Oms *= f          # one E per call: tighter budgets by larger memories
+    for seed in (4, 12, 16, 18, 33, 53):                 # several accepted moves each
+        st = gi.Stream(9000 + seed)
+        P = int(st.integers(1, 2, 5)[0]); Lm = int(st.integers(1, 3 * P, 5 * P)[0])
+        ob_max = int(st.integers(1, 2, 60)[0]); f = int(st.integers(1, 1, 3)[0])
+        base = gi.random_pipeline_model(300 + seed, Lm, 5, P, E=260, m=4, R_rng=(0.0, 0.5), skew=True)
+        models.append(gi.with_memory_split(base, 400 + seed, ob_max=ob_max))
+        models[-1].M *= f; models[-1].Oms *= f
+    res, ctx = _search(g, models, flags=flags)
+    check_partition_search(res, models, 64)
+    assert (res["n_iter"] > 2).sum() >= 6
+    # the check changes results: the same models searched without it differ somewhere
+    plain = [gi.PipelineModel(m.S, m.E, m.P, m.m, m.c, m.c_ns, m.R, m.M, m.p0, m.p_t, m.name) for m in models]
+    res0, ctx = _search(g, plain, flags=flags, ctx=ctx)
+    assert any(int(res0["n_iter"][k]) != int(res["n_iter"][k]) or
+               not np.array_equal(res0["C"][k, 0], res["C"][k, 0]) for k in range(len(models)))
+    # structured models at the benchmark's S
+    big = [gi.with_memory_split(gi.structured_pipeline_model(70 + k, 24, P, 1200, S=44, act_scale=0.25), 500 + k,
+                                ob_max=ob) for k, (P, ob) in enumerate([(2, 100), (4, 300), (8, 30)])]
+    res, ctx = _search(g, big, max_iter=12, flags=flags, ctx=ctx)
+    check_partition_search(res, big, 12)
     g.gbmw_destroy(ctx)
 
 

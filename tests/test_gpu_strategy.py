@@ -107,11 +107,14 @@ def test_argument_errors(g):
         g.gbmw_cost_model(layers, bad, hw, 8.0, 2)
 
 
+@pytest.mark.parametrize("overall", [False, True], ids=["forward-memory", "overall-memory"])
 @pytest.mark.parametrize("P", [1, 2, 4, 8])
-def test_shapes_to_partition_search(g, P):
+def test_shapes_to_partition_search(g, P, overall):
     """The whole planner path for one (batch size, PP degree) pair of a Table-1 model
     on 8 devices: strategies of the 8/P-device group, cost model, Algorithm 2's
-    partition loop -- library against oracle, each on its own cost model output."""
+    partition loop -- library against oracle, each on its own cost model output.
+    overall: the stage searches check the overall memory (Appendix A) with the cost
+    model's O_b and O_ms, the same for every stage a layer may sit in."""
     import oracle.bmw as bmw
     layers = gi.table1_layers("BERT-Huge-32")
     layers[:, 1] *= np.linspace(0.7, 1.4, len(layers))           # deeper layers cost more time
@@ -124,10 +127,15 @@ def test_shapes_to_partition_search(g, P):
     _compare(got, ref)
     p0 = gi.proportional_partition(Lm, 1.0 / np.arange(P, 0, -1))
     p_t = gi.proportional_partition(Lm, np.ones(P))
+    tile = lambda a: np.ascontiguousarray(np.broadcast_to(a, (P, Lm, S)))
     res, ctx = g.gbmw_partition_search([P], [Lm], [m], got["c"], got["c_nosync"], got["R"],
-                                       got["M"].reshape(P * Lm, S), p0, p_t, S, E, max_iter=16)
-    want = bmw.partition_search(dict(c=ref["c"], c_ns=ref["c_ns"], R=ref["R"], M=ref["M"]), p0, E, m, p_t=p_t,
-                                max_iter=16)
+                                       got["M"].reshape(P * Lm, S), p0, p_t, S, E, max_iter=16,
+                                       O_b=tile(got["O_b"]).reshape(P * Lm, S) if overall else None,
+                                       O_ms=tile(got["O_ms"]).reshape(P * Lm, S) if overall else None)
+    model = dict(c=ref["c"], c_ns=ref["c_ns"], R=ref["R"], M=ref["M"])
+    if overall:
+        model.update(Ob=tile(ref["O_b"]), Oms=tile(ref["O_ms"]))
+    want = bmw.partition_search(model, p0, E, m, p_t=p_t, max_iter=16)
     n = len(want["trace"])
     assert int(res["n_iter"][0]) == n and int(res["O_t"][0]) == want["O_t"]
     for j, t in enumerate(want["trace"]):
