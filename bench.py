@@ -191,6 +191,9 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="instead of the benchmark, run a plain 1 GiB device-to-device copy five times "
                          "(a kernel of known traffic against which HBM byte counters are scaled)")
+    ap.add_argument("--dense-arithmetic", action="store_true",
+                    help="GBMW_FLAG_DENSE_ARITHMETIC for every solve: no shortcut for waves whose budgets "
+                         "share one input column")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other configs")
     ap.add_argument("--no-partition", action="store_true", help="skip the partition-search leg (Algorithm 2)")
@@ -230,6 +233,8 @@ def main():
     p = gi.make_config(args.config)
     d = to_device(torch, p)
     base_flags = g.GBMW_FLAG_ONE_STREAM if args.streams == 1 else 0
+    if args.dense_arithmetic:
+        base_flags |= g.GBMW_FLAG_DENSE_ARITHMETIC
     ctx, sec = solve_steps(g, torch, p, d, args.steps, args.warmup, flags=base_flags)
     nominal, executed = p.nominal_updates(), p.executed_updates()
 
@@ -238,7 +243,7 @@ def main():
     mp_ms = mp_n = tot_ms = 0.0
     reps = max(3, min(args.steps, 10))
     for _ in range(reps):
-        tctx = g.gbmw_dp_solve_batched(p.L, d[0], d[1], d[2], p.S, p.E, flags=g.GBMW_FLAG_TIME_KERNELS, ctx=tctx)
+        tctx = g.gbmw_dp_solve_batched(p.L, d[0], d[1], d[2], p.S, p.E, flags=g.GBMW_FLAG_TIME_KERNELS | (base_flags & g.GBMW_FLAG_DENSE_ARITHMETIC), ctx=tctx)
         a, b, n = g.gbmw_last_solve_ms(tctx)
         tot_ms += a; mp_ms += b; mp_n += n
     g.gbmw_destroy(tctx)
@@ -254,8 +259,14 @@ def main():
         for line in open(tpath):
             if line.startswith("hbm_bytes_per_launch:"):
                 traffic = int(line.split(":")[1])
+    hbm_alg = 9.0 * executed / p.S / launches_per_solve if mp_n else 0.0
     roofline = {
         "bound": "alu", "kernel": "k_minplus (fused min-plus + argmin + shift-add)",
+        "note": "achieved = algorithmic lane-ops (2 per candidate update: one add, one min) of the updates a "
+                "launch covers / its duration.  By default a wave whose 64 budgets share one input column "
+                "computes that column once, so the algorithmic rate can pass what dense arithmetic reaches "
+                "(dense_arithmetic below: the same solve with every lane computing its own cell); the launch "
+                "then runs against the HBM bound (hbm_frac_algorithmic)",
         "achieved": achieved, "peak": PEAK_PLAIN_FP32_TOPS, "unit": "TFLOP/s",
         "frac": achieved / PEAK_PLAIN_FP32_TOPS, "traffic": traffic,
         "ops_per_update": OPS_PER_UPDATE, "updates_per_launch": executed / launches_per_solve if mp_n else 0,
@@ -263,6 +274,7 @@ def main():
         "frac_of_published_fp32_vector_peak": achieved / PEAK_PUBLISHED_FP32_TFLOPS,
         "algorithmic_bytes_per_launch": 9.0 * executed / p.S / launches_per_solve if mp_n else 0,
         "hbm_GBps_algorithmic": (9.0 * executed / p.S / launches_per_solve) / (avg_launch_ms * 1e-3) / 1e9 if mp_n else 0,
+        "hbm_frac_algorithmic": hbm_alg / (avg_launch_ms * 1e-3) / 8e12 if mp_n else 0,
         "kernel_share_of_solve": mp_ms / tot_ms if tot_ms else None,
     }
 
@@ -278,6 +290,26 @@ def main():
         "value_executed": executed / sec,
         "roofline": roofline,
     }
+    # The same solve with every lane computing its own cell (GBMW_FLAG_DENSE_ARITHMETIC): what the
+    # arithmetic itself reaches against the ALU roofline, without the shortcut for runs of equal columns.
+    if not args.dense_arithmetic:
+        dflags = base_flags | g.GBMW_FLAG_DENSE_ARITHMETIC
+        dctx, dsec = solve_steps(g, torch, p, d, args.steps, args.warmup, flags=dflags)
+        g.gbmw_destroy(dctx)
+        dt_ = None
+        dmp = dmn = 0.0
+        for _ in range(reps):
+            dt_ = g.gbmw_dp_solve_batched(p.L, d[0], d[1], d[2], p.S, p.E,
+                                          flags=g.GBMW_FLAG_TIME_KERNELS | g.GBMW_FLAG_DENSE_ARITHMETIC, ctx=dt_)
+            _, b3, n3 = g.gbmw_last_solve_ms(dt_)
+            dmp += b3; dmn += n3
+        g.gbmw_destroy(dt_)
+        d_launch_ms = dmp / dmn if dmn else float("nan")
+        d_ach = OPS_PER_UPDATE * executed / (dmn / reps) / (d_launch_ms * 1e-3) / 1e12 if dmn else 0.0
+        out["dense_arithmetic"] = {
+            "ms_per_step": dsec * 1e3, "value": nominal / dsec, "value_executed": executed / dsec,
+            "avg_launch_ms": d_launch_ms, "achieved": d_ach, "peak": PEAK_PLAIN_FP32_TOPS,
+            "frac": d_ach / PEAK_PLAIN_FP32_TOPS, "bound": "alu"}
     # The same solve without argmin records (GBMW_FLAG_LAZY_ARGMIN): every layer's fp32 table
     # is kept and the walkers recompute the records they need.  Reported beside the headline,
     # never as it: the headline path materialises every record.
@@ -287,7 +319,7 @@ def main():
     lmp = lmn = 0.0
     for _ in range(reps):
         lt = g.gbmw_dp_solve_batched(p.L, d[0], d[1], d[2], p.S, p.E,
-                                     flags=g.GBMW_FLAG_TIME_KERNELS | g.GBMW_FLAG_LAZY_ARGMIN, ctx=lt)
+                                     flags=g.GBMW_FLAG_TIME_KERNELS | g.GBMW_FLAG_LAZY_ARGMIN | (base_flags & g.GBMW_FLAG_DENSE_ARITHMETIC), ctx=lt)
         _, b2, n2 = g.gbmw_last_solve_ms(lt)
         lmp += b2; lmn += n2
     # plans through the recomputing walker, same query set as the backtrack leg below
@@ -348,6 +380,10 @@ def main():
             others[f"cfg{k}"]["lazy_argmin_ms_per_step"] = s3 * 1e3
             others[f"cfg{k}"]["lazy_argmin_value_executed"] = q.executed_updates() / s3
             g.gbmw_destroy(c3)
+            if k == 5 and not args.dense_arithmetic:
+                c4, s4 = solve_steps(g, torch, q, dq, 5, 2, flags=base_flags | g.GBMW_FLAG_DENSE_ARITHMETIC)
+                others[f"cfg{k}"]["dense_arithmetic_ms_per_step"] = s4 * 1e3
+                g.gbmw_destroy(c4)
             del dq
         out["other_configs"] = others
 

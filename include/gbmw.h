@@ -69,7 +69,14 @@ enum {
                                   the one record they need per layer, with the same
                                   arithmetic and tie rule, so every result is identical.
                                   The fill then costs one add and half a three-input min
-                                  per candidate and nothing else                         */
+                                  per candidate and nothing else                         */,
+  GBMW_FLAG_DENSE_ARITHMETIC = 32u /* every lane computes its own cell.  Default: a wave
+                                  whose 64 consecutive budgets all read the same column of
+                                  the previous layer's table (the tables are step functions
+                                  of the budget, so most waves do) computes that column's
+                                  cells once, one output strategy per lane, and writes the
+                                  result to all 64 budgets.  Identical results either way;
+                                  the flag exists to time the dense arithmetic            */
 };
 
 #define GBMW_MAX_S 256

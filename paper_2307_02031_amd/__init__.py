@@ -28,6 +28,7 @@ GBMW_FLAG_TIME_KERNELS = 2
 GBMW_FLAG_ONE_STREAM = 4
 GBMW_FLAG_RESOLVE_ALL = 8
 GBMW_FLAG_LAZY_ARGMIN = 16
+GBMW_FLAG_DENSE_ARITHMETIC = 32
 GBMW_MAX_S = 256
 
 EXPORTS = [

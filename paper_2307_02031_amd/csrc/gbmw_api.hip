@@ -146,7 +146,7 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
   if (p->ptr_space != GBMW_PTR_HOST && p->ptr_space != GBMW_PTR_DEVICE)
     return fail(GBMW_ERR_INVALID_ARG, "ptr_space=%d", p->ptr_space);
   if (flags & ~(uint32_t)(GBMW_FLAG_KEEP_ALL_C | GBMW_FLAG_TIME_KERNELS | GBMW_FLAG_ONE_STREAM |
-                          GBMW_FLAG_LAZY_ARGMIN))
+                          GBMW_FLAG_LAZY_ARGMIN | GBMW_FLAG_DENSE_ARITHMETIC))
     return fail(GBMW_ERR_INVALID_ARG, "unknown flag bits 0x%x", flags);
 
   const int B = p->B, S = p->S, E = p->E;
@@ -271,6 +271,7 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
   gbmw::Tables& t = c->t;
   t.B = B; t.S = S; t.SP = SP; t.RS = RS; t.E = E; t.EP = EP; t.keep_all = keep ? 1 : 0;
   t.final_from = std::min(std::max(final_from, 0), E);
+  t.runs = (flags & GBMW_FLAG_DENSE_ARITHMETIC) ? 0 : 1;
   t.L = (const int*)c->d_L.p; t.off = (const int*)c->d_off.p; t.perm = (const int*)c->d_perm.p;
   t.c = dc; t.M = dM; t.Rt = (const float*)c->d_Rt.p;
   t.Cbuf = (float*)c->d_C.p; t.A = lazy ? nullptr : (uint8_t*)c->d_A.p;

@@ -23,6 +23,9 @@ struct Tables {
   int B, S, SP, RS, E, EP;
   int keep_all;        // 1: Call[row][S][EP] for every layer row; 0: rolling pair
   int final_from;      // the final reduce fills best / best_s for e >= final_from only
+  int runs;            // 1: a wave whose 64 budgets all have the same input column (the tables are
+                       // step functions of the budget) computes that column once, one output
+                       // strategy per lane; 0: every lane computes its own cell
   const int* L;        // [B]   device
   const int* off;      // [B]   device, first row of each instance
   const int* perm;     // [B]   device, instances ordered by L descending

@@ -133,9 +133,66 @@ __device__ __forceinline__ float fmin3(float a, float b, float c) {
   return __builtin_fminf(__builtin_fminf(a, b), c);
 }
 
-template <int SP, int K, int NW, int CH, int MINW, bool FIRST, bool ARG, bool SPLIT>
+// A wave whose 64 budgets all carry the same column C_{l-1}[e'][.] (a run of the step function
+// that the table is along the budget axis) has 64 identical cells per output strategy.  It is
+// computed once, with the lanes over the output strategies instead: lane j forms
+// min_s' (column[s'] + R[s'][s_begin + j]) with the lowest minimising s' (strict compare in index
+// order), adds c, and the results go out to the 64 budgets strategy by strategy.  Same operands
+// and operations per cell as the dense path, hence the same bits.
+template <int SP, bool ARG>
+__device__ __forceinline__ void uniform_tile(const float (&col)[SP], const float4* rt_lds, int s_begin,
+                                             int s_end, int lane, int e0, int wbase, float* __restrict__ Cn,
+                                             uint8_t* __restrict__ An, int E, int EP) {
+  constexpr int RS = (SP + 2 + 3) / 4 * 4;
+  constexpr int RQ = RS / 4;
+  const int srow = (s_begin + lane < s_end) ? s_begin + lane : s_begin;   // idle lanes redo a valid row
+  float best = INFINITY, cs = 0.0f;
+  int a = 0, m_own = 0;
+  int roff = srow * RQ;
+#pragma unroll
+  for (int q = 0; q < RQ; ++q) {
+    // one quad of the row in flight at a time: the read of quad q waits for the fold of quad
+    // q - 1, so that the row never occupies more than four registers (this path is bound by
+    // its stores, not by this latency)
+    asm volatile("" : "+v"(roff), "+v"(best));
+    const float4 v = rt_lds[roff + q];
+    const float rq[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+      const int i = 4 * q + i4;
+      if (i < SP) {
+        const float f = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(col[i])));
+        const float x = f + rq[i4];
+        if (x < best) { best = x; a = i; }
+      }
+    }
+    if (4 * q == SP) { cs = rq[0]; m_own = __float_as_int(rq[1]); }
+  }
+  const int outv = __float_as_int(best + cs);
+  for (int s = s_begin; s < s_end; ++s) {
+    const int j = s - s_begin;
+    const unsigned v = (unsigned)__builtin_amdgcn_readlane(outv, j);
+    const int m_raw = __builtin_amdgcn_readlane(m_own, j);
+    const int m = (m_raw < 0 || m_raw > E + 1) ? E + 1 : m_raw;
+    float* Cs = Cn + (size_t)s * EP;
+    const __amdgpu_buffer_rsrc_t bc = __builtin_amdgcn_make_buffer_rsrc(Cs, 0, (E + 1) * 4, kBufWord3);
+    const __amdgpu_buffer_rsrc_t binf = __builtin_amdgcn_make_buffer_rsrc(Cs, 0, m * 4, kBufWord3);
+    if (ARG) {
+      const int ar = __builtin_amdgcn_readlane(a, j);
+      const __amdgpu_buffer_rsrc_t ba = __builtin_amdgcn_make_buffer_rsrc(An + (size_t)s * EP, 0, EP, kBufWord3);
+      __builtin_amdgcn_raw_buffer_store_b8((unsigned char)ar, ba, e0, 0, 0);
+    }
+    __builtin_amdgcn_raw_buffer_store_b32(v, bc, (e0 + m) * 4, 0, 0);
+    if (wbase < m) __builtin_amdgcn_raw_buffer_store_b32(0x7f800000u, binf, e0 * 4, 0, 0);
+  }
+}
+
+// RUNS: waves whose budgets share one input column take uniform_tile (never in split mode:
+// those launches are bound by a wave's own latency, which the test would lengthen).
+template <int SP, int K, int NW, int CH, int MINW, bool FIRST, bool ARG, bool SPLIT, bool RUNS>
 __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int tiles, int first) {
   constexpr bool split = SPLIT;
+  static_assert(!(SPLIT && RUNS), "no run shortcut in split mode");
   constexpr int NC = (SP + CH - 1) / CH;                 // chunks (last may be short)
   constexpr int NP = NC / 2 + 1;                         // prefix minima / blocks
   constexpr int RS = (SP + 2 + 3) / 4 * 4;               // row: SP x R, c, M, padding
@@ -194,6 +251,22 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
 #pragma unroll
       for (int j = 0; j < K; ++j)
         cp[j][sp] = (sp < SP - 3 || sp < S) ? Cp[(size_t)sp * EP + e0 + 64 * j] : INFINITY;
+    }
+  }
+
+  if (RUNS) {
+    // are the columns of all budgets of this wave (those inside the table) the same, bit for bit?
+    static_assert(K == 1, "one budget per lane");
+    const bool inside = e0 <= E;
+    unsigned long long differ = 0;
+#pragma unroll
+    for (int sp = 0; sp < SP; ++sp) {
+      const int own = __float_as_int(cp[0][sp]);
+      differ |= __builtin_amdgcn_ballot_w64(inside && own != __builtin_amdgcn_readfirstlane(own));
+    }
+    if (differ == 0) {
+      uniform_tile<SP, ARG>(cp[0], rt_lds, s_begin, s_end, lane, e0, wbase, Cn, An, E, EP);
+      return;
     }
   }
 
@@ -383,6 +456,9 @@ struct Blocking {                       // budgets per lane for a given strategy
   static constexpr int MINW_FIRST = (SP > 40 && SP <= 44) ? 7 : MINW;
   // without the argmin pass: the SP table values plus about 16 working registers
   static constexpr int MINW_VALUES = (SP <= 44) ? 8 : (SP <= 52) ? 7 : (SP <= 60) ? 6 : 5;
+  // with the run shortcut compiled in, the records kernel at 44 strategies needs one wave fewer
+  static constexpr int MINW_RUNS = (SP > 40 && SP <= 44) ? 7 : MINW;
+  static constexpr int MINW_VALUES_FIRST_RUNS = (SP > 40 && SP <= 44) ? 7 : MINW_VALUES;
 };
 
 template <int SP>
@@ -399,17 +475,33 @@ static void launch_minplus_sp(const Tables& t, int l, int first, int n_active, h
   // Split launches are the small ones, where a wave's own latency counts and registers are
   // plentiful: a low occupancy target lets the compiler keep the whole R row in flight.
   constexpr int MS = Blocking<SP>::MINW_SPLIT;
-#define GBMW_LAUNCH(MW, FIRST_, ARG_, SPLIT_)                                                        \
-  hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, MW, FIRST_, ARG_, SPLIT_>), grid, block, lds, st, t, l, \
+#define GBMW_LAUNCH(MW, FIRST_, ARG_, SPLIT_, RUNS_)                                                        \
+  hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, MW, FIRST_, ARG_, SPLIT_, RUNS_>), grid, block, lds, st, t, l, \
                      tiles, first)
+  const bool runs = t.runs != 0;
   if (t.A == nullptr) {
-    constexpr int MW = Blocking<SP>::MINW_VALUES;
-    if (l == 1) { if (split) GBMW_LAUNCH(MS, true, false, true); else GBMW_LAUNCH(MW, true, false, false); }
-    else        { if (split) GBMW_LAUNCH(MS, false, false, true); else GBMW_LAUNCH(MW, false, false, false); }
+    constexpr int MW = Blocking<SP>::MINW_VALUES, MW1R = Blocking<SP>::MINW_VALUES_FIRST_RUNS;
+    if (l == 1) {
+      if (split) GBMW_LAUNCH(MS, true, false, true, false);
+      else if (runs) GBMW_LAUNCH(MW1R, true, false, false, true);
+      else GBMW_LAUNCH(MW, true, false, false, false);
+    } else {
+      if (split) GBMW_LAUNCH(MS, false, false, true, false);
+      else if (runs) GBMW_LAUNCH(MW, false, false, false, true);
+      else GBMW_LAUNCH(MW, false, false, false, false);
+    }
   } else {
-    constexpr int M1 = Blocking<SP>::MINW_FIRST;
-    if (l == 1) { if (split) GBMW_LAUNCH(MS, true, true, true); else GBMW_LAUNCH(M1, true, true, false); }
-    else        { if (split) GBMW_LAUNCH(MS, false, true, true); else GBMW_LAUNCH(MINW, false, true, false); }
+    constexpr int M1 = Blocking<SP>::MINW_FIRST, MR = Blocking<SP>::MINW_RUNS;
+    constexpr int M1R = M1 < MR ? M1 : MR;
+    if (l == 1) {
+      if (split) GBMW_LAUNCH(MS, true, true, true, false);
+      else if (runs) GBMW_LAUNCH(M1R, true, true, false, true);
+      else GBMW_LAUNCH(M1, true, true, false, false);
+    } else {
+      if (split) GBMW_LAUNCH(MS, false, true, true, false);
+      else if (runs) GBMW_LAUNCH(MR, false, true, false, true);
+      else GBMW_LAUNCH(MINW, false, true, false, false);
+    }
   }
 #undef GBMW_LAUNCH
 }

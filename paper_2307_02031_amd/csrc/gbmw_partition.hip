@@ -457,7 +457,7 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
   if (q->S < 1 || q->S > GBMW_MAX_S) return fail(GBMW_ERR_INVALID_ARG, "S=%d not in 1..256", q->S);
   if (q->E < 0 || q->E > (1 << 28)) return fail(GBMW_ERR_INVALID_ARG, "E=%d out of range", q->E);
   if (q->max_iter < 1 || q->max_iter > 4096) return fail(GBMW_ERR_INVALID_ARG, "max_iter=%d not in 1..4096", q->max_iter);
-  if (flags & ~(uint32_t)(GBMW_FLAG_RESOLVE_ALL | GBMW_FLAG_LAZY_ARGMIN))
+  if (flags & ~(uint32_t)(GBMW_FLAG_RESOLVE_ALL | GBMW_FLAG_LAZY_ARGMIN | GBMW_FLAG_DENSE_ARITHMETIC))
     return fail(GBMW_ERR_INVALID_ARG, "unknown flag bits 0x%x", flags);
 
   const int n = q->n_chain, S = q->S, E = q->E;
@@ -636,6 +636,7 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
 
   gbmw::Tables& t = c->t;
   t.B = B; t.S = S; t.SP = SP; t.RS = RS; t.E = E; t.EP = EP; t.keep_all = lazy ? 1 : 0;
+  t.runs = (flags & GBMW_FLAG_DENSE_ARITHMETIC) ? 0 : 1;
   t.final_from = std::max(0, E - ob_max);              // Algorithm 3 reads best(e) from E - b_up on
   t.L = (const int*)c->d_L.p; t.off = (const int*)c->d_off.p; t.perm = (const int*)c->d_perm.p;
   t.c = gc; t.M = gM; t.Rt = (const float*)c->d_Rt.p;

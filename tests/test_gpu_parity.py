@@ -213,6 +213,63 @@ def test_non_default_stream(g):
     g.gbmw_destroy(ctx)
 
 
+MODES = {"records": 0, "lazy-argmin": 16, "records-dense": 32, "lazy-argmin-dense": 48}
+
+
+@pytest.mark.parametrize("mode", list(MODES), ids=list(MODES))
+@pytest.mark.parametrize("S", [5, 44, 61])
+def test_runs_of_equal_columns_edge_cases(g, S, mode):
+    """By default a wave whose 64 budgets read the same column of the previous table computes
+    it once.  Layer-0 memories are placed so that the columns change exactly at, just before
+    and just after the wave boundaries (budgets 63, 64, 65, 127, 128, ...), at budget 0, at E
+    and beyond E, in unsplit launches (>= 1024 workgroups) whose last wave is cut by E; later
+    layers shift by multiples of 64 and by odd amounts.  Full tables against the oracle, with
+    and without the shortcut, with and without records."""
+    E = 26453                                       # E + 1 = 103 * 256 + 86: a ragged last wave
+    flags = MODES[mode]
+    edges = [0, 1, 63, 64, 65, 127, 128, 129, 191, 192, 4095, 4096, 4097, E - 64, E - 63, E - 1, E, E + 1]
+    st = gi.Stream(7700 + S)
+    parts = []
+    for i in range(12):
+        L = 3 if i < 10 else 2
+        c = st.integers(L * S, 1, 6).astype(np.float32).reshape(L, S)
+        R = st.integers(L * S * S, 0, 3).astype(np.float32).reshape(L, S, S)
+        M = np.zeros((L, S), np.int64)
+        M[0] = [edges[(i + 3 * s) % len(edges)] for s in range(S)]
+        if i % 2:                                   # shifts that keep the alignment / that break it
+            M[1:] = 64 * st.integers((L - 1) * S, 0, 40).reshape(L - 1, S)
+        else:
+            M[1:] = st.integers((L - 1) * S, 0, 3000).reshape(L - 1, S)
+        if i == 3:
+            c[0, ::2] = np.inf                      # forbidden strategies: columns of +inf
+        if i == 4:
+            M[0] = E + 1                            # nothing fits: every column is +inf everywhere
+        parts.append(gi.Problem(1, S, E, np.array([L]), c, M, R))
+    p = gi.stack(parts, f"runs-S{S}")
+    keep = 0 if flags & 16 else g.GBMW_FLAG_KEEP_ALL_C
+    # one stream: every layer's launch then covers all instances (1248 and 1040 workgroups)
+    ctx = solve_gpu(p, flags=flags | keep | g.GBMW_FLAG_ONE_STREAM, device_inputs=True)
+    best, best_s = g.gbmw_get_best(ctx)
+    for b in range(p.B):
+        _log(f"runs S={S} {mode} instance {b}")
+        check_instance(g, ctx, p, b, full_C=True, q_es=[0, 63, 64, 4096, E - 1, E], best=best, best_s=best_s)
+    g.gbmw_destroy(ctx)
+
+
+@pytest.mark.parametrize("lazy", [False, True], ids=["records", "lazy-argmin"])
+def test_config4_dense_arithmetic(g, lazy):
+    """The benchmark's batch with GBMW_FLAG_DENSE_ARITHMETIC (every lane computes its own
+    cell): every ninth instance against the oracle."""
+    p = gi.make_config(4)
+    ctx = solve_gpu(p, flags=g.GBMW_FLAG_DENSE_ARITHMETIC | (g.GBMW_FLAG_LAZY_ARGMIN if lazy else 0),
+                    device_inputs=True)
+    best, best_s = g.gbmw_get_best(ctx)
+    for b in range(0, p.B, 9):
+        _log(f"cfg4 dense instance {b} L={p.L[b]}")
+        check_instance(g, ctx, p, b, full_C=False, best=best, best_s=best_s)
+    g.gbmw_destroy(ctx)
+
+
 def test_config4_batched_full_size(g):
     """All 64 instances in the launch configuration the benchmark times; full A,
     last two layers of C, best, plans against the oracle for every instance."""

@@ -204,7 +204,8 @@ def test_outer_loops_throughput(g):
 
 def test_benchmark_workload_all_modes_agree(g):
     """The workload bench.py times (16 pairs, 48 layers, S = 44, E = 32768): kept tables,
-    every stage re-solved, and no argmin records give the same traces bit for bit; the
+    every stage re-solved, no argmin records, and dense arithmetic (no shortcut for waves whose
+    budgets share one input column) give the same traces bit for bit; the
     first pair is also checked against the oracle."""
     import importlib.util
     import os
@@ -213,7 +214,8 @@ def test_benchmark_workload_all_modes_agree(g):
     spec.loader.exec_module(bench)
     models = bench.partition_workload(gi)
     ref, ctx = _search(g, models, max_iter=32)
-    for flags in (g.GBMW_FLAG_RESOLVE_ALL, g.GBMW_FLAG_LAZY_ARGMIN):
+    for flags in (g.GBMW_FLAG_RESOLVE_ALL, g.GBMW_FLAG_LAZY_ARGMIN, g.GBMW_FLAG_DENSE_ARITHMETIC,
+                  g.GBMW_FLAG_DENSE_ARITHMETIC | g.GBMW_FLAG_LAZY_ARGMIN):
         res, ctx = _search(g, models, max_iter=32, flags=flags, ctx=ctx)
         for key in ("n_iter", "O_t", "p", "cost", "C", "Cns", "O", "alpha_t", "alpha_m", "strat"):
             assert np.array_equal(ref[key].view(np.uint8), res[key].view(np.uint8)), (flags, key)
