@@ -199,8 +199,18 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
   constexpr int RQ = RS / 4;
   extern __shared__ float4 rt_lds[];                     // [S][RQ]
 
-  const int inst = t.perm[first + blockIdx.x / tiles];
-  const int tile = blockIdx.x % tiles;
+  // Workgroups go to the 8 XCDs round-robin by their index; each XCD (its own L2) gets a
+  // contiguous range of (instance, row tile) instead, so that neighbouring tiles, whose
+  // shifted stores share a cache line at their common border, meet in one L2.  Only where the
+  // launch is bound by its memory traffic (the run shortcut); with dense arithmetic the
+  // round-robin order balances the work better.
+  int wg = blockIdx.x;
+  if (RUNS) {
+    const int nb = gridDim.x, q8 = nb >> 3, r8 = nb & 7, x = wg & 7;
+    wg = x * q8 + (x < r8 ? x : r8) + (wg >> 3);
+  }
+  const int inst = t.perm[first + wg / tiles];
+  const int tile = wg % tiles;
   const int S = t.S, E = t.E, EP = t.EP;
   const int row = t.off[inst] + l;
   {
