@@ -128,6 +128,12 @@ void launch_init_layer0(const Tables& t, int first, int count, hipStream_t st) {
 // ---------------------------------------------------------------------------
 // Word 3 of a gfx9-family raw buffer descriptor: 32-bit data format, no swizzle.
 constexpr int kBufWord3 = 0x00020000;
+// Cache policy of a buffer store: non-temporal.  The argmin records of an unsplit launch are
+// written once and not read again before the solve ends, and the previous table is read once
+// (streaming loads): keeping both out of the way leaves the L2 to the fp32 stores, whose
+// shifted rows meet their neighbours' in shared cache lines and are merged there (the same
+// hint on those stores costs 20 %: the halves of a line are then written back separately).
+constexpr int kStreaming = 2;
 
 __device__ __forceinline__ float fmin3(float a, float b, float c) {
   return __builtin_fminf(__builtin_fminf(a, b), c);
@@ -180,7 +186,7 @@ __device__ __forceinline__ void uniform_tile(const float (&col)[SP], const float
     if (ARG) {
       const int ar = __builtin_amdgcn_readlane(a, j);
       const __amdgpu_buffer_rsrc_t ba = __builtin_amdgcn_make_buffer_rsrc(An + (size_t)s * EP, 0, EP, kBufWord3);
-      __builtin_amdgcn_raw_buffer_store_b8((unsigned char)ar, ba, e0, 0, 0);
+      __builtin_amdgcn_raw_buffer_store_b8((unsigned char)ar, ba, e0, 0, kStreaming);
     }
     __builtin_amdgcn_raw_buffer_store_b32(v, bc, (e0 + m) * 4, 0, 0);
     if (wbase < m) __builtin_amdgcn_raw_buffer_store_b32(0x7f800000u, binf, e0 * 4, 0, 0);
@@ -260,7 +266,12 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
     for (int sp = 0; sp < SP; ++sp) {
 #pragma unroll
       for (int j = 0; j < K; ++j)
-        cp[j][sp] = (sp < SP - 3 || sp < S) ? Cp[(size_t)sp * EP + e0 + 64 * j] : INFINITY;
+        {
+        // a large launch reads every table value exactly once: streaming loads leave the
+        // caches to the stores; a split launch is small enough to find its table in cache
+        const float* src = &Cp[(size_t)sp * EP + e0 + 64 * j];
+        cp[j][sp] = !(sp < SP - 3 || sp < S) ? INFINITY : SPLIT ? *src : __builtin_nontemporal_load(src);
+      }
     }
   }
 
@@ -408,7 +419,7 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
       }
 
       const int e = e0 + 64 * j;                         // pre-shift budget e'
-      __builtin_amdgcn_raw_buffer_store_b8((unsigned char)arg, ba, e, 0, 0);
+      __builtin_amdgcn_raw_buffer_store_b8((unsigned char)arg, ba, e, 0, SPLIT ? 0 : kStreaming);
       __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(T + cs), bc, (e + m) * 4, 0, 0);
       if (wbase + 64 * j < m)                            // wave-uniform: some lane is below M
         __builtin_amdgcn_raw_buffer_store_b32(0x7f800000u, binf, e * 4, 0, 0);
