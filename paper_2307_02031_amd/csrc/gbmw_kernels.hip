@@ -91,17 +91,23 @@ void launch_prepare(const Tables& t, const float* R, int sumL, bool validate, hi
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_init_layer0(Tables t, int first) {
   const int inst = t.perm[first + blockIdx.z], s = blockIdx.y;
-  const int e = blockIdx.x * 256 + threadIdx.x;           // EP is a multiple of 256
+  const int e = (blockIdx.x * 256 + threadIdx.x) * 4;     // EP is a multiple of 256: whole float4s
+  if (e >= t.EP) return;
   const int row = t.off[inst];
   const int m = t.M[(size_t)row * t.S + s];
   const float cs = t.c[(size_t)row * t.S + s];
   float* C0 = c_table(t, inst, row, 0);
-  C0[(size_t)s * t.EP + e] = (m >= 0 && e >= m && e <= t.E) ? cs : INFINITY;   // padding rows: +inf
+  float4 v;                                                // padding rows: +inf
+  v.x = (m >= 0 && e >= m && e <= t.E) ? cs : INFINITY;
+  v.y = (m >= 0 && e + 1 >= m && e + 1 <= t.E) ? cs : INFINITY;
+  v.z = (m >= 0 && e + 2 >= m && e + 2 <= t.E) ? cs : INFINITY;
+  v.w = (m >= 0 && e + 3 >= m && e + 3 <= t.E) ? cs : INFINITY;
+  *reinterpret_cast<float4*>(C0 + (size_t)s * t.EP + e) = v;
 }
 
 void launch_init_layer0(const Tables& t, int first, int count, hipStream_t st) {
   if (count <= 0) return;
-  hipLaunchKernelGGL(k_init_layer0, dim3(t.EP / 256, t.S, count), dim3(256), 0, st, t, first);
+  hipLaunchKernelGGL(k_init_layer0, dim3((t.EP + 1023) / 1024, t.S, count), dim3(256), 0, st, t, first);
 }
 
 // ---------------------------------------------------------------------------
@@ -560,7 +566,17 @@ __global__ __launch_bounds__(256) void k_final(Tables t, int first) {
   const float* __restrict__ C = c_table(t, inst, t.off[inst] + l, l);
   float b = INFINITY;
   int a = 0;
-  for (int s = 0; s < t.S; ++s) {
+  // eight loads in flight, then the compares in strategy order
+  int s = 0;
+  for (; s + 8 <= t.S; s += 8) {
+    float x[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = __builtin_nontemporal_load(&C[(size_t)(s + i) * t.EP + e]);
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (x[i] < b) { b = x[i]; a = s + i; }
+  }
+  for (; s < t.S; ++s) {
     const float x = C[(size_t)s * t.EP + e];
     if (x < b) { b = x; a = s; }
   }
