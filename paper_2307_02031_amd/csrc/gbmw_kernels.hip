@@ -493,8 +493,8 @@ static void launch_minplus_sp(const Tables& t, int l, int first, int n_active, h
   constexpr int K = Blocking<SP>::K, NW = Blocking<SP>::NW, CH = Blocking<SP>::CH,
                 MINW = Blocking<SP>::MINW;
   int tiles = (t.E + 1 + 64 * K * NW - 1) / (64 * K * NW);
-  // fewer than four workgroups per compute unit: split the strategies over the waves
-  const int split = ((long long)tiles * n_active < 1024) ? 1 : 0;
+  // fewer than two and a half workgroups per compute unit: split the strategies over the waves
+  const int split = ((long long)tiles * n_active < 640) ? 1 : 0;
   if (split) tiles = (t.E + 1 + 64 * K - 1) / (64 * K);
   constexpr int RS = (SP + 2 + 3) / 4 * 4;
   const dim3 grid((unsigned)tiles * n_active), block(64 * NW);

@@ -91,7 +91,7 @@ def test_ragged_batches_all_shapes(g, S, E, Ls, device_inputs, lazy):
 @pytest.mark.parametrize("lazy", [False, True], ids=["records", "lazy-argmin"])
 @pytest.mark.parametrize("S", [3, 7, 11, 15, 19, 23, 26, 30, 34, 39, 43, 47, 51, 54, 59, 62])
 def test_wide_launches_every_instantiation(g, S, lazy):
-    """Launches of 1024 workgroups and more take the kernel's other path (each wave owns
+    """Launches of 640 workgroups and more take the kernel's other path (each wave owns
     its own 64 budgets instead of sharing a tile with the other waves of its workgroup):
     ten instances of E = 32805 for every register-blocked instantiation, with
     integer-valued costs so that ties are everywhere."""
@@ -222,7 +222,7 @@ def test_runs_of_equal_columns_edge_cases(g, S, mode):
     """By default a wave whose 64 budgets read the same column of the previous table computes
     it once.  Layer-0 memories are placed so that the columns change exactly at, just before
     and just after the wave boundaries (budgets 63, 64, 65, 127, 128, ...), at budget 0, at E
-    and beyond E, in unsplit launches (>= 1024 workgroups) whose last wave is cut by E; later
+    and beyond E, in unsplit launches (>= 640 workgroups) whose last wave is cut by E; later
     layers shift by multiples of 64 and by odd amounts.  Full tables against the oracle, with
     and without the shortcut, with and without records."""
     E = 26453                                       # E + 1 = 103 * 256 + 86: a ragged last wave
