@@ -49,7 +49,7 @@ void free_ctx(gbmw_ctx* c) {
   if (!c) return;
   (void)hipSetDevice(c->device);
   (void)hipStreamSynchronize(c->stream);
-  for (DevBuf* b : {&c->d_L, &c->d_off, &c->d_perm, &c->d_c, &c->d_M, &c->d_R, &c->d_Rt, &c->d_C,
+  for (DevBuf* b : {&c->d_L, &c->d_off, &c->d_perm, &c->d_c, &c->d_M, &c->d_R, &c->d_Rt, &c->d_C, &c->d_sum,
                     &c->d_A, &c->d_best, &c->d_best_s, &c->d_status, &c->d_q, &c->d_stage,
                     &c->d_search, &c->d_gather})
     b->release();
@@ -237,6 +237,8 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
   const int RS = (SP + 2 + 3) / 4 * 4;
   TRY(c->d_Rt.reserve(sizeof(float) * (size_t)sumL * S * RS));
   TRY(c->d_C.reserve(sizeof(float) * slab * (keep ? (size_t)sumL : (size_t)2 * B)));
+  const bool runs = (flags & GBMW_FLAG_DENSE_ARITHMETIC) == 0;
+  if (runs) TRY(c->d_sum.reserve(sizeof(float) * ((size_t)S * (EP / 64)) * (keep ? (size_t)sumL : (size_t)2 * B)));
   if (!lazy) TRY(c->d_A.reserve(slab * (size_t)sumL));
   TRY(c->d_best.reserve(sizeof(float) * (size_t)B * EP));
   TRY(c->d_best_s.reserve((size_t)B * EP));
@@ -271,7 +273,8 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
   gbmw::Tables& t = c->t;
   t.B = B; t.S = S; t.SP = SP; t.RS = RS; t.E = E; t.EP = EP; t.keep_all = keep ? 1 : 0;
   t.final_from = std::min(std::max(final_from, 0), E);
-  t.runs = (flags & GBMW_FLAG_DENSE_ARITHMETIC) ? 0 : 1;
+  t.runs = runs ? 1 : 0;
+  t.Tsum = runs ? (float*)c->d_sum.p : nullptr;
   t.L = (const int*)c->d_L.p; t.off = (const int*)c->d_off.p; t.perm = (const int*)c->d_perm.p;
   t.c = dc; t.M = dM; t.Rt = (const float*)c->d_Rt.p;
   t.Cbuf = (float*)c->d_C.p; t.A = lazy ? nullptr : (uint8_t*)c->d_A.p;

@@ -66,7 +66,7 @@ struct gbmw_ctx {
   int B = 0, S = 0, SP = 0, E = 0, EP = 0, sumL = 0, Lmax = 0;
   std::vector<int> L, off, perm;
   gbmw::Tables t{};
-  gbmw_detail::DevBuf d_L, d_off, d_perm, d_c, d_M, d_R, d_Rt, d_C, d_A, d_best, d_best_s, d_status,
+  gbmw_detail::DevBuf d_L, d_off, d_perm, d_c, d_M, d_R, d_Rt, d_C, d_sum, d_A, d_best, d_best_s, d_status,
       d_q, d_stage, d_search, d_gather;
   hipEvent_t ev0 = nullptr, ev1 = nullptr, ev_fork = nullptr;
   std::vector<hipStream_t> aux;              // extra streams for instance groups

@@ -35,6 +35,10 @@ struct Tables {
   float* Cbuf;         // keep_all ? [sumL][S][EP] : [2][B][S][EP]
   uint8_t* A;          // [sumL][S][EP]; null: records are not kept (needs keep_all), the
                        // walkers recompute the one they need from the kept tables
+  float* Tsum;         // per table (indexed like Cbuf) [S][EP/64]: for every strategy and every group
+                       // of 64 budgets e' of the layer's min-plus product, the value T + c if it is the
+                       // same for all 64 (those inside the table), NaN otherwise; written by the layer's
+                       // launch and read by the next one when runs != 0; null when runs == 0
   float* best;         // [B][EP]
   uint8_t* best_s;     // [B][EP]
   int* status;         // device word; bit 0: bad c, bit 1: bad M, bit 2: bad R

@@ -21,6 +21,16 @@ __device__ __forceinline__ const GBMW_AS4 T* as_const(const T* p) {
 #pragma clang diagnostic pop
 }
 
+// Summary of a table, laid out and indexed like the table itself: [S][EP / 64].
+__device__ __forceinline__ float* sum_table(const Tables& t, int inst, int row, int l) {
+  const size_t slab = (size_t)t.S * (t.EP >> 6);
+  return t.keep_all ? t.Tsum + (size_t)row * slab
+                    : t.Tsum + ((size_t)(l & 1) * t.B + inst) * slab;
+}
+
+constexpr int kNaNBits = 0x7fc00000;
+__device__ __forceinline__ bool is_nan_bits(int b) { return (b & 0x7fffffff) > 0x7f800000; }
+
 __device__ __forceinline__ float* c_table(const Tables& t, int inst, int row, int l) {
   const size_t slab = (size_t)t.S * t.EP;
   return t.keep_all ? t.Cbuf + (size_t)row * slab
@@ -147,14 +157,16 @@ __device__ __forceinline__ float fmin3(float a, float b, float c) {
 
 // A wave whose 64 budgets all carry the same column C_{l-1}[e'][.] (a run of the step function
 // that the table is along the budget axis) has 64 identical cells per output strategy.  It is
-// computed once, with the lanes over the output strategies instead: lane j forms
+// computed once, with the lanes over the output strategies instead (colv: lane s' holds
+// column[s'], +inf beyond the last strategy): lane j forms
 // min_s' (column[s'] + R[s'][s_begin + j]) with the lowest minimising s' (strict compare in index
 // order), adds c, and the results go out to the 64 budgets strategy by strategy.  Same operands
 // and operations per cell as the dense path, hence the same bits.
 template <int SP, bool ARG>
-__device__ __forceinline__ void uniform_tile(const float (&col)[SP], const float4* rt_lds, int s_begin,
+__device__ __forceinline__ void uniform_tile(const float colv, const float4* rt_lds, int s_begin,
                                              int s_end, int lane, int e0, int wbase, float* __restrict__ Cn,
-                                             uint8_t* __restrict__ An, int E, int EP) {
+                                             uint8_t* __restrict__ An, float* __restrict__ sum_cur, int E,
+                                             int EP) {
   constexpr int RS = (SP + 2 + 3) / 4 * 4;
   constexpr int RQ = RS / 4;
   const int srow = (s_begin + lane < s_end) ? s_begin + lane : s_begin;   // idle lanes redo a valid row
@@ -173,7 +185,7 @@ __device__ __forceinline__ void uniform_tile(const float (&col)[SP], const float
     for (int i4 = 0; i4 < 4; ++i4) {
       const int i = 4 * q + i4;
       if (i < SP) {
-        const float f = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(col[i])));
+        const float f = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(colv), i));
         const float x = f + rq[i4];
         if (x < best) { best = x; a = i; }
       }
@@ -181,6 +193,8 @@ __device__ __forceinline__ void uniform_tile(const float (&col)[SP], const float
     if (4 * q == SP) { cs = rq[0]; m_own = __float_as_int(rq[1]); }
   }
   const int outv = __float_as_int(best + cs);
+  // the layer's own summary: every strategy's 64 cells are equal
+  if (s_begin + lane < s_end) sum_cur[(size_t)(s_begin + lane) * (EP >> 6) + (wbase >> 6)] = __int_as_float(outv);
   for (int s = s_begin; s < s_end; ++s) {
     const int j = s - s_begin;
     const unsigned v = (unsigned)__builtin_amdgcn_readlane(outv, j);
@@ -247,6 +261,48 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
   uint8_t* __restrict__ An = ARG ? t.A + (size_t)row * S * EP : nullptr;
   const int e0 = wbase + lane;
 
+  // Summaries: besides its table every layer leaves, per strategy and per group of 64 budgets
+  // e' of its min-plus product, the value T + c if all 64 are equal and NaN if not (sum_cur).
+  // With the run shortcut the next layer reads those few words first: column s' of its input
+  // over the wave's budgets [wbase, e_last] is C_{l-1}[s'][e] = +inf below M(l-1, s') and the
+  // previous layer's T + c at e - M above, which spans at most two of its groups; the column
+  // is constant if both summaries are the same number.  If every column is, the wave takes
+  // uniform_tile and never loads the table; otherwise it loads it and computes every cell.
+  // The layer-1 launch tests layer 0's closed form at the two ends (the columns are monotone).
+  const bool want_sum = RUNS ? true : (SPLIT ? t.runs != 0 : false);
+  float* __restrict__ sum_cur = want_sum ? sum_table(t, inst, row, l) : nullptr;
+  const int n_in = (E - wbase + 1 < 64) ? E - wbase + 1 : 64;   // budgets of this wave inside the table
+  if (RUNS) {
+    static_assert(K == 1 && SP <= 64, "one budget per lane, one lane per strategy");
+    const int e_last = wbase + n_in - 1;
+    bool ok = true;
+    float v = INFINITY;
+    if (lane < S) {
+      const int m_raw = t.M[(size_t)(row - 1) * S + lane];
+      const int m = (m_raw < 0 || m_raw > E + 1) ? E + 1 : m_raw;
+      if (FIRST) {
+        const float cv = t.c[(size_t)(row - 1) * S + lane];
+        v = wbase >= m ? cv : INFINITY;
+        const float hi = e_last >= m ? cv : INFINITY;
+        ok = __float_as_int(v) == __float_as_int(hi);
+      } else if (e_last < m) {
+        // the whole range lies in the +inf prefix
+      } else if (wbase < m) {
+        ok = false;
+      } else {
+        const float* __restrict__ sp_ = sum_table(t, inst, row - 1, l - 1) + (size_t)lane * (EP >> 6);
+        const int b1 = __float_as_int(sp_[(wbase - m) >> 6]), b2 = __float_as_int(sp_[(e_last - m) >> 6]);
+        ok = b1 == b2 && !is_nan_bits(b1);
+        v = __int_as_float(b1);
+      }
+    }
+    if (__builtin_amdgcn_ballot_w64(!ok) == 0) {
+      uniform_tile<SP, ARG>(v, rt_lds, s_begin, s_end, lane, e0, wbase, Cn, An, sum_cur, E, EP);
+      return;
+    }
+  }
+  int sumv = kNaNBits;                                    // lane j: summary of strategy s_begin + j
+
   // EP is a multiple of 64*K and wbase <= E < EP, so rows e0 + 64*j < EP are
   // inside the allocation; rows in (E, EP) are padding whose results are
   // never stored into the table proper.
@@ -281,22 +337,6 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
     }
   }
 
-  if (RUNS) {
-    // are the columns of all budgets of this wave (those inside the table) the same, bit for bit?
-    static_assert(K == 1, "one budget per lane");
-    const bool inside = e0 <= E;
-    unsigned long long differ = 0;
-#pragma unroll
-    for (int sp = 0; sp < SP; ++sp) {
-      const int own = __float_as_int(cp[0][sp]);
-      differ |= __builtin_amdgcn_ballot_w64(inside && own != __builtin_amdgcn_readfirstlane(own));
-    }
-    if (differ == 0) {
-      uniform_tile<SP, ARG>(cp[0], rt_lds, s_begin, s_end, lane, e0, wbase, Cn, An, E, EP);
-      return;
-    }
-  }
-
   if (!ARG) {
     // Values only: the argmin records are not materialised (the walkers recompute the
     // one record they need per layer from the kept tables).  One add and half a
@@ -326,10 +366,18 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
       float* Cs = Cn + (size_t)s * EP;
       const __amdgpu_buffer_rsrc_t bc = __builtin_amdgcn_make_buffer_rsrc(Cs, 0, (E + 1) * 4, kBufWord3);
       const __amdgpu_buffer_rsrc_t binf = __builtin_amdgcn_make_buffer_rsrc(Cs, 0, m * 4, kBufWord3);
-      __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc + cs), bc, (e0 + m) * 4, 0, 0);
+      const int outb = __float_as_int(acc + cs);
+      __builtin_amdgcn_raw_buffer_store_b32((unsigned)outb, bc, (e0 + m) * 4, 0, 0);
       if (wbase < m)                                       // wave-uniform: some lane is below M
         __builtin_amdgcn_raw_buffer_store_b32(0x7f800000u, binf, e0 * 4, 0, 0);
+      if (want_sum) {
+        // T + c is non-increasing along the budgets: all equal exactly when the ends are
+        const int first = __builtin_amdgcn_readfirstlane(outb), last = __builtin_amdgcn_readlane(outb, n_in - 1);
+        sumv = (lane == s - s_begin) ? (first == last ? first : kNaNBits) : sumv;
+      }
     }
+    if (want_sum && s_begin + lane < s_end)
+      sum_cur[(size_t)(s_begin + lane) * (EP >> 6) + (wbase >> 6)] = __int_as_float(sumv);
     return;
   }
 
@@ -426,11 +474,18 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
 
       const int e = e0 + 64 * j;                         // pre-shift budget e'
       __builtin_amdgcn_raw_buffer_store_b8((unsigned char)arg, ba, e, 0, SPLIT ? 0 : kStreaming);
-      __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(T + cs), bc, (e + m) * 4, 0, 0);
+      const int outb = __float_as_int(T + cs);
+      __builtin_amdgcn_raw_buffer_store_b32((unsigned)outb, bc, (e + m) * 4, 0, 0);
       if (wbase + 64 * j < m)                            // wave-uniform: some lane is below M
         __builtin_amdgcn_raw_buffer_store_b32(0x7f800000u, binf, e * 4, 0, 0);
+      if (want_sum) {
+        const int first = __builtin_amdgcn_readfirstlane(outb), last = __builtin_amdgcn_readlane(outb, n_in - 1);
+        sumv = (lane == s - s_begin) ? (first == last ? first : kNaNBits) : sumv;
+      }
     }
   }
+  if (want_sum && s_begin + lane < s_end)
+    sum_cur[(size_t)(s_begin + lane) * (EP >> 6) + (wbase >> 6)] = __int_as_float(sumv);
 }
 
 // Any S up to 256: the C_{l-1} tile of 64 budgets is staged in LDS as
@@ -483,8 +538,9 @@ struct Blocking {                       // budgets per lane for a given strategy
   static constexpr int MINW_FIRST = (SP > 40 && SP <= 44) ? 7 : MINW;
   // without the argmin pass: the SP table values plus about 16 working registers
   static constexpr int MINW_VALUES = (SP <= 44) ? 8 : (SP <= 52) ? 7 : (SP <= 60) ? 6 : 5;
-  // with the run shortcut compiled in, the records kernel at 44 strategies needs one wave fewer
-  static constexpr int MINW_RUNS = (SP > 40 && SP <= 44) ? 7 : MINW;
+  // with the run shortcut and the summaries compiled in, the records kernel needs one wave fewer
+  // where the registers were already tight
+  static constexpr int MINW_RUNS = (SP > 36 && SP <= 44) ? 7 : (SP > 52 && SP <= 56) ? 5 : MINW;
   static constexpr int MINW_VALUES_FIRST_RUNS = (SP > 40 && SP <= 44) ? 7 : MINW_VALUES;
 };
 

@@ -623,6 +623,8 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
   // with argmin records: a rolling pair of fp32 layer tables per slot and one byte per cell of
   // every layer; without: the fp32 tables of all layers
   const bool lazy = (flags & GBMW_FLAG_LAZY_ARGMIN) != 0;
+  const bool runs = (flags & GBMW_FLAG_DENSE_ARITHMETIC) == 0;
+  if (runs) TRY(c->d_sum.reserve(sizeof(float) * ((size_t)S * (EP / 64)) * (lazy ? rows : (size_t)2 * B)));
   if (lazy) {
     TRY(c->d_C.reserve(sizeof(float) * slab * rows));
   } else {
@@ -636,7 +638,8 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
 
   gbmw::Tables& t = c->t;
   t.B = B; t.S = S; t.SP = SP; t.RS = RS; t.E = E; t.EP = EP; t.keep_all = lazy ? 1 : 0;
-  t.runs = (flags & GBMW_FLAG_DENSE_ARITHMETIC) ? 0 : 1;
+  t.runs = runs ? 1 : 0;
+  t.Tsum = runs ? (float*)c->d_sum.p : nullptr;
   t.final_from = std::max(0, E - ob_max);              // Algorithm 3 reads best(e) from E - b_up on
   t.L = (const int*)c->d_L.p; t.off = (const int*)c->d_off.p; t.perm = (const int*)c->d_perm.p;
   t.c = gc; t.M = gM; t.Rt = (const float*)c->d_Rt.p;
