@@ -162,16 +162,14 @@ __device__ __forceinline__ float fmin3(float a, float b, float c) {
 // min_s' (column[s'] + R[s'][s_begin + j]) with the lowest minimising s' (strict compare in index
 // order), adds c, and the results go out to the 64 budgets strategy by strategy.  Same operands
 // and operations per cell as the dense path, hence the same bits.
-template <int SP, bool ARG>
-__device__ __forceinline__ void uniform_tile(const float colv, const float4* rt_lds, int s_begin,
-                                             int s_end, int lane, int e0, int wbase, float* __restrict__ Cn,
-                                             uint8_t* __restrict__ An, float* __restrict__ sum_cur, int E,
-                                             int EP) {
+template <int SP>
+__device__ __forceinline__ void uniform_min(const float colv, const float4* rt_lds, int srow, int& outv,
+                                            int& a, int& m_own) {
   constexpr int RS = (SP + 2 + 3) / 4 * 4;
   constexpr int RQ = RS / 4;
-  const int srow = (s_begin + lane < s_end) ? s_begin + lane : s_begin;   // idle lanes redo a valid row
   float best = INFINITY, cs = 0.0f;
-  int a = 0, m_own = 0;
+  a = 0;
+  m_own = 0;
   int roff = srow * RQ;
 #pragma unroll
   for (int q = 0; q < RQ; ++q) {
@@ -192,7 +190,17 @@ __device__ __forceinline__ void uniform_tile(const float colv, const float4* rt_
     }
     if (4 * q == SP) { cs = rq[0]; m_own = __float_as_int(rq[1]); }
   }
-  const int outv = __float_as_int(best + cs);
+  outv = __float_as_int(best + cs);
+}
+
+template <int SP, bool ARG>
+__device__ __forceinline__ void uniform_tile(const float colv, const float4* rt_lds, int s_begin,
+                                             int s_end, int lane, int e0, int wbase, float* __restrict__ Cn,
+                                             uint8_t* __restrict__ An, float* __restrict__ sum_cur, int E,
+                                             int EP) {
+  const int srow = (s_begin + lane < s_end) ? s_begin + lane : s_begin;   // idle lanes redo a valid row
+  int outv, a, m_own;
+  uniform_min<SP>(colv, rt_lds, srow, outv, a, m_own);
   // the layer's own summary: every strategy's 64 cells are equal
   if (s_begin + lane < s_end) sum_cur[(size_t)(s_begin + lane) * (EP >> 6) + (wbase >> 6)] = __int_as_float(outv);
   for (int s = s_begin; s < s_end; ++s) {
@@ -210,6 +218,50 @@ __device__ __forceinline__ void uniform_tile(const float colv, const float4* rt_
     }
     __builtin_amdgcn_raw_buffer_store_b32(v, bc, (e0 + m) * 4, 0, 0);
     if (wbase < m) __builtin_amdgcn_raw_buffer_store_b32(0x7f800000u, binf, e0 * 4, 0, 0);
+  }
+}
+
+// The same for a whole workgroup whose four waves (256 budgets from `base`) all carry that one
+// column: the waves divide the output strategies instead of the budgets, and every store
+// covers all 256 budgets of its strategy: lane i writes budgets base + 4 i .. 4 i + 3 with one
+// 128-bit store (range-checked per dword, so the end of the table and the +inf prefix cut it
+// where they fall), the records as one dword of four equal bytes.  A quarter of the stores
+// and of the bookkeeping per cell.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+template <int SP, bool ARG>
+__device__ __forceinline__ void wide_tile(const float colv, const float4* rt_lds, int s_begin, int s_end,
+                                          int lane, int base, float* __restrict__ Cn,
+                                          uint8_t* __restrict__ An, float* __restrict__ sum_cur, int E,
+                                          int EP) {
+  const int srow = (s_begin + lane < s_end) ? s_begin + lane : s_begin;
+  int outv, a, m_own;
+  uniform_min<SP>(colv, rt_lds, srow, outv, a, m_own);
+  if (s_begin + lane < s_end) {
+    float* sp_ = sum_cur + (size_t)(s_begin + lane) * (EP >> 6) + (base >> 6);
+    const int last_group = E >> 6;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      if ((base >> 6) + k <= last_group) sp_[k] = __int_as_float(outv);
+  }
+  for (int s = s_begin; s < s_end; ++s) {
+    const int j = s - s_begin;
+    const unsigned v = (unsigned)__builtin_amdgcn_readlane(outv, j);
+    const int m_raw = __builtin_amdgcn_readlane(m_own, j);
+    const int m = (m_raw < 0 || m_raw > E + 1) ? E + 1 : m_raw;
+    float* Cs = Cn + (size_t)s * EP;
+    const __amdgpu_buffer_rsrc_t bc = __builtin_amdgcn_make_buffer_rsrc(Cs, 0, (E + 1) * 4, kBufWord3);
+    const __amdgpu_buffer_rsrc_t binf = __builtin_amdgcn_make_buffer_rsrc(Cs, 0, m * 4, kBufWord3);
+    if (ARG) {
+      const unsigned ar = (unsigned)__builtin_amdgcn_readlane(a, j);
+      const __amdgpu_buffer_rsrc_t ba = __builtin_amdgcn_make_buffer_rsrc(An + (size_t)s * EP, 0, EP, kBufWord3);
+      __builtin_amdgcn_raw_buffer_store_b32(ar * 0x01010101u, ba, base + 4 * lane, 0, kStreaming);
+    }
+    const u32x4 vv = {v, v, v, v};
+    __builtin_amdgcn_raw_buffer_store_b128(vv, bc, (base + m + 4 * lane) * 4, 0, 0);
+    if (base < m) {
+      const u32x4 inf4 = {0x7f800000u, 0x7f800000u, 0x7f800000u, 0x7f800000u};
+      __builtin_amdgcn_raw_buffer_store_b128(inf4, binf, (base + 4 * lane) * 4, 0, 0);
+    }
   }
 }
 
@@ -253,7 +305,8 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
   // shortens the serial chain per wave NW-fold at the price of loading the tile
   // NW times (from L2).
   const int wbase = (split ? tile : tile * NW + wave) * (64 * K);
-  if (wbase > E) return;                                 // whole wave beyond the table
+  const bool present = wbase <= E;                       // else: whole wave beyond the table
+  if (!RUNS && !present) return;
   const int s_begin = split ? (wave * S) / NW : 0;
   const int s_end = split ? ((wave + 1) * S) / NW : S;
   const float* __restrict__ Cp = c_table(t, inst, row - 1, l - 1);
@@ -277,7 +330,7 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
     const int e_last = wbase + n_in - 1;
     bool ok = true;
     float v = INFINITY;
-    if (lane < S) {
+    if (present && lane < S) {
       const int m_raw = t.M[(size_t)(row - 1) * S + lane];
       const int m = (m_raw < 0 || m_raw > E + 1) ? E + 1 : m_raw;
       if (FIRST) {
@@ -296,7 +349,29 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
         v = __int_as_float(b1);
       }
     }
-    if (__builtin_amdgcn_ballot_w64(!ok) == 0) {
+    const bool mine = __builtin_amdgcn_ballot_w64(!ok) == 0;
+    // Do all waves of the workgroup (those inside the table) carry the same one column?  Each
+    // publishes its verdict and its column, and every wave forms the same answer from them.
+    static_assert(NW == 4, "four waves share their columns");
+    __shared__ float x_col[NW][64];
+    __shared__ int x_ok[NW];
+    x_col[wave][lane] = v;
+    if (lane == 0) x_ok[wave] = present ? (mine ? 1 : 0) : 2;       // 2: not inside the table
+    __syncthreads();
+    const float v0 = x_col[0][lane];
+    bool same = true;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const int st = x_ok[w];
+      same = same && (st == 2 || (st == 1 && __float_as_int(x_col[w][lane]) == __float_as_int(v0)));
+    }
+    if (__builtin_amdgcn_ballot_w64(!same) == 0) {
+      wide_tile<SP, ARG>(v0, rt_lds, (wave * S) / NW, ((wave + 1) * S) / NW, lane, tile * NW * 64, Cn, An,
+                         sum_cur, E, EP);
+      return;
+    }
+    if (!present) return;
+    if (mine) {
       uniform_tile<SP, ARG>(v, rt_lds, s_begin, s_end, lane, e0, wbase, Cn, An, sum_cur, E, EP);
       return;
     }
@@ -540,8 +615,10 @@ struct Blocking {                       // budgets per lane for a given strategy
   static constexpr int MINW_VALUES = (SP <= 44) ? 8 : (SP <= 52) ? 7 : (SP <= 60) ? 6 : 5;
   // with the run shortcut and the summaries compiled in, the records kernel needs one wave fewer
   // where the registers were already tight
-  static constexpr int MINW_RUNS = (SP > 36 && SP <= 44) ? 7 : (SP > 52 && SP <= 56) ? 5 : MINW;
-  static constexpr int MINW_VALUES_FIRST_RUNS = (SP > 40 && SP <= 44) ? 7 : MINW_VALUES;
+  // with the run shortcut compiled in (summaries, the exchange between the waves, the wide
+  // stores) both kernels need a few registers more; targets found by compiling every size
+  static constexpr int MINW_RUNS = (SP <= 36) ? 8 : (SP <= 44) ? 7 : (SP <= 48) ? 6 : 5;
+  static constexpr int MINW_VALUES_RUNS = (SP <= 36) ? 8 : (SP <= 44) ? 7 : (SP <= 52) ? 6 : 5;
 };
 
 template <int SP>
@@ -563,22 +640,21 @@ static void launch_minplus_sp(const Tables& t, int l, int first, int n_active, h
                      tiles, first)
   const bool runs = t.runs != 0;
   if (t.A == nullptr) {
-    constexpr int MW = Blocking<SP>::MINW_VALUES, MW1R = Blocking<SP>::MINW_VALUES_FIRST_RUNS;
+    constexpr int MW = Blocking<SP>::MINW_VALUES, MWR = Blocking<SP>::MINW_VALUES_RUNS;
     if (l == 1) {
       if (split) GBMW_LAUNCH(MS, true, false, true, false);
-      else if (runs) GBMW_LAUNCH(MW1R, true, false, false, true);
+      else if (runs) GBMW_LAUNCH(MWR, true, false, false, true);
       else GBMW_LAUNCH(MW, true, false, false, false);
     } else {
       if (split) GBMW_LAUNCH(MS, false, false, true, false);
-      else if (runs) GBMW_LAUNCH(MW, false, false, false, true);
+      else if (runs) GBMW_LAUNCH(MWR, false, false, false, true);
       else GBMW_LAUNCH(MW, false, false, false, false);
     }
   } else {
     constexpr int M1 = Blocking<SP>::MINW_FIRST, MR = Blocking<SP>::MINW_RUNS;
-    constexpr int M1R = M1 < MR ? M1 : MR;
     if (l == 1) {
       if (split) GBMW_LAUNCH(MS, true, true, true, false);
-      else if (runs) GBMW_LAUNCH(M1R, true, true, false, true);
+      else if (runs) GBMW_LAUNCH(MR, true, true, false, true);
       else GBMW_LAUNCH(M1, true, true, false, false);
     } else {
       if (split) GBMW_LAUNCH(MS, false, true, true, false);
