@@ -291,12 +291,6 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
   const int tile = wg % tiles;
   const int S = t.S, E = t.E, EP = t.EP;
   const int row = t.off[inst] + l;
-  {
-    const float4* __restrict__ src = reinterpret_cast<const float4*>(t.Rt + (size_t)row * S * RS);
-    for (int i = threadIdx.x; i < S * RQ; i += 64 * NW) rt_lds[i] = src[i];
-  }
-  __syncthreads();
-
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, scalar
   const int lane = threadIdx.x & 63;
   // Normal mode: the workgroup's waves take consecutive row tiles and every
@@ -306,6 +300,43 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
   // NW times (from L2).
   const int wbase = (split ? tile : tile * NW + wave) * (64 * K);
   const bool present = wbase <= E;                       // else: whole wave beyond the table
+  const int n_in = (E - wbase + 1 < 64) ? E - wbase + 1 : 64;   // budgets of this wave inside the table
+
+  // The run test's words (the previous layer's M, then two summaries whose place depends on
+  // it: two memory round trips in a row) are asked for around the loads that stage the tile
+  // of R, so that the three overlap instead of following one another.
+  int rt_m = 0, rt_b1 = 0, rt_b2 = 0;
+  float rt_c = INFINITY;
+  const bool rt_lane = RUNS && present && lane < S;
+  if (rt_lane) {
+    rt_m = t.M[(size_t)(row - 1) * S + lane];
+    if (FIRST) rt_c = t.c[(size_t)(row - 1) * S + lane];
+  }
+  {
+    const float4* __restrict__ src = reinterpret_cast<const float4*>(t.Rt + (size_t)row * S * RS);
+    constexpr int NSTG = (SP * RQ + 64 * NW - 1) / (64 * NW);
+    float4 stg[NSTG];
+#pragma unroll
+    for (int k = 0; k < NSTG; ++k) {
+      const int i = threadIdx.x + k * 64 * NW;
+      stg[k] = (i < S * RQ) ? src[i] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    }
+    if (rt_lane && !FIRST) {
+      const int m = (rt_m < 0 || rt_m > E + 1) ? E + 1 : rt_m;
+      const int e_last = wbase + n_in - 1;
+      if (wbase >= m) {                                  // else: decided below without the summaries
+        const float* __restrict__ sp_ = sum_table(t, inst, row - 1, l - 1) + (size_t)lane * (EP >> 6);
+        rt_b1 = __float_as_int(sp_[(wbase - m) >> 6]);
+        rt_b2 = __float_as_int(sp_[(e_last - m) >> 6]);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < NSTG; ++k) {
+      const int i = threadIdx.x + k * 64 * NW;
+      if (i < S * RQ) rt_lds[i] = stg[k];
+    }
+  }
+  __syncthreads();
   if (!RUNS && !present) return;
   const int s_begin = split ? (wave * S) / NW : 0;
   const int s_end = split ? ((wave + 1) * S) / NW : S;
@@ -324,17 +355,15 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
   // The layer-1 launch tests layer 0's closed form at the two ends (the columns are monotone).
   const bool want_sum = RUNS ? true : (SPLIT ? t.runs != 0 : false);
   float* __restrict__ sum_cur = want_sum ? sum_table(t, inst, row, l) : nullptr;
-  const int n_in = (E - wbase + 1 < 64) ? E - wbase + 1 : 64;   // budgets of this wave inside the table
   if (RUNS) {
     static_assert(K == 1 && SP <= 64, "one budget per lane, one lane per strategy");
     const int e_last = wbase + n_in - 1;
     bool ok = true;
     float v = INFINITY;
-    if (present && lane < S) {
-      const int m_raw = t.M[(size_t)(row - 1) * S + lane];
-      const int m = (m_raw < 0 || m_raw > E + 1) ? E + 1 : m_raw;
+    if (rt_lane) {
+      const int m = (rt_m < 0 || rt_m > E + 1) ? E + 1 : rt_m;
       if (FIRST) {
-        const float cv = t.c[(size_t)(row - 1) * S + lane];
+        const float cv = rt_c;
         v = wbase >= m ? cv : INFINITY;
         const float hi = e_last >= m ? cv : INFINITY;
         ok = __float_as_int(v) == __float_as_int(hi);
@@ -343,10 +372,8 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
       } else if (wbase < m) {
         ok = false;
       } else {
-        const float* __restrict__ sp_ = sum_table(t, inst, row - 1, l - 1) + (size_t)lane * (EP >> 6);
-        const int b1 = __float_as_int(sp_[(wbase - m) >> 6]), b2 = __float_as_int(sp_[(e_last - m) >> 6]);
-        ok = b1 == b2 && !is_nan_bits(b1);
-        v = __int_as_float(b1);
+        ok = rt_b1 == rt_b2 && !is_nan_bits(rt_b1);
+        v = __int_as_float(rt_b1);
       }
     }
     const bool mine = __builtin_amdgcn_ballot_w64(!ok) == 0;
