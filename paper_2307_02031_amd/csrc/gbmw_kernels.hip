@@ -271,6 +271,10 @@ template <int SP, int K, int NW, int CH, int MINW, bool FIRST, bool ARG, bool SP
 __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int tiles, int first) {
   constexpr bool split = SPLIT;
   static_assert(!(SPLIT && RUNS), "no run shortcut in split mode");
+  // With the run shortcut the waves that compute every cell are few and sit among waves that
+  // hardly use the VALU: nothing hides the latency of their reads of the R tile, so they fetch
+  // row s + 1 into registers while row s is being folded (a software pipeline one row deep).
+  constexpr bool PRE = RUNS && SP <= 48;                 // beyond, two rows of R no longer fit beside the table values
   constexpr int NC = (SP + CH - 1) / CH;                 // chunks (last may be short)
   constexpr int NP = NC / 2 + 1;                         // prefix minima / blocks
   constexpr int RS = (SP + 2 + 3) / 4 * 4;               // row: SP x R, c, M, padding
@@ -444,12 +448,20 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
     // one record they need per layer from the kept tables).  One add and half a
     // three-input min per candidate; the R row is consumed quad by quad as it arrives.
     static_assert(K == 1 || ARG, "the values-only path handles one budget per lane");
+    float4 rowq[PRE ? RQ : 1];
+    if (PRE) {
+#pragma unroll
+      for (int q = 0; q < RQ; ++q) rowq[q] = rt_lds[s_begin * RQ + q];
+    }
     for (int s = s_begin; s < s_end; ++s) {
       float acc = INFINITY, cs = 0.0f;
       int m_raw = 0;
+      const int s_next = (s + 1 < s_end) ? s + 1 : s;      // the last row is fetched once more, unused
 #pragma unroll
       for (int q = 0; q < RQ; ++q) {
-        const float4 v = rt_lds[s * RQ + q];
+        float4 v;
+        if (PRE) { v = rowq[q]; rowq[q] = rt_lds[s_next * RQ + q]; }
+        else v = rt_lds[s * RQ + q];
         const float rq[4] = {v.x, v.y, v.z, v.w};
         float xq[4];
 #pragma unroll
@@ -484,7 +496,13 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
   }
 
   static_assert(K == 1, "one budget per lane");
+  float4 rowq[PRE ? RQ : 1];
+  if (PRE) {
+#pragma unroll
+    for (int q = 0; q < RQ; ++q) rowq[q] = rt_lds[s_begin * RQ + q];
+  }
   for (int s = s_begin; s < s_end; ++s) {
+    const int s_next = (s + 1 < s_end) ? s + 1 : s;        // the last row is fetched once more, unused
     // ---- value pass, streaming: the R row is consumed quad by quad as it arrives from LDS,
     // candidates fold into chunk minima and those into the prefix minima at once, so that
     // only the prefix minima stay live (the sums are not kept: the rescan redoes the few it
@@ -495,7 +513,9 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
     int m_raw = 0;
 #pragma unroll
     for (int q = 0; q < RQ; ++q) {
-      const float4 v = rt_lds[s * RQ + q];
+      float4 v;
+      if (PRE) { v = rowq[q]; rowq[q] = rt_lds[s_next * RQ + q]; }
+      else v = rt_lds[s * RQ + q];
       const float rq[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
@@ -642,10 +662,12 @@ struct Blocking {                       // budgets per lane for a given strategy
   static constexpr int MINW_VALUES = (SP <= 44) ? 8 : (SP <= 52) ? 7 : (SP <= 60) ? 6 : 5;
   // with the run shortcut and the summaries compiled in, the records kernel needs one wave fewer
   // where the registers were already tight
-  // with the run shortcut compiled in (summaries, the exchange between the waves, the wide
-  // stores) both kernels need a few registers more; targets found by compiling every size
-  static constexpr int MINW_RUNS = (SP <= 36) ? 8 : (SP <= 44) ? 7 : (SP <= 48) ? 6 : 5;
-  static constexpr int MINW_VALUES_RUNS = (SP <= 36) ? 8 : (SP <= 44) ? 7 : (SP <= 52) ? 6 : 5;
+  // with the run shortcut compiled in: up to 48 strategies the dense path keeps two rows of R
+  // in registers (see PRE in the kernel), beyond it needs a few registers more than without
+  // the shortcut; targets found by compiling every size
+  static constexpr int MINW_RUNS = (SP <= 16) ? 8 : (SP <= 20) ? 7 : (SP <= 24) ? 6 : (SP <= 28) ? 5
+                                   : (SP <= 44) ? 4 : (SP <= 48) ? 3 : 5;
+  static constexpr int MINW_VALUES_RUNS = (SP <= 48) ? MINW_RUNS : (SP <= 52) ? 6 : 5;
 };
 
 template <int SP>
