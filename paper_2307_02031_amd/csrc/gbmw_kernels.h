@@ -23,9 +23,12 @@ struct Tables {
   int B, S, SP, RS, E, EP;
   int keep_all;        // 1: Call[row][S][EP] for every layer row; 0: rolling pair
   int final_from;      // the final reduce fills best / best_s for e >= final_from only
-  int runs;            // 1: a wave whose 64 budgets all have the same input column (the tables are
+  int runs;            // 1, 2: a wave whose 64 budgets all have the same input column (the tables are
                        // step functions of the budget) computes that column once, one output
-                       // strategy per lane; 0: every lane computes its own cell
+                       // strategy per lane; 0: every lane computes its own cell.  2: split launches
+                       // write summaries as well (needed where a later, larger launch may extend a
+                       // table that a split launch produced: the partition search; inside one solve
+                       // the launches only shrink, and a split launch is followed by split launches)
   const int* L;        // [B]   device
   const int* off;      // [B]   device, first row of each instance
   const int* perm;     // [B]   device, instances ordered by L descending

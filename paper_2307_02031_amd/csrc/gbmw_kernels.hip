@@ -357,7 +357,7 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
   // is constant if both summaries are the same number.  If every column is, the wave takes
   // uniform_tile and never loads the table; otherwise it loads it and computes every cell.
   // The layer-1 launch tests layer 0's closed form at the two ends (the columns are monotone).
-  const bool want_sum = RUNS ? true : (SPLIT ? t.runs != 0 : false);
+  const bool want_sum = RUNS ? true : (SPLIT ? t.runs == 2 : false);
   float* __restrict__ sum_cur = want_sum ? sum_table(t, inst, row, l) : nullptr;
   if (RUNS) {
     static_assert(K == 1 && SP <= 64, "one budget per lane, one lane per strategy");

@@ -638,7 +638,7 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
 
   gbmw::Tables& t = c->t;
   t.B = B; t.S = S; t.SP = SP; t.RS = RS; t.E = E; t.EP = EP; t.keep_all = lazy ? 1 : 0;
-  t.runs = runs ? 1 : 0;
+  t.runs = runs ? 2 : 0;
   t.Tsum = runs ? (float*)c->d_sum.p : nullptr;
   t.final_from = std::max(0, E - ob_max);              // Algorithm 3 reads best(e) from E - b_up on
   t.L = (const int*)c->d_L.p; t.off = (const int*)c->d_off.p; t.perm = (const int*)c->d_perm.p;
