@@ -75,8 +75,11 @@ enum {
                                   the previous layer's table (the tables are step functions
                                   of the budget, so most waves do) computes that column's
                                   cells once, one output strategy per lane, and writes the
-                                  result to all 64 budgets.  Identical results either way;
-                                  the flag exists to time the dense arithmetic            */
+                                  result to all 64 budgets; to recognise such waves without
+                                  reading the table every layer also leaves one word per
+                                  strategy and 64 budgets (1/64 of the fp32 table bytes of
+                                  device memory more).  Identical results either way; the
+                                  flag exists to time the dense arithmetic                */
 };
 
 #define GBMW_MAX_S 256
