@@ -118,6 +118,31 @@ def test_kept_tables_are_extended_not_recomputed(g):
     g.gbmw_destroy(ctx)
 
 
+def test_large_launch_extends_tables_that_small_launches_produced(g):
+    """Eight pairs whose long first stage (10 layers) takes one more layer at its end after the
+    first search.  In the first round the deep layers of those stages run in small launches
+    (four stages per stream group: the shape in which the waves of a workgroup share a tile);
+    the extension runs as ONE launch over all eight (the shape with the shortcut for runs of
+    equal columns), which decides from the summaries the small launches left.  Traces against
+    the oracle, with and without records, and the count of executed layer steps."""
+    E = 32768
+    models = []
+    for k in (0, 2, 4, 5, 6, 7, 8, 9):
+        mod = gi.random_pipeline_model(900 + k, 13, 5, 2, E=E, m=4, M_rng=(200, 2400), R_rng=(0.0, 0.5),
+                                       with_pt=False)
+        mod.c[11:] *= 8.0; mod.c_ns[11:] *= 8.0          # the last two layers make stage 1 the slowest
+        mod.p0 = np.array([10, 3], np.int32)
+        models.append(mod)
+    ctx = None
+    for flags in (0, g.GBMW_FLAG_LAZY_ARGMIN):
+        res, ctx = _search(g, models, max_iter=6, flags=flags, ctx=ctx)
+        check_partition_search(res, models, 6)
+        assert all(list(res["p"][k, 1, :2]) == [11, 2] for k in range(8))
+        # first round 8 x (9 + 2) steps; second 8 x (1 + 1); the last pair goes on to [12, 1]: 1 + 0
+        assert res["cell_updates"] == (88 + 16 + 1) * (E + 1) * 25, res["cell_updates"]
+    g.gbmw_destroy(ctx)
+
+
 def test_changed_stage_reuse_solves_less_and_agrees(g):
     models = [gi.random_pipeline_model(9500 + k, 24, 22, 4, 600, M_rng=(1, 40)) for k in range(6)]
     a, ctx = _search(g, models, max_iter=32)
