@@ -289,7 +289,28 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
   int wg = blockIdx.x;
   if (RUNS) {
     const int nb = gridDim.x, q8 = nb >> 3, r8 = nb & 7, x = wg & 7;
-    wg = x * q8 + (x < r8 ? x : r8) + (wg >> 3);
+    // j-th workgroup of XCD x, which owns the cnt consecutive (instance, tile) pairs from first
+    const int j = wg >> 3, cnt = q8 + (x < r8 ? 1 : 0), first_pair = x * q8 + (x < r8 ? x : r8);
+    // Inside that range the order is tile by tile across the instances, not instance by
+    // instance: the tiles that must be computed cell by cell lie at the low budgets of every
+    // instance and take many times longer than the others, so they have to start early, all
+    // of them, and leave the end of the launch to the quick ones.  (A range starts and ends
+    // inside an instance: the tail piece of the last instance goes first, it holds that
+    // instance's low tiles; the head piece of the first one, its high tiles, goes last.)
+    const int last_pair = first_pair + cnt - 1;
+    const int ia = first_pair / tiles, t0 = first_pair % tiles, ib = last_pair / tiles, t1 = last_pair % tiles;
+    if (ia == ib) {
+      wg = first_pair + j;
+    } else {
+      const int c = (t1 == tiles - 1) ? 0 : t1 + 1;      // piece of the last instance
+      const int fb = (t0 == 0) ? ia : ia + 1;            // whole instances fb .. fe
+      const int fe = (t1 == tiles - 1) ? ib : ib - 1;
+      const int nf = fe - fb + 1;
+      const int q = j - c;
+      if (j < c) wg = ib * tiles + j;
+      else if (q < nf * tiles) wg = (fb + q % nf) * tiles + q / nf;
+      else wg = ia * tiles + t0 + (q - nf * tiles);
+    }
   }
   const int inst = t.perm[first + wg / tiles];
   const int tile = wg % tiles;
