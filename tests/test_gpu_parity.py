@@ -256,6 +256,36 @@ def test_runs_of_equal_columns_edge_cases(g, S, mode):
     g.gbmw_destroy(ctx)
 
 
+@pytest.mark.parametrize("mode", list(MODES), ids=list(MODES))
+@pytest.mark.parametrize("E", [100, 300, 767])
+def test_many_small_instances_in_one_launch(g, E, mode):
+    """Hundreds of instances with one to three workgroups each: a launch large enough for the
+    unsplit shape whose workgroups are mostly cut by the end of the table (waves entirely
+    beyond E, a ragged last wave, E + 1 a multiple of 256 for E = 767).  Integer costs, so runs
+    of equal columns and ties are everywhere.  Every 37th instance cell by cell, best rows of all."""
+    flags = MODES[mode]
+    B, S = 700, 7
+    st = gi.Stream(8800 + E)
+    parts = []
+    for i in range(B):
+        L = 2 + i % 3
+        c = st.integers(L * S, 1, 5).astype(np.float32).reshape(L, S)
+        M = st.integers(L * S, 0, max(1, E // 3)).reshape(L, S)
+        R = st.integers(L * S * S, 0, 2).astype(np.float32).reshape(L, S, S)
+        parts.append(gi.Problem(1, S, E, np.array([L]), c, M, R))
+    p = gi.stack(parts, f"small-E{E}")
+    keep = 0 if flags & 16 else g.GBMW_FLAG_KEEP_ALL_C
+    ctx = solve_gpu(p, flags=flags | keep | g.GBMW_FLAG_ONE_STREAM, device_inputs=True)
+    best, best_s = g.gbmw_get_best(ctx)
+    for b in range(0, B, 37):
+        check_instance(g, ctx, p, b, full_C=True, q_es=[0, E // 2, E], best=best, best_s=best_s, nthreads=2)
+    for b in range(B):
+        ref = oracle.solve_problem(p, b, keep_C=False, keep_A=False, nthreads=1)
+        pins.assert_same_f32(best[b], ref.best, f"small-E{E}[{b}] best")
+        assert np.array_equal(best_s[b], ref.best_s)
+    g.gbmw_destroy(ctx)
+
+
 @pytest.mark.parametrize("lazy", [False, True], ids=["records", "lazy-argmin"])
 def test_config4_dense_arithmetic(g, lazy):
     """The benchmark's batch with GBMW_FLAG_DENSE_ARITHMETIC (every lane computes its own
