@@ -230,7 +230,8 @@ def test_outer_loops_throughput(g):
 def test_benchmark_workload_all_modes_agree(g):
     """The workload bench.py times (16 pairs, 48 layers, S = 44, E = 32768): kept tables,
     every stage re-solved, no argmin records, and dense arithmetic (no shortcut for waves whose
-    budgets share one input column) give the same traces bit for bit; the
+    budgets share one input column) give the same traces bit for bit, with and without
+    O_b / O_ms tables; the
     first pair is also checked against the oracle."""
     import importlib.util
     import os
@@ -244,6 +245,15 @@ def test_benchmark_workload_all_modes_agree(g):
         res, ctx = _search(g, models, max_iter=32, flags=flags, ctx=ctx)
         for key in ("n_iter", "O_t", "p", "cost", "C", "Cns", "O", "alpha_t", "alpha_m", "strat"):
             assert np.array_equal(ref[key].view(np.uint8), res[key].view(np.uint8)), (flags, key)
-    g.gbmw_destroy(ctx)
     first = {k: (v[:1] if isinstance(v, np.ndarray) else v) for k, v in ref.items()}
     check_partition_search(first, models[:1], 32)
+    # the same pairs with O_b / O_ms tables (every stage search with Appendix A's check)
+    split = [gi.with_memory_split(m, 900 + k) for k, m in enumerate(models)]
+    ref, ctx = _search(g, split, max_iter=32, ctx=ctx)
+    for flags in (g.GBMW_FLAG_RESOLVE_ALL, g.GBMW_FLAG_LAZY_ARGMIN, g.GBMW_FLAG_DENSE_ARITHMETIC):
+        res, ctx = _search(g, split, max_iter=32, flags=flags, ctx=ctx)
+        for key in ("n_iter", "O_t", "p", "cost", "C", "Cns", "O", "alpha_t", "alpha_m", "strat"):
+            assert np.array_equal(ref[key].view(np.uint8), res[key].view(np.uint8)), (flags, key)
+    g.gbmw_destroy(ctx)
+    last = {k: (v[-1:] if isinstance(v, np.ndarray) else v) for k, v in ref.items()}
+    check_partition_search(last, split[-1:], 32)             # P = 16: sixteen short stages
