@@ -342,3 +342,27 @@ def test_config5_large_batched_full_size(g):
         _log(f"cfg5 instance {b}: plan properties")
         check_plans_by_definition(g, ctx, p, b, q, best)
     g.gbmw_destroy(ctx)
+
+
+def test_config5_all_modes_agree(g):
+    """cfg5 under the four combinations of records / values only and run shortcut / dense
+    arithmetic: best rows, their argmins, the last layer's table and the records of two
+    layers of one instance are the same bytes (the default mode is checked against the
+    oracle above)."""
+    p = gi.make_config(5)
+    ref = None
+    for mode, flags in MODES.items():
+        _log(f"cfg5 {mode}")
+        ctx = solve_gpu(p, flags=flags, device_inputs=True)
+        best, best_s = g.gbmw_get_best(ctx)
+        Lb = int(p.L[3])
+        C, _ = g.gbmw_export_tables(ctx, 3, Lb - 1, Lb, want_C=True, want_A=False)
+        _, A = g.gbmw_export_tables(ctx, 3, Lb - 2, Lb, want_C=False, want_A=True)
+        got = (best.copy(), best_s.copy(), C.copy(), A.copy())
+        g.gbmw_destroy(ctx)
+        if ref is None:
+            ref = got
+        else:
+            for x, y, what in zip(ref, got, ("best", "best_s", "C", "A")):
+                assert np.array_equal(x.view(np.uint8), y.view(np.uint8)), (mode, what)
+
