@@ -257,7 +257,7 @@ def test_runs_of_equal_columns_edge_cases(g, S, mode):
 
 
 @pytest.mark.parametrize("mode", list(MODES), ids=list(MODES))
-@pytest.mark.parametrize("E", [100, 300, 767])
+@pytest.mark.parametrize("E", [0, 5, 100, 300, 767])
 def test_many_small_instances_in_one_launch(g, E, mode):
     """Hundreds of instances with one to three workgroups each: a launch large enough for the
     unsplit shape whose workgroups are mostly cut by the end of the table (waves entirely
