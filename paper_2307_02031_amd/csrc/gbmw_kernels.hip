@@ -272,48 +272,60 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
   constexpr bool split = SPLIT;
   static_assert(!(SPLIT && RUNS), "no run shortcut in split mode");
   // With the run shortcut the waves that compute every cell are few and sit among waves that
-  // hardly use the VALU: nothing hides the latency of their reads of the R tile, so they fetch
-  // row s + 1 into registers while row s is being folded (a software pipeline one row deep).
-  constexpr bool PRE = RUNS && SP <= 48;                 // beyond, two rows of R no longer fit beside the table values
+  // hardly use the VALU: nothing hides the latency of their reads of the R tile, so they keep
+  // PD quads of R in flight ahead of the fold, across the end of the row into the next one
+  // (a rotating software pipeline: the fold of a quad takes about 30 cycles, an LDS read
+  // about 130; the whole next row, tried first, costs 48 registers instead of 16 and with them
+  // a wave per SIMD).
+  constexpr bool PRE = RUNS && SP <= 56;                 // beyond, the table values leave no room for it
   constexpr int NC = (SP + CH - 1) / CH;                 // chunks (last may be short)
   constexpr int NP = NC / 2 + 1;                         // prefix minima / blocks
   constexpr int RS = (SP + 2 + 3) / 4 * 4;               // row: SP x R, c, M, padding
   constexpr int RQ = RS / 4;
+  constexpr int PD = 4;                                  // quads of R in flight ahead of the fold (PRE)
+  constexpr int RQP = (RQ + PD - 1) / PD * PD;           // the row's quads, padded to whole rounds of PD
   extern __shared__ float4 rt_lds[];                     // [S][RQ]
 
-  // Workgroups go to the 8 XCDs round-robin by their index; each XCD (its own L2) gets a
-  // contiguous range of (instance, row tile) instead, so that neighbouring tiles, whose
-  // shifted stores share a cache line at their common border, meet in one L2.  Only where the
-  // launch is bound by its memory traffic (the run shortcut); with dense arithmetic the
-  // round-robin order balances the work better.
-  int wg = blockIdx.x;
+  // Workgroups go to the 8 XCDs (each with its own L2) round-robin by their index, and an XCD
+  // works through its share in index order.  With the run shortcut the (instance, tile) pairs
+  // are dealt out accordingly:
+  //  - in chunks of kChunk consecutive tiles of one instance per XCD, so that neighbouring
+  //    tiles, whose shifted stores share a cache line at their common border, mostly meet in
+  //    one L2;
+  //  - chunk row by chunk row across the instances (all chunks 0, then all chunks 1, ...): the
+  //    tiles that must be computed cell by cell lie at the low budgets of every instance and
+  //    take many times longer than the others, so they have to start early, all of them, and
+  //    leave the end of the launch to the quick ones;
+  //  - each chunk row starting one instance further on, so that the chunks of an instance go
+  //    round the XCDs instead of all landing on one: the instances differ in how many such
+  //    tiles they have, and an XCD cannot take work from another.
+  // With dense arithmetic every tile costs the same and the plain order is kept.
+  int slot, tile;
   if (RUNS) {
-    const int nb = gridDim.x, q8 = nb >> 3, r8 = nb & 7, x = wg & 7;
-    // j-th workgroup of XCD x, which owns the cnt consecutive (instance, tile) pairs from first
-    const int j = wg >> 3, cnt = q8 + (x < r8 ? 1 : 0), first_pair = x * q8 + (x < r8 ? x : r8);
-    // Inside that range the order is tile by tile across the instances, not instance by
-    // instance: the tiles that must be computed cell by cell lie at the low budgets of every
-    // instance and take many times longer than the others, so they have to start early, all
-    // of them, and leave the end of the launch to the quick ones.  (A range starts and ends
-    // inside an instance: the tail piece of the last instance goes first, it holds that
-    // instance's low tiles; the head piece of the first one, its high tiles, goes last.)
-    const int last_pair = first_pair + cnt - 1;
-    const int ia = first_pair / tiles, t0 = first_pair % tiles, ib = last_pair / tiles, t1 = last_pair % tiles;
-    if (ia == ib) {
-      wg = first_pair + j;
-    } else {
-      const int c = (t1 == tiles - 1) ? 0 : t1 + 1;      // piece of the last instance
-      const int fb = (t0 == 0) ? ia : ia + 1;            // whole instances fb .. fe
-      const int fe = (t1 == tiles - 1) ? ib : ib - 1;
-      const int nf = fe - fb + 1;
-      const int q = j - c;
-      if (j < c) wg = ib * tiles + j;
-      else if (q < nf * tiles) wg = (fb + q % nf) * tiles + q / nf;
-      else wg = ia * tiles + t0 + (q - nf * tiles);
+    constexpr int kChunk = 16, kRound = 8 * kChunk;        // one round: a chunk for each XCD
+    const int b = blockIdx.x, nb = gridDim.x, n = nb / tiles;
+    int p = b;                                            // place in the dealt order (the ragged end keeps its own)
+    if (b < nb / kRound * kRound) {
+      const int w = b % kRound;                           // b = 8 * (round * kChunk + r) + xcd
+      p = ((b / kRound) * 8 + (w & 7)) * kChunk + (w >> 3);
     }
+    const int full = tiles / kChunk, rowlen = n * kChunk;
+    int c, k, r;
+    if (p < full * rowlen) {
+      c = p / rowlen;
+      const int rem = p - c * rowlen;
+      k = rem / kChunk; r = rem % kChunk;
+    } else {                                              // the short last chunk of every instance
+      const int cl = tiles - full * kChunk, pp = p - full * rowlen;
+      c = full; k = pp / cl; r = pp - k * cl;
+    }
+    slot = (k + c) % n;
+    tile = c * kChunk + r;
+  } else {
+    slot = blockIdx.x / tiles;
+    tile = blockIdx.x % tiles;
   }
-  const int inst = t.perm[first + wg / tiles];
-  const int tile = wg % tiles;
+  const int inst = t.perm[first + slot];
   const int S = t.S, E = t.E, EP = t.EP;
   const int row = t.off[inst] + l;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, scalar
@@ -464,25 +476,51 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
     }
   }
 
+  if (RUNS) {
+    // The summaries speak for whole groups of 64 budgets of the previous layer's product, and a
+    // column of this wave lies across two of them: about half of the waves that arrive here
+    // have 64 equal columns after all, as the loaded values show.  They take the run path too,
+    // with the column put together from the first lane's values.
+    bool differs = false;
+#pragma unroll
+    for (int sp = 0; sp < SP; ++sp) {
+      const int b = __float_as_int(cp[0][sp]);
+      differs = differs || (b != __builtin_amdgcn_readfirstlane(b));
+    }
+    if (__builtin_amdgcn_ballot_w64(differs && e0 <= E) == 0) {
+      float colv = INFINITY;
+#pragma unroll
+      for (int sp = 0; sp < SP; ++sp) {
+        const int f = __builtin_amdgcn_readfirstlane(__float_as_int(cp[0][sp]));
+        colv = (lane == sp) ? __int_as_float(f) : colv;
+      }
+      uniform_tile<SP, ARG>(colv, rt_lds, s_begin, s_end, lane, e0, wbase, Cn, An, sum_cur, E, EP);
+      return;
+    }
+  }
+
   if (!ARG) {
     // Values only: the argmin records are not materialised (the walkers recompute the
     // one record they need per layer from the kept tables).  One add and half a
     // three-input min per candidate; the R row is consumed quad by quad as it arrives.
     static_assert(K == 1 || ARG, "the values-only path handles one budget per lane");
-    float4 rowq[PRE ? RQ : 1];
+    float4 rowq[PRE ? PD : 1];
     if (PRE) {
 #pragma unroll
-      for (int q = 0; q < RQ; ++q) rowq[q] = rt_lds[s_begin * RQ + q];
+      for (int q = 0; q < PD; ++q) rowq[q] = rt_lds[s_begin * RQ + (q < RQ ? q : RQ - 1)];
     }
     for (int s = s_begin; s < s_end; ++s) {
       float acc = INFINITY, cs = 0.0f;
       int m_raw = 0;
       const int s_next = (s + 1 < s_end) ? s + 1 : s;      // the last row is fetched once more, unused
 #pragma unroll
-      for (int q = 0; q < RQ; ++q) {
+      for (int q = 0; q < (PRE ? RQP : RQ); ++q) {
         float4 v;
-        if (PRE) { v = rowq[q]; rowq[q] = rt_lds[s_next * RQ + q]; }
-        else v = rt_lds[s * RQ + q];
+        if (PRE) {
+          const int nq = q + PD, qq = nq < RQP ? nq : nq - RQP;
+          v = rowq[q % PD];
+          rowq[q % PD] = rt_lds[(nq < RQP ? s : s_next) * RQ + (qq < RQ ? qq : RQ - 1)];
+        } else v = rt_lds[s * RQ + q];
         const float rq[4] = {v.x, v.y, v.z, v.w};
         float xq[4];
 #pragma unroll
@@ -517,10 +555,10 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
   }
 
   static_assert(K == 1, "one budget per lane");
-  float4 rowq[PRE ? RQ : 1];
+  float4 rowq[PRE ? PD : 1];
   if (PRE) {
 #pragma unroll
-    for (int q = 0; q < RQ; ++q) rowq[q] = rt_lds[s_begin * RQ + q];
+    for (int q = 0; q < PD; ++q) rowq[q] = rt_lds[s_begin * RQ + (q < RQ ? q : RQ - 1)];
   }
   for (int s = s_begin; s < s_end; ++s) {
     const int s_next = (s + 1 < s_end) ? s + 1 : s;        // the last row is fetched once more, unused
@@ -533,10 +571,13 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
     float cs = 0.0f;
     int m_raw = 0;
 #pragma unroll
-    for (int q = 0; q < RQ; ++q) {
+    for (int q = 0; q < (PRE ? RQP : RQ); ++q) {
       float4 v;
-      if (PRE) { v = rowq[q]; rowq[q] = rt_lds[s_next * RQ + q]; }
-      else v = rt_lds[s * RQ + q];
+      if (PRE) {
+        const int nq = q + PD, qq = nq < RQP ? nq : nq - RQP;
+        v = rowq[q % PD];
+        rowq[q % PD] = rt_lds[(nq < RQP ? s : s_next) * RQ + (qq < RQ ? qq : RQ - 1)];
+      } else v = rt_lds[s * RQ + q];
       const float rq[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
@@ -681,14 +722,13 @@ struct Blocking {                       // budgets per lane for a given strategy
   static constexpr int MINW_FIRST = (SP > 40 && SP <= 44) ? 7 : MINW;
   // without the argmin pass: the SP table values plus about 16 working registers
   static constexpr int MINW_VALUES = (SP <= 44) ? 8 : (SP <= 52) ? 7 : (SP <= 60) ? 6 : 5;
-  // with the run shortcut and the summaries compiled in, the records kernel needs one wave fewer
-  // where the registers were already tight
-  // with the run shortcut compiled in: up to 48 strategies the dense path keeps two rows of R
-  // in registers (see PRE in the kernel), beyond it needs a few registers more than without
-  // the shortcut; targets found by compiling every size
-  static constexpr int MINW_RUNS = (SP <= 16) ? 8 : (SP <= 20) ? 7 : (SP <= 24) ? 6 : (SP <= 28) ? 5
-                                   : (SP <= 44) ? 4 : (SP <= 48) ? 3 : 5;
-  static constexpr int MINW_VALUES_RUNS = (SP <= 48) ? MINW_RUNS : (SP <= 52) ? 6 : 5;
+  // with the run shortcut compiled in: the summaries, the exchange, the second look at the
+  // loaded columns and (up to 56 strategies) four quads of R in flight ahead of the fold (see
+  // PRE in the kernel) take a few registers more; targets found by compiling every size.  The
+  // values-only kernels would fit one wave more at some sizes; measured, that is no gain
+  // (S=44: 7 waves 1.80 ms per solve, 5 or 4 waves 1.76).
+  static constexpr int MINW_RUNS = (SP <= 24) ? 8 : (SP <= 36) ? 7 : (SP <= 40) ? 6 : 5;
+  static constexpr int MINW_VALUES_RUNS = MINW_RUNS;
 };
 
 template <int SP>
