@@ -237,7 +237,8 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
   const int RS = (SP + 2 + 3) / 4 * 4;
   TRY(c->d_Rt.reserve(sizeof(float) * (size_t)sumL * S * RS));
   TRY(c->d_C.reserve(sizeof(float) * slab * (keep ? (size_t)sumL : (size_t)2 * B)));
-  const bool runs = (flags & GBMW_FLAG_DENSE_ARITHMETIC) == 0;
+  // the run shortcut and its summaries exist for the register-blocked kernels (S <= 64)
+  const bool runs = (flags & GBMW_FLAG_DENSE_ARITHMETIC) == 0 && gbmw::layer0_in_registers(S);
   if (runs) TRY(c->d_sum.reserve(sizeof(float) * ((size_t)S * (EP / 64)) * (keep ? (size_t)sumL : (size_t)2 * B)));
   if (!lazy) TRY(c->d_A.reserve(slab * (size_t)sumL));
   TRY(c->d_best.reserve(sizeof(float) * (size_t)B * EP));
@@ -280,6 +281,7 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
   t.Cbuf = (float*)c->d_C.p; t.A = lazy ? nullptr : (uint8_t*)c->d_A.p;
   t.best = (float*)c->d_best.p; t.best_s = (uint8_t*)c->d_best_s.p;
   t.status = (int*)c->d_status.p;
+  t.prev_full = 0;
 
   c->timed_launches = 0;
   if (timed) {
@@ -316,7 +318,7 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
       const int na = active_in_group(g, l);
       if (na == 0) break;
       if (timed) HIP_TRY_B(hipEventRecord(c->ev_layer[2 * c->timed_launches], sg));
-      gbmw::launch_minplus(t, l, gfirst[g], na, sg);
+      gbmw::launch_minplus(t, l, gfirst[g], na, sg, l > 1 ? active_in_group(g, l - 1) : 0);
       if (timed) {
         HIP_TRY_B(hipEventRecord(c->ev_layer[2 * c->timed_launches + 1], sg));
         ++c->timed_launches;
@@ -525,9 +527,10 @@ gbmw_status gbmw_export_tables(gbmw_ctx* c, int32_t inst, int32_t l0, int32_t l1
   if (st != GBMW_OK) return st;
   for (int l = l0; l < l1; ++l) {
     if (C) {
-      const float* src = keep ? (const float*)c->d_C.p + (size_t)(row0 + l) * slab
-                              : (const float*)c->d_C.p + ((size_t)(l & 1) * c->B + inst) * slab;
-      gbmw::launch_export_f32(src, (float*)c->d_stage.p, 1, c->S, c->E, c->EP, c->stream);
+      const size_t tab = keep ? (size_t)(row0 + l) : (size_t)(l & 1) * c->B + inst;   // as c_table / sum_table
+      const float* src = (const float*)c->d_C.p + tab * slab;
+      const float* sum = c->t.Tsum ? c->t.Tsum + tab * (S * (c->EP >> 6)) : nullptr;
+      gbmw::launch_export_c(c->t, src, sum, c->t.M + (size_t)(row0 + l) * S, (float*)c->d_stage.p, c->stream);
       HIP_TRY(hipGetLastError());
       HIP_TRY(hipMemcpyAsync(C + (size_t)(l - l0) * rows * S, c->d_stage.p, rows * S * sizeof(float),
                              hipMemcpyDeviceToHost, c->stream));

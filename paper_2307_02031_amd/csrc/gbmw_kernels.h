@@ -23,12 +23,12 @@ struct Tables {
   int B, S, SP, RS, E, EP;
   int keep_all;        // 1: Call[row][S][EP] for every layer row; 0: rolling pair
   int final_from;      // the final reduce fills best / best_s for e >= final_from only
-  int runs;            // 1, 2: a wave whose 64 budgets all have the same input column (the tables are
+  int prev_full;       // set per launch: the input tables have every cell written (see runs)
+  int runs;            // != 0: a wave whose 64 budgets all have the same input column (the tables are
                        // step functions of the budget) computes that column once, one output
-                       // strategy per lane; 0: every lane computes its own cell.  2: split launches
-                       // write summaries as well (needed where a later, larger launch may extend a
-                       // table that a split launch produced: the partition search; inside one solve
-                       // the launches only shrink, and a split launch is followed by split launches)
+                       // strategy per lane, and leaves its cells of the fp32 table unwritten: the
+                       // summaries say what they hold (see Tsum and table_cell); 0: every lane
+                       // computes and writes its own cell, and there are no summaries
   const int* L;        // [B]   device
   const int* off;      // [B]   device, first row of each instance
   const int* perm;     // [B]   device, instances ordered by L descending
@@ -40,26 +40,47 @@ struct Tables {
                        // walkers recompute the one they need from the kept tables
   float* Tsum;         // per table (indexed like Cbuf) [S][EP/64]: for every strategy and every group
                        // of 64 budgets e' of the layer's min-plus product, the value T + c if it is the
-                       // same for all 64 (those inside the table), NaN otherwise; written by the layer's
-                       // launch and read by the next one when runs != 0; null when runs == 0
+                       // same for all 64 (those inside the table), NaN otherwise; written by every
+                       // launch when runs != 0; null when runs == 0.  Where the word is a number the
+                       // table's cells of that group (at e = e' + M) may be unwritten; where it is
+                       // NaN they are written
   float* best;         // [B][EP]
   uint8_t* best_s;     // [B][EP]
   int* status;         // device word; bit 0: bad c, bit 1: bad M, bit 2: bad R
 };
 
 #if defined(__HIPCC__)
+constexpr int kNaNBits = 0x7fc00000;
+__device__ __forceinline__ bool is_nan_bits(int b) { return (b & 0x7fffffff) > 0x7f800000; }
+
+// C(l, e, s) of the layer whose table starts at Ctab ([S][EP]), whose summaries start at Tsum_tab
+// ([S][EP/64], unused when runs == 0) and whose M row is Mrow: +inf below M(l, s) (a negative M, or
+// one beyond the budget axis, leaves no feasible budget), else the summary of the group that
+// e - M falls in if it is a number, else the table's cell.
+__device__ __forceinline__ float table_cell(const Tables& t, const float* __restrict__ Ctab,
+                                            const float* __restrict__ Tsum_tab, const int* __restrict__ Mrow,
+                                            int s, int e) {
+  if (t.runs == 0) return Ctab[(size_t)s * t.EP + e];
+  const int m = Mrow[s];
+  if (m < 0 || e < m) return INFINITY;
+  const float w = Tsum_tab[(size_t)s * (t.EP >> 6) + ((e - m) >> 6)];
+  return is_nan_bits(__float_as_int(w)) ? Ctab[(size_t)s * t.EP + e] : w;
+}
+
 // Predecessor strategy of table row `row` (layer l >= 1 of some instance) under strategy s
 // when e units are left for the layers below: the recorded one, or, where records are not
 // kept, recomputed from the kept table of layer l - 1 with the recurrence's own arithmetic
 // ((C + R), lowest index among equals, 0 if every candidate is +inf).
 __device__ __forceinline__ int pred_strategy(const Tables& t, int row, int s, int e) {
   if (t.A) return t.A[((size_t)row * t.S + s) * t.EP + e];
-  const float* __restrict__ Cp = t.Cbuf + (size_t)(row - 1) * t.S * t.EP + e;
+  const float* __restrict__ Cp = t.Cbuf + (size_t)(row - 1) * t.S * t.EP;
+  const float* __restrict__ Tp = t.Tsum ? t.Tsum + (size_t)(row - 1) * t.S * (t.EP >> 6) : nullptr;
+  const int* __restrict__ Mp = t.M + (size_t)(row - 1) * t.S;
   const float* __restrict__ Rr = t.Rt + ((size_t)row * t.S + s) * t.RS;
   float best = INFINITY;
   int a = 0;
   for (int sp = 0; sp < t.S; ++sp) {
-    const float x = Cp[(size_t)sp * t.EP] + Rr[sp];
+    const float x = table_cell(t, Cp, Tp, Mp, sp, e) + Rr[sp];
     if (x < best) { best = x; a = sp; }
   }
   return a;
@@ -70,12 +91,14 @@ __device__ __forceinline__ int pred_strategy(const Tables& t, int row, int s, in
 // and the minimum with its lowest index is found by a butterfly over the wave.
 __device__ __forceinline__ int pred_strategy_wave(const Tables& t, int row, int s, int e, int lane) {
   if (t.A) return t.A[((size_t)row * t.S + s) * t.EP + e];
-  const float* __restrict__ Cp = t.Cbuf + (size_t)(row - 1) * t.S * t.EP + e;
+  const float* __restrict__ Cp = t.Cbuf + (size_t)(row - 1) * t.S * t.EP;
+  const float* __restrict__ Tp = t.Tsum ? t.Tsum + (size_t)(row - 1) * t.S * (t.EP >> 6) : nullptr;
+  const int* __restrict__ Mp = t.M + (size_t)(row - 1) * t.S;
   const float* __restrict__ Rr = t.Rt + ((size_t)row * t.S + s) * t.RS;
   float best = INFINITY;
   int a = 0x7fffffff;
   for (int sp = lane; sp < t.S; sp += 64) {
-    const float x = Cp[(size_t)sp * t.EP] + Rr[sp];
+    const float x = table_cell(t, Cp, Tp, Mp, sp, e) + Rr[sp];
     if (x < best) { best = x; a = sp; }
   }
   for (int d = 32; d >= 1; d >>= 1) {
@@ -98,7 +121,9 @@ bool layer0_in_registers(int S);
 // One layer l >= 1 for instances perm[first .. first + n_active):
 // min-plus product with argmin, fused with the shift by M(l,s), the + c(l,s)
 // and the +inf prefix.
-void launch_minplus(const Tables& t, int l, int first, int n_active, hipStream_t st);
+// n_prev: instances in the launch that produced this one's input tables (layer l - 1 of the same
+// instances and more), 0 if not known (tables kept from other launches).
+void launch_minplus(const Tables& t, int l, int first, int n_active, hipStream_t st, int n_prev = 0);
 // best(e), best_s(e) for e = final_from .. E over the last layer of instances
 // perm[first .. first + count).
 void launch_final(const Tables& t, int first, int count, hipStream_t st);
@@ -117,7 +142,9 @@ void launch_pipeline_cost(const Tables& t, int n_stage, const int* st_inst, cons
                           float* st_Cns, int n_pipe, const int* st_begin, const int* mb,
                           float* cost, hipStream_t st);
 // [S][EP] -> [E+1][S] for rows [row0, row0+n) of C (fp32; base pointer given) or A (bytes).
-void launch_export_f32(const float* src, float* dst, int n, int S, int E, int EP, hipStream_t st);
+// C(l, ., .) of one layer as [E+1][S]; Ctab / Tsum_tab / Mrow as for table_cell.
+void launch_export_c(const Tables& t, const float* Ctab, const float* Tsum_tab, const int* Mrow, float* dst,
+                     hipStream_t st);
 void launch_export_u8(const uint8_t* src, uint8_t* dst, int n, int S, int E, int EP, hipStream_t st);
 // The argmin records of one table row, [S][EP] bytes, recomputed from the kept tables.
 void launch_argmin_row(const Tables& t, int row, uint8_t* dst, hipStream_t st);

@@ -28,8 +28,6 @@ __device__ __forceinline__ float* sum_table(const Tables& t, int inst, int row, 
                     : t.Tsum + ((size_t)(l & 1) * t.B + inst) * slab;
 }
 
-constexpr int kNaNBits = 0x7fc00000;
-__device__ __forceinline__ bool is_nan_bits(int b) { return (b & 0x7fffffff) > 0x7f800000; }
 
 __device__ __forceinline__ float* c_table(const Tables& t, int inst, int row, int l) {
   const size_t slab = (size_t)t.S * t.EP;
@@ -113,6 +111,8 @@ __global__ __launch_bounds__(256) void k_init_layer0(Tables t, int first) {
   v.z = (m >= 0 && e + 2 >= m && e + 2 <= t.E) ? cs : INFINITY;
   v.w = (m >= 0 && e + 3 >= m && e + 3 <= t.E) ? cs : INFINITY;
   *reinterpret_cast<float4*>(C0 + (size_t)s * t.EP + e) = v;
+  // T + c of layer 0 is c(0, s) at every budget: one summary word per group of 64
+  if (t.runs != 0 && (e & 63) == 0 && e <= t.E) sum_table(t, inst, row, 0)[(size_t)s * (t.EP >> 6) + (e >> 6)] = cs;
 }
 
 void launch_init_layer0(const Tables& t, int first, int count, hipStream_t st) {
@@ -160,16 +160,17 @@ __device__ __forceinline__ float fmin3(float a, float b, float c) {
 // computed once, with the lanes over the output strategies instead (colv: lane s' holds
 // column[s'], +inf beyond the last strategy): lane j forms
 // min_s' (column[s'] + R[s'][s_begin + j]) with the lowest minimising s' (strict compare in index
-// order), adds c, and the results go out to the 64 budgets strategy by strategy.  Same operands
-// and operations per cell as the dense path, hence the same bits.
+// order) and adds c.  Same operands and operations per cell as the dense path, hence the same
+// bits.  The value goes into the layer's summary word of that group and strategy and nowhere
+// else: the 64 cells of the fp32 table stay unwritten, every reader takes the word where it is
+// a number (table_cell).  Only the argmin records go out to the 64 budgets.
 template <int SP>
 __device__ __forceinline__ void uniform_min(const float colv, const float4* rt_lds, int srow, int& outv,
-                                            int& a, int& m_own) {
+                                            int& a) {
   constexpr int RS = (SP + 2 + 3) / 4 * 4;
   constexpr int RQ = RS / 4;
   float best = INFINITY, cs = 0.0f;
   a = 0;
-  m_own = 0;
   int roff = srow * RQ;
 #pragma unroll
   for (int q = 0; q < RQ; ++q) {
@@ -188,7 +189,7 @@ __device__ __forceinline__ void uniform_min(const float colv, const float4* rt_l
         if (x < best) { best = x; a = i; }
       }
     }
-    if (4 * q == SP) { cs = rq[0]; m_own = __float_as_int(rq[1]); }
+    if (4 * q == SP) cs = rq[0];
   }
   outv = __float_as_int(best + cs);
 }
@@ -199,43 +200,32 @@ __device__ __forceinline__ void uniform_tile(const float colv, const float4* rt_
                                              uint8_t* __restrict__ An, float* __restrict__ sum_cur, int E,
                                              int EP) {
   const int srow = (s_begin + lane < s_end) ? s_begin + lane : s_begin;   // idle lanes redo a valid row
-  int outv, a, m_own;
-  uniform_min<SP>(colv, rt_lds, srow, outv, a, m_own);
+  int outv, a;
+  uniform_min<SP>(colv, rt_lds, srow, outv, a);
   // the layer's own summary: every strategy's 64 cells are equal
   if (s_begin + lane < s_end) sum_cur[(size_t)(s_begin + lane) * (EP >> 6) + (wbase >> 6)] = __int_as_float(outv);
-  for (int s = s_begin; s < s_end; ++s) {
-    const int j = s - s_begin;
-    const unsigned v = (unsigned)__builtin_amdgcn_readlane(outv, j);
-    const int m_raw = __builtin_amdgcn_readlane(m_own, j);
-    const int m = (m_raw < 0 || m_raw > E + 1) ? E + 1 : m_raw;
-    float* Cs = Cn + (size_t)s * EP;
-    const __amdgpu_buffer_rsrc_t bc = __builtin_amdgcn_make_buffer_rsrc(Cs, 0, (E + 1) * 4, kBufWord3);
-    const __amdgpu_buffer_rsrc_t binf = __builtin_amdgcn_make_buffer_rsrc(Cs, 0, m * 4, kBufWord3);
-    if (ARG) {
-      const int ar = __builtin_amdgcn_readlane(a, j);
+  // the summary word stands for the 64 cells: only the records are written out
+  if (ARG) {
+    for (int s = s_begin; s < s_end; ++s) {
+      const int ar = __builtin_amdgcn_readlane(a, s - s_begin);
       const __amdgpu_buffer_rsrc_t ba = __builtin_amdgcn_make_buffer_rsrc(An + (size_t)s * EP, 0, EP, kBufWord3);
       __builtin_amdgcn_raw_buffer_store_b8((unsigned char)ar, ba, e0, 0, kStreaming);
     }
-    __builtin_amdgcn_raw_buffer_store_b32(v, bc, (e0 + m) * 4, 0, 0);
-    if (wbase < m) __builtin_amdgcn_raw_buffer_store_b32(0x7f800000u, binf, e0 * 4, 0, 0);
   }
 }
 
 // The same for a whole workgroup whose four waves (256 budgets from `base`) all carry that one
-// column: the waves divide the output strategies instead of the budgets, and every store
-// covers all 256 budgets of its strategy: lane i writes budgets base + 4 i .. 4 i + 3 with one
-// 128-bit store (range-checked per dword, so the end of the table and the +inf prefix cut it
-// where they fall), the records as one dword of four equal bytes.  A quarter of the stores
-// and of the bookkeeping per cell.
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+// column: the waves divide the output strategies instead of the budgets; each writes the four
+// summary words of its strategies and, with records, covers all 256 budgets of a strategy with
+// one store (lane i: one dword of four equal bytes for budgets base + 4 i .. 4 i + 3).
 template <int SP, bool ARG>
 __device__ __forceinline__ void wide_tile(const float colv, const float4* rt_lds, int s_begin, int s_end,
                                           int lane, int base, float* __restrict__ Cn,
                                           uint8_t* __restrict__ An, float* __restrict__ sum_cur, int E,
                                           int EP) {
   const int srow = (s_begin + lane < s_end) ? s_begin + lane : s_begin;
-  int outv, a, m_own;
-  uniform_min<SP>(colv, rt_lds, srow, outv, a, m_own);
+  int outv, a;
+  uniform_min<SP>(colv, rt_lds, srow, outv, a);
   if (s_begin + lane < s_end) {
     float* sp_ = sum_cur + (size_t)(s_begin + lane) * (EP >> 6) + (base >> 6);
     const int last_group = E >> 6;
@@ -243,24 +233,11 @@ __device__ __forceinline__ void wide_tile(const float colv, const float4* rt_lds
     for (int k = 0; k < 4; ++k)
       if ((base >> 6) + k <= last_group) sp_[k] = __int_as_float(outv);
   }
-  for (int s = s_begin; s < s_end; ++s) {
-    const int j = s - s_begin;
-    const unsigned v = (unsigned)__builtin_amdgcn_readlane(outv, j);
-    const int m_raw = __builtin_amdgcn_readlane(m_own, j);
-    const int m = (m_raw < 0 || m_raw > E + 1) ? E + 1 : m_raw;
-    float* Cs = Cn + (size_t)s * EP;
-    const __amdgpu_buffer_rsrc_t bc = __builtin_amdgcn_make_buffer_rsrc(Cs, 0, (E + 1) * 4, kBufWord3);
-    const __amdgpu_buffer_rsrc_t binf = __builtin_amdgcn_make_buffer_rsrc(Cs, 0, m * 4, kBufWord3);
-    if (ARG) {
-      const unsigned ar = (unsigned)__builtin_amdgcn_readlane(a, j);
+  if (ARG) {
+    for (int s = s_begin; s < s_end; ++s) {
+      const unsigned ar = (unsigned)__builtin_amdgcn_readlane(a, s - s_begin);
       const __amdgpu_buffer_rsrc_t ba = __builtin_amdgcn_make_buffer_rsrc(An + (size_t)s * EP, 0, EP, kBufWord3);
       __builtin_amdgcn_raw_buffer_store_b32(ar * 0x01010101u, ba, base + 4 * lane, 0, kStreaming);
-    }
-    const u32x4 vv = {v, v, v, v};
-    __builtin_amdgcn_raw_buffer_store_b128(vv, bc, (base + m + 4 * lane) * 4, 0, 0);
-    if (base < m) {
-      const u32x4 inf4 = {0x7f800000u, 0x7f800000u, 0x7f800000u, 0x7f800000u};
-      __builtin_amdgcn_raw_buffer_store_b128(inf4, binf, (base + 4 * lane) * 4, 0, 0);
     }
   }
 }
@@ -361,9 +338,12 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
     if (rt_lane && !FIRST) {
       const int m = (rt_m < 0 || rt_m > E + 1) ? E + 1 : rt_m;
       const int e_last = wbase + n_in - 1;
-      if (wbase >= m) {                                  // else: decided below without the summaries
+      if (e_last >= m) {                                 // else: +inf throughout
+        // the words of the (at most two) groups that this wave's budgets fall in; the run test
+        // is decided without them where the column starts inside the wave (wbase < m), but the
+        // dense path wants them there too
         const float* __restrict__ sp_ = sum_table(t, inst, row - 1, l - 1) + (size_t)lane * (EP >> 6);
-        rt_b1 = __float_as_int(sp_[(wbase - m) >> 6]);
+        rt_b1 = __float_as_int(sp_[(wbase > m ? wbase - m : 0) >> 6]);
         rt_b2 = __float_as_int(sp_[(e_last - m) >> 6]);
       }
     }
@@ -390,7 +370,7 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
   // is constant if both summaries are the same number.  If every column is, the wave takes
   // uniform_tile and never loads the table; otherwise it loads it and computes every cell.
   // The layer-1 launch tests layer 0's closed form at the two ends (the columns are monotone).
-  const bool want_sum = RUNS ? true : (SPLIT ? t.runs == 2 : false);
+  const bool want_sum = RUNS ? true : (SPLIT ? t.runs != 0 : false);
   float* __restrict__ sum_cur = want_sum ? sum_table(t, inst, row, l) : nullptr;
   if (RUNS) {
     static_assert(K == 1 && SP <= 64, "one budget per lane, one lane per strategy");
@@ -446,6 +426,10 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
   // inside the allocation; rows in (E, EP) are padding whose results are
   // never stored into the table proper.
   float cp[K][SP];
+  // the table values are formed here, after the run test, not before it (they would stay live
+  // across the run paths otherwise)
+  int e0d = e0;
+  asm volatile("" : "+v"(e0d));
   if (FIRST) {
     // l == 1: layer 0 is a closed form, C(0, e, s') = e >= M(0, s') ? c(0, s') : +inf,
     // built here instead of being written to and read back from HBM.
@@ -458,8 +442,77 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
       const int mv = col ? m0[sp] : 0;
 #pragma unroll
       for (int j = 0; j < K; ++j) {
-        const int e = e0 + 64 * j;
+        const int e = e0d + 64 * j;
         cp[j][sp] = (mv >= 0 && e >= mv && e <= E) ? cv : INFINITY;
+      }
+    }
+  } else if (RUNS) {
+    // With summaries the previous layer's cells are written only where their group's word is
+    // NaN (see table_cell); below M(l-1, s') the cell is +inf.  The words of this wave's groups
+    // are already here, in the lane of their column (the run test asked for them): the cell is
+    // loaded whatever it holds, and the word wins where it is a number.
+    static_assert(K == 1, "one budget per lane");
+#pragma unroll
+    for (int sp = 0; sp < SP; ++sp) {
+      float c = INFINITY;
+      if (sp < SP - 3 || sp < S) c = __builtin_nontemporal_load(&Cp[(size_t)sp * EP + e0d]);
+      cp[0][sp] = c;
+    }
+#pragma unroll
+    for (int sp = 0; sp < SP; ++sp) {
+      if (sp < SP - 3 || sp < S) {
+        const int m_raw = __builtin_amdgcn_readlane(rt_m, sp);
+        const int m = (m_raw < 0 || m_raw > E + 1) ? E + 1 : m_raw;
+        const int b1 = __builtin_amdgcn_readlane(rt_b1, sp), b2 = __builtin_amdgcn_readlane(rt_b2, sp);
+        const int g1 = (wbase > m ? wbase - m : 0) >> 6;
+        const int idx = e0d - m;
+        const int w = ((idx >> 6) == g1) ? b1 : b2;
+        cp[0][sp] = idx < 0 ? INFINITY : is_nan_bits(w) ? cp[0][sp] : __int_as_float(w);
+      }
+    }
+  } else if (SPLIT && t.runs != 0 && !t.prev_full) {
+    // A split launch whose input came from an unsplit one with the run shortcut, or from an
+    // unknown launch (the partition search's kept tables): the same rule, but no words at
+    // hand.  (A split launch that follows a split launch finds every cell written and takes
+    // the plain loads below.)
+    static_assert(K == 1, "one budget per lane");
+    const float* __restrict__ Tp = sum_table(t, inst, row - 1, l - 1);
+    // lane s' holds M(l-1, s')
+    const int mprev = (lane < S) ? t.M[(size_t)(row - 1) * S + lane] : 0;
+    // First the summaries of all columns, into the registers of the table values.  Then one
+    // more load per column from an address chosen by what came: the cell where the word is
+    // NaN, the word once more where it is a number (a cache hit).  No branch, so the loads of
+    // the second round go out back to back, and never two values per column in registers
+    // (asking for word and cell of every column at once takes 2 SP registers; a branch around
+    // each cell's load makes every one of them a round trip of its own).
+#pragma unroll
+    for (int sp = 0; sp < SP; ++sp) {
+      float w = INFINITY;
+      if (sp < SP - 3 || sp < S) {
+        const int m_raw = __builtin_amdgcn_readlane(mprev, sp);
+        const int m = (m_raw < 0 || m_raw > E + 1) ? E + 1 : m_raw;
+        const int idx = e0d - m;
+        w = Tp[(size_t)sp * (EP >> 6) + ((idx > 0 ? idx : 0) >> 6)];
+      }
+      cp[0][sp] = w;
+    }
+#pragma unroll
+    for (int sp = 0; sp < SP; ++sp) {
+      if (sp < SP - 3 || sp < S) {
+        const int m_raw = __builtin_amdgcn_readlane(mprev, sp);
+        const int m = (m_raw < 0 || m_raw > E + 1) ? E + 1 : m_raw;
+        const int idx = e0d - m;
+        const float* again = &Tp[(size_t)sp * (EP >> 6) + ((idx > 0 ? idx : 0) >> 6)];
+        const float* cell = &Cp[(size_t)sp * EP + e0d];
+        cp[0][sp] = *(is_nan_bits(__float_as_int(cp[0][sp])) ? cell : again);
+      }
+    }
+#pragma unroll
+    for (int sp = 0; sp < SP; ++sp) {
+      if (sp < SP - 3 || sp < S) {
+        const int m_raw = __builtin_amdgcn_readlane(mprev, sp);
+        const int m = (m_raw < 0 || m_raw > E + 1) ? E + 1 : m_raw;
+        cp[0][sp] = e0d < m ? INFINITY : cp[0][sp];
       }
     }
   } else {
@@ -470,7 +523,7 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
         {
         // a large launch reads every table value exactly once: streaming loads leave the
         // caches to the stores; a split launch is small enough to find its table in cache
-        const float* src = &Cp[(size_t)sp * EP + e0 + 64 * j];
+        const float* src = &Cp[(size_t)sp * EP + e0d + 64 * j];
         cp[j][sp] = !(sp < SP - 3 || sp < S) ? INFINITY : SPLIT ? *src : __builtin_nontemporal_load(src);
       }
     }
@@ -509,6 +562,7 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
 #pragma unroll
       for (int q = 0; q < PD; ++q) rowq[q] = rt_lds[s_begin * RQ + (q < RQ ? q : RQ - 1)];
     }
+#pragma unroll 1
     for (int s = s_begin; s < s_end; ++s) {
       float acc = INFINITY, cs = 0.0f;
       int m_raw = 0;
@@ -541,8 +595,8 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
       const __amdgpu_buffer_rsrc_t binf = __builtin_amdgcn_make_buffer_rsrc(Cs, 0, m * 4, kBufWord3);
       const int outb = __float_as_int(acc + cs);
       __builtin_amdgcn_raw_buffer_store_b32((unsigned)outb, bc, (e0 + m) * 4, 0, 0);
-      if (wbase < m)                                       // wave-uniform: some lane is below M
-        __builtin_amdgcn_raw_buffer_store_b32(0x7f800000u, binf, e0 * 4, 0, 0);
+      if (!RUNS && wbase < m)                              // wave-uniform: some lane is below M (with
+        __builtin_amdgcn_raw_buffer_store_b32(0x7f800000u, binf, e0 * 4, 0, 0);   // the run shortcut the readers know)
       if (want_sum) {
         // T + c is non-increasing along the budgets: all equal exactly when the ends are
         const int first = __builtin_amdgcn_readfirstlane(outb), last = __builtin_amdgcn_readlane(outb, n_in - 1);
@@ -560,6 +614,7 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
 #pragma unroll
     for (int q = 0; q < PD; ++q) rowq[q] = rt_lds[s_begin * RQ + (q < RQ ? q : RQ - 1)];
   }
+#pragma unroll 1
   for (int s = s_begin; s < s_end; ++s) {
     const int s_next = (s + 1 < s_end) ? s + 1 : s;        // the last row is fetched once more, unused
     // ---- value pass, streaming: the R row is consumed quad by quad as it arrives from LDS,
@@ -660,8 +715,8 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
       __builtin_amdgcn_raw_buffer_store_b8((unsigned char)arg, ba, e, 0, SPLIT ? 0 : kStreaming);
       const int outb = __float_as_int(T + cs);
       __builtin_amdgcn_raw_buffer_store_b32((unsigned)outb, bc, (e + m) * 4, 0, 0);
-      if (wbase + 64 * j < m)                            // wave-uniform: some lane is below M
-        __builtin_amdgcn_raw_buffer_store_b32(0x7f800000u, binf, e * 4, 0, 0);
+      if (!RUNS && wbase + 64 * j < m)                   // wave-uniform: some lane is below M (with
+        __builtin_amdgcn_raw_buffer_store_b32(0x7f800000u, binf, e * 4, 0, 0);    // the run shortcut the readers know)
       if (want_sum) {
         const int first = __builtin_amdgcn_readfirstlane(outb), last = __builtin_amdgcn_readlane(outb, n_in - 1);
         sumv = (lane == s - s_begin) ? (first == last ? first : kNaNBits) : sumv;
@@ -728,16 +783,20 @@ struct Blocking {                       // budgets per lane for a given strategy
   // values-only kernels would fit one wave more at some sizes; measured, that is no gain
   // (S=44: 7 waves 1.80 ms per solve, 5 or 4 waves 1.76).
   static constexpr int MINW_RUNS = (SP <= 24) ? 8 : (SP <= 36) ? 7 : (SP <= 40) ? 6 : 5;
-  static constexpr int MINW_VALUES_RUNS = MINW_RUNS;
+  static constexpr int MINW_VALUES_RUNS = (SP <= 24) ? 8 : (SP <= 28) ? 7 : (SP <= 32) ? 6 : (SP <= 40) ? 5
+                                          : (SP <= 52) ? 4 : (SP <= 56) ? 3 : 5;
 };
 
 template <int SP>
-static void launch_minplus_sp(const Tables& t, int l, int first, int n_active, hipStream_t st) {
+static void launch_minplus_sp(const Tables& t_in, int l, int first, int n_active, int n_prev, hipStream_t st) {
   constexpr int K = Blocking<SP>::K, NW = Blocking<SP>::NW, CH = Blocking<SP>::CH,
                 MINW = Blocking<SP>::MINW;
+  Tables t = t_in;
   int tiles = (t.E + 1 + 64 * K * NW - 1) / (64 * K * NW);
   // fewer than two and a half workgroups per compute unit: split the strategies over the waves
   const int split = ((long long)tiles * n_active < 640) ? 1 : 0;
+  // did the launch that produced this one's input split too (and so write every cell)?
+  t.prev_full = (n_prev > 0 && (long long)tiles * n_prev < 640) ? 1 : 0;
   if (split) tiles = (t.E + 1 + 64 * K - 1) / (64 * K);
   constexpr int RS = (SP + 2 + 3) / 4 * 4;
   const dim3 grid((unsigned)tiles * n_active), block(64 * NW);
@@ -775,10 +834,10 @@ static void launch_minplus_sp(const Tables& t, int l, int first, int n_active, h
 #undef GBMW_LAUNCH
 }
 
-void launch_minplus(const Tables& t, int l, int first, int n_active, hipStream_t st) {
+void launch_minplus(const Tables& t, int l, int first, int n_active, hipStream_t st, int n_prev) {
   if (n_active <= 0) return;
   switch (t.SP) {
-#define GBMW_CASE(N) case N: launch_minplus_sp<N>(t, l, first, n_active, st); return;
+#define GBMW_CASE(N) case N: launch_minplus_sp<N>(t, l, first, n_active, n_prev, st); return;
     GBMW_CASE(4) GBMW_CASE(8) GBMW_CASE(12) GBMW_CASE(16) GBMW_CASE(20) GBMW_CASE(24)
     GBMW_CASE(28) GBMW_CASE(32) GBMW_CASE(36) GBMW_CASE(40) GBMW_CASE(44) GBMW_CASE(48)
     GBMW_CASE(52) GBMW_CASE(56) GBMW_CASE(60) GBMW_CASE(64)
@@ -808,6 +867,35 @@ __global__ __launch_bounds__(256) void k_final(Tables t, int first) {
   const float* __restrict__ C = c_table(t, inst, t.off[inst] + l, l);
   float b = INFINITY;
   int a = 0;
+  if (t.runs != 0) {
+    // the summaries stand for the cells of their groups where they are numbers (table_cell)
+    const float* __restrict__ Ts = sum_table(t, inst, t.off[inst] + l, l);
+    const int* __restrict__ Ml = t.M + (size_t)(t.off[inst] + l) * t.S;
+    int s = 0;
+    for (; s + 8 <= t.S; s += 8) {
+      float x[8], w[8];
+      int idx[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int m = Ml[s + i];
+        idx[i] = (m < 0) ? -1 : e - m;
+        w[i] = Ts[(size_t)(s + i) * (t.EP >> 6) + ((idx[i] > 0 ? idx[i] : 0) >> 6)];
+        x[i] = C[(size_t)(s + i) * t.EP + e];
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float v = idx[i] < 0 ? INFINITY : is_nan_bits(__float_as_int(w[i])) ? x[i] : w[i];
+        if (v < b) { b = v; a = s + i; }
+      }
+    }
+    for (; s < t.S; ++s) {
+      const float v = table_cell(t, C, Ts, Ml, s, e);
+      if (v < b) { b = v; a = s; }
+    }
+    t.best[(size_t)inst * t.EP + e] = b;
+    t.best_s[(size_t)inst * t.EP + e] = (uint8_t)a;
+    return;
+  }
   // eight loads in flight, then the compares in strategy order
   int s = 0;
   for (; s + 8 <= t.S; s += 8) {
@@ -1086,9 +1174,16 @@ void launch_argmin_row(const Tables& t, int row, uint8_t* dst, hipStream_t st) {
   hipLaunchKernelGGL(k_argmin_row, dim3(t.EP / 256, t.S), dim3(256), 0, st, t, row, dst);
 }
 
-void launch_export_f32(const float* src, float* dst, int n, int S, int E, int EP, hipStream_t st) {
-  hipLaunchKernelGGL(k_export<float>, dim3((E + 64) / 64, (S + 63) / 64, n), dim3(256), 0, st, src,
-                     dst, S, E, EP);
+__global__ __launch_bounds__(256) void k_export_c(Tables t, const float* __restrict__ Ctab,
+                                                  const float* __restrict__ Tsum_tab, const int* __restrict__ Mrow,
+                                                  float* __restrict__ dst) {
+  const int e = blockIdx.x * 256 + threadIdx.x, s = blockIdx.y;
+  if (e > t.E) return;
+  dst[(size_t)e * t.S + s] = table_cell(t, Ctab, Tsum_tab, Mrow, s, e);
+}
+void launch_export_c(const Tables& t, const float* Ctab, const float* Tsum_tab, const int* Mrow, float* dst,
+                     hipStream_t st) {
+  hipLaunchKernelGGL(k_export_c, dim3((t.E + 256) / 256, t.S), dim3(256), 0, st, t, Ctab, Tsum_tab, Mrow, dst);
 }
 void launch_export_u8(const uint8_t* src, uint8_t* dst, int n, int S, int E, int EP,
                       hipStream_t st) {

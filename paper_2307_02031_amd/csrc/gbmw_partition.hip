@@ -623,7 +623,7 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
   // with argmin records: a rolling pair of fp32 layer tables per slot and one byte per cell of
   // every layer; without: the fp32 tables of all layers
   const bool lazy = (flags & GBMW_FLAG_LAZY_ARGMIN) != 0;
-  const bool runs = (flags & GBMW_FLAG_DENSE_ARITHMETIC) == 0;
+  const bool runs = (flags & GBMW_FLAG_DENSE_ARITHMETIC) == 0 && gbmw::layer0_in_registers(S);
   if (runs) TRY(c->d_sum.reserve(sizeof(float) * ((size_t)S * (EP / 64)) * (lazy ? rows : (size_t)2 * B)));
   if (lazy) {
     TRY(c->d_C.reserve(sizeof(float) * slab * rows));
@@ -646,6 +646,7 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
   t.Cbuf = (float*)c->d_C.p; t.A = lazy ? nullptr : (uint8_t*)c->d_A.p;
   t.best = (float*)c->d_best.p; t.best_s = (uint8_t*)c->d_best_s.p;
   t.status = (int*)c->d_status.p;
+  t.prev_full = 0;
 
   HIP_TRY_B(hipEventCreate(&ev0));
   HIP_TRY_B(hipEventCreate(&ev1));
