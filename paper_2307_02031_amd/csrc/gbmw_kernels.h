@@ -122,8 +122,11 @@ bool layer0_in_registers(int S);
 // min-plus product with argmin, fused with the shift by M(l,s), the + c(l,s)
 // and the +inf prefix.
 // n_prev: instances in the launch that produced this one's input tables (layer l - 1 of the same
-// instances and more), 0 if not known (tables kept from other launches).
+// instances and more); 0 if not known (tables kept from other launches); < 0: whatever produced
+// them wrote every cell (split launches: launch_is_split).
 void launch_minplus(const Tables& t, int l, int first, int n_active, hipStream_t st, int n_prev = 0);
+// Does a launch over n_active instances take the split shape (which writes every table cell)?
+bool launch_is_split(const Tables& t, int n_active);
 // best(e), best_s(e) for e = final_from .. E over the last layer of instances
 // perm[first .. first + count).
 void launch_final(const Tables& t, int first, int count, hipStream_t st);

@@ -796,7 +796,7 @@ static void launch_minplus_sp(const Tables& t_in, int l, int first, int n_active
   // fewer than two and a half workgroups per compute unit: split the strategies over the waves
   const int split = ((long long)tiles * n_active < 640) ? 1 : 0;
   // did the launch that produced this one's input split too (and so write every cell)?
-  t.prev_full = (n_prev > 0 && (long long)tiles * n_prev < 640) ? 1 : 0;
+  t.prev_full = (n_prev < 0 || (n_prev > 0 && (long long)tiles * n_prev < 640)) ? 1 : 0;
   if (split) tiles = (t.E + 1 + 64 * K - 1) / (64 * K);
   constexpr int RS = (SP + 2 + 3) / 4 * 4;
   const dim3 grid((unsigned)tiles * n_active), block(64 * NW);
@@ -850,6 +850,10 @@ void launch_minplus(const Tables& t, int l, int first, int n_active, hipStream_t
 }
 
 bool layer0_in_registers(int S) { return S <= 64; }
+
+bool launch_is_split(const Tables& t, int n_active) {
+  return t.S <= 64 && (long long)((t.E + 256) / 256) * n_active < 640;
+}
 
 const char* minplus_variant(int S) {
   return S <= 64 ? "register-blocked, LDS-staged R tile, prefix-min value pass + on-demand argmin rescan"

@@ -693,6 +693,7 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
   // per slot: layers it holds, first model layer, and which of its fp32 layer tables are in
   // memory (the rolling pair keeps the last two computed; hi = -1: none)
   std::vector<int> slotL(B, 0), slot_first(B, 0), c_hi(B, -1), c_lo(B, -1), mode(B, kSkip);
+  std::vector<char> last_full(B, 0);                 // the slot's newest table has every cell written
   std::vector<int> h_src, h_msrc, h_dst, h_touched, h_perm, h_flags(3 * (size_t)n);
   int rounds = 0, stage_solves = 0;
   long long cell_updates = 0;
@@ -730,6 +731,7 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
         c_hi[b] = L - 1;
       } else {
         final_only.push_back(b);
+        last_full[b] = 0;                            // its newest table is now an older one
       }
     }
     const int nt = (int)h_touched.size();
@@ -784,17 +786,28 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
         for (size_t x = 0; x < append.size();) {
           size_t y = x;
           while (y < append.size() && slotL[append[y]] == slotL[append[x]]) ++y;
-          gbmw::launch_minplus(t, slotL[append[x]] - 1, a_first + (int)x, (int)(y - x), sg);
+          // the kept table that the step extends: every cell written if all of these slots got
+          // theirs from a split launch
+          bool all_full = true;
+          for (size_t z = x; z < y; ++z) all_full = all_full && last_full[append[z]];
+          gbmw::launch_minplus(t, slotL[append[x]] - 1, a_first + (int)x, (int)(y - x), sg, all_full ? -1 : 0);
+          const bool now_full = gbmw::launch_is_split(t, (int)(y - x));
+          for (size_t z = x; z < y; ++z) last_full[append[z]] = now_full;
           x = y;
         }
         gbmw::launch_final(t, a_first, (int)h_perm.size() - a_first, sg);
       }
       const int gn = gfirst[g + 1] - gfirst[g];
       const int Lmax_g = gn ? slotL[h_perm[gfirst[g]]] : 0;
+      int n_prev = 0;                                      // a complete solve: layer l - 1 comes from the launch before
       for (int l = 1; l < Lmax_g; ++l) {
         int na = 0;
         while (na < gn && slotL[h_perm[gfirst[g] + na]] > l) ++na;
-        gbmw::launch_minplus(t, l, gfirst[g], na, sg);
+        gbmw::launch_minplus(t, l, gfirst[g], na, sg, n_prev);
+        n_prev = na;
+        // the slots whose last layer this launch produced
+        for (int x = 0; x < na; ++x)
+          if (slotL[h_perm[gfirst[g] + x]] == l + 1) last_full[h_perm[gfirst[g] + x]] = gbmw::launch_is_split(t, na);
       }
       gbmw::launch_final(t, gfirst[g], gn, sg);
       if (g > 0) {
