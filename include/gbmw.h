@@ -74,12 +74,15 @@ enum {
                                   whose 64 consecutive budgets all read the same column of
                                   the previous layer's table (the tables are step functions
                                   of the budget, so most waves do) computes that column's
-                                  cells once, one output strategy per lane, and writes the
-                                  result to all 64 budgets; to recognise such waves without
-                                  reading the table every layer also leaves one word per
-                                  strategy and 64 budgets (1/64 of the fp32 table bytes of
-                                  device memory more).  Identical results either way; the
-                                  flag exists to time the dense arithmetic                */
+                                  cells once, one output strategy per lane.  Every layer
+                                  leaves one word per strategy and 64 budgets (1/64 of the
+                                  fp32 table bytes of device memory more) that holds such a
+                                  group's value: the next layer recognises its runs from
+                                  those words without reading the table, and the group's
+                                  cells are not written inside the library's own tables
+                                  (what gbmw_export_tables and every other call return is
+                                  unaffected).  Identical results either way; the flag
+                                  exists to time the dense arithmetic                     */
 };
 
 #define GBMW_MAX_S 256
