@@ -286,6 +286,39 @@ def test_many_small_instances_in_one_launch(g, E, mode):
     g.gbmw_destroy(ctx)
 
 
+@pytest.mark.parametrize("mode", list(MODES), ids=list(MODES))
+@pytest.mark.parametrize("streams", ["one-stream", "two-groups"])
+def test_launch_shapes_follow_one_another(g, mode, streams):
+    """Six instances of 2..7 layers over 120 row tiles: the layer launches shrink from the unsplit
+    shape (6 x 120 workgroups) to the split one, so that a split launch reads tables that an
+    unsplit launch with the run shortcut left (cells of uniform groups unwritten, the summary
+    words standing for them), later split launches read tables that split launches wrote, and
+    the final reduce, the export and the walkers read both kinds.  Two kinds of inputs: integer
+    costs with coarse memory (long runs, ties) and random ones (few runs).  Every cell of every
+    layer against the oracle."""
+    flags = MODES[mode] | (g.GBMW_FLAG_ONE_STREAM if streams == "one-stream" else 0)
+    S, E = 9, 120 * 256 - 77
+    for kind in (0, 1):
+        st = gi.Stream(4100 + kind)
+        parts = []
+        for i, L in enumerate([7, 2, 5, 3, 6, 4]):
+            if kind == 0:
+                c = st.integers(L * S, 1, 6).astype(np.float32).reshape(L, S)
+                M = (st.integers(L * S, 0, 40) * 97).reshape(L, S)
+                R = st.integers(L * S * S, 0, 3).astype(np.float32).reshape(L, S, S)
+                parts.append(gi.Problem(1, S, E, np.array([L]), c, M, R))
+            else:
+                parts.append(gi.random_instance(4200 + i, L, S, E, M_rng=(0, 5000)))
+        p = gi.stack(parts, f"shapes-{kind}")
+        keep = 0 if flags & 16 else g.GBMW_FLAG_KEEP_ALL_C
+        ctx = solve_gpu(p, flags=flags | keep, device_inputs=bool(kind))
+        best, best_s = g.gbmw_get_best(ctx)
+        for b in range(p.B):
+            check_instance(g, ctx, p, b, full_C=True, q_es=[0, 1, E // 3, E - 1, E], best=best, best_s=best_s,
+                           nthreads=4)
+        g.gbmw_destroy(ctx)
+
+
 @pytest.mark.parametrize("lazy", [False, True], ids=["records", "lazy-argmin"])
 def test_config4_dense_arithmetic(g, lazy):
     """The benchmark's batch with GBMW_FLAG_DENSE_ARITHMETIC (every lane computes its own
