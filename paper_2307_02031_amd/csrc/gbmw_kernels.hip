@@ -464,10 +464,11 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
         const int m_raw = __builtin_amdgcn_readlane(rt_m, sp);
         const int m = (m_raw < 0 || m_raw > E + 1) ? E + 1 : m_raw;
         const int b1 = __builtin_amdgcn_readlane(rt_b1, sp), b2 = __builtin_amdgcn_readlane(rt_b2, sp);
-        const int g1 = (wbase > m ? wbase - m : 0) >> 6;
-        const int idx = e0d - m;
-        const int w = ((idx >> 6) == g1) ? b1 : b2;
-        cp[0][sp] = idx < 0 ? INFINITY : is_nan_bits(w) ? cp[0][sp] : __int_as_float(w);
+        // the first budget of the second group; which word is a number is known per wave
+        const int thr = m + ((((wbase > m ? wbase - m : 0) >> 6) + 1) << 6);
+        const float v1 = is_nan_bits(b1) ? cp[0][sp] : __int_as_float(b1);
+        const float v2 = is_nan_bits(b2) ? cp[0][sp] : __int_as_float(b2);
+        cp[0][sp] = e0d < m ? INFINITY : e0d < thr ? v1 : v2;
       }
     }
   } else if (SPLIT && t.runs != 0 && !t.prev_full) {
