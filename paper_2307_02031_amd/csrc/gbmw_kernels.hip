@@ -371,6 +371,10 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
   // uniform_tile and never loads the table; otherwise it loads it and computes every cell.
   // The layer-1 launch tests layer 0's closed form at the two ends (the columns are monotone).
   const bool want_sum = RUNS ? true : (SPLIT ? t.runs != 0 : false);
+  // A split launch writes every cell, so NaN in all its words is as good as the true words
+  // for every reader; the true ones only help a later unsplit launch to recognise runs, which
+  // happens in the partition search (runs == 2) and never inside one solve (launches shrink).
+  const bool true_sum = RUNS ? true : (SPLIT ? t.runs == 2 : false);
   float* __restrict__ sum_cur = want_sum ? sum_table(t, inst, row, l) : nullptr;
   if (RUNS) {
     static_assert(K == 1 && SP <= 64, "one budget per lane, one lane per strategy");
@@ -598,7 +602,7 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
       __builtin_amdgcn_raw_buffer_store_b32((unsigned)outb, bc, (e0 + m) * 4, 0, 0);
       if (!RUNS && wbase < m)                              // wave-uniform: some lane is below M (with
         __builtin_amdgcn_raw_buffer_store_b32(0x7f800000u, binf, e0 * 4, 0, 0);   // the run shortcut the readers know)
-      if (want_sum) {
+      if (true_sum) {
         // T + c is non-increasing along the budgets: all equal exactly when the ends are
         const int first = __builtin_amdgcn_readfirstlane(outb), last = __builtin_amdgcn_readlane(outb, n_in - 1);
         sumv = (lane == s - s_begin) ? (first == last ? first : kNaNBits) : sumv;
@@ -718,7 +722,7 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
       __builtin_amdgcn_raw_buffer_store_b32((unsigned)outb, bc, (e + m) * 4, 0, 0);
       if (!RUNS && wbase + 64 * j < m)                   // wave-uniform: some lane is below M (with
         __builtin_amdgcn_raw_buffer_store_b32(0x7f800000u, binf, e * 4, 0, 0);    // the run shortcut the readers know)
-      if (want_sum) {
+      if (true_sum) {
         const int first = __builtin_amdgcn_readfirstlane(outb), last = __builtin_amdgcn_readlane(outb, n_in - 1);
         sumv = (lane == s - s_begin) ? (first == last ? first : kNaNBits) : sumv;
       }
