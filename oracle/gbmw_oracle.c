@@ -23,9 +23,9 @@
  * Arithmetic contract: IEEE binary32, round-to-nearest-even, two separately
  * rounded additions per transition in the order (C_prev + R) + c, no fused
  * multiply-add, no reassociation; every min keeps the LOWEST index on ties
- * (an update happens only on strict "<"); infeasible cells are +infinity
- * ("if the forward memory usage exceeds the budget the cost is infinity",
- * Section 4.1.2).  Build with -ffp-contract=off and without -ffast-math.
+ * (an update happens only on strict "<"); a cell whose forward memory
+ * exceeds the budget is infeasible and holds +infinity (Section 4.1.2).
+ * Build with -ffp-contract=off and without -ffast-math.
  *
  * Two forms are given, as the method is exact:
  *   - gbmw_oracle_bruteforce: the plain definition, enumerating all S^L plans;

@@ -26,19 +26,21 @@ def solve_gpu(p: gi.Problem, flags: int = 0, device_inputs: bool = False, ctx=No
 
 
 def check_instance(g, ctx, p: gi.Problem, b: int, full_C: bool, q_es=None, nthreads: int = 16,
-                   best=None, best_s=None):
-    """Everything the library can return for instance b against the oracle."""
-    ref = oracle.solve_problem(p, b, keep_C=True, keep_A=True, nthreads=nthreads)
+                   best=None, best_s=None, with_C: bool = True):
+    """Everything the library can return for instance b against the oracle (with_C=False:
+    everything but the fp32 tables, so that the oracle need not hold them)."""
+    ref = oracle.solve_problem(p, b, keep_C=with_C, keep_A=True, nthreads=nthreads)
     Lb = int(p.L[b])
     if best is None:
         best, best_s = g.gbmw_get_best(ctx)
     pins.assert_same_f32(best[b], ref.best, f"{p.name}[{b}] best")
     assert np.array_equal(best_s[b], ref.best_s), f"{p.name}[{b}] best_s"
-    l0 = 0 if full_C else max(0, Lb - 2)
-    C, _ = g.gbmw_export_tables(ctx, b, l0, Lb, want_C=True, want_A=False)
-    for l in range(l0, Lb):
-        pins.assert_same_f32(C[l - l0], ref.C[l], f"{p.name}[{b}] C layer {l}")
-    del C
+    if with_C:
+        l0 = 0 if full_C else max(0, Lb - 2)
+        C, _ = g.gbmw_export_tables(ctx, b, l0, Lb, want_C=True, want_A=False)
+        for l in range(l0, Lb):
+            pins.assert_same_f32(C[l - l0], ref.C[l], f"{p.name}[{b}] C layer {l}")
+        del C
     _, A = g.gbmw_export_tables(ctx, b, 0, Lb, want_C=False, want_A=True)
     for l in range(Lb):
         if not np.array_equal(A[l], ref.A[l]):
