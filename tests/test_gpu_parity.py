@@ -213,6 +213,43 @@ def test_non_default_stream(g):
     g.gbmw_destroy(ctx)
 
 
+def test_device_inputs_may_be_overwritten_after_the_solve(g):
+    """The caller's device arrays are read by the solve's own enqueued work only: once a
+    waiting call has returned they are overwritten with garbage here, and the walkers, the
+    export (which rebuilds cells from M under the run shortcut), Algorithm 3's loop and the
+    pipeline cost still give the oracle's results, with and without records."""
+    import torch
+    for flags in (0, g.GBMW_FLAG_LAZY_ARGMIN):
+        # 700 row tiles x 2 instances: unsplit launches with the run shortcut; integer costs and
+        # coarse memories, so that most cells are left to their summary words
+        E, S = 700 * 256 - 13, 6
+        st = gi.Stream(9100)
+        parts = []
+        for L in (4, 3):
+            c = st.integers(L * S, 1, 6).astype(np.float32).reshape(L, S)
+            M = (st.integers(L * S, 1, 50) * 640).reshape(L, S)
+            R = st.integers(L * S * S, 0, 3).astype(np.float32).reshape(L, S, S)
+            parts.append(gi.Problem(1, S, E, np.array([L]), c, M, R))
+        p = gi.stack(parts, "overwrite")
+        c = torch.from_numpy(p.c).cuda(); M = torch.from_numpy(p.M).cuda(); R = torch.from_numpy(p.R).cuda()
+        ctx = g.gbmw_dp_solve_batched(p.L, c, M, R, p.S, p.E, flags=flags)
+        g.gbmw_synchronize(ctx)
+        c.fill_(float("nan")); M.fill_(-7); R.fill_(float("nan"))
+        torch.cuda.synchronize()
+        for b in range(p.B):
+            check_instance(g, ctx, p, b, full_C=False, q_es=[0, 640, E // 2, E - 1, E])
+        Of, Ob, Oms = gi.split_memory(p, 4)
+        e_opt, cost, plan, e_all = g.gbmw_select_forward_budget(ctx, Of, Ob, Oms)
+        for b in range(p.B):
+            o, Lb = int(p.offsets[b]), int(p.L[b])
+            ref = oracle.solve_problem(p, b, keep_C=False, keep_A=True, nthreads=8)
+            r = oracle.select_budget(ref, Of[o:o + Lb], Ob[o:o + Lb], Oms[o:o + Lb])
+            assert int(e_opt[b]) == r[0] and pins.bits(cost[b]) == pins.bits(r[1]) and int(e_all[b]) == r[3]
+            if r[0] >= 0 and np.isfinite(r[1]):
+                assert np.array_equal(plan[b, :Lb], r[2])
+        g.gbmw_destroy(ctx)
+
+
 MODES = {"records": 0, "lazy-argmin": 16, "records-dense": 32, "lazy-argmin-dense": 48}
 
 
