@@ -88,11 +88,18 @@ enum {
 #define GBMW_MAX_S 256
 
 /*
- * The problem statement.  L is always a host pointer.  c, M and R are all host
- * pointers (ptr_space == GBMW_PTR_HOST; the library copies them to the device)
- * or all device pointers (GBMW_PTR_DEVICE; used in place, must stay valid and
- * unchanged until the solve has completed on `stream`).  Rows of instance b
- * start at off_b = L[0] + ... + L[b-1]; sumL = L[0] + ... + L[B-1].
+ * The problem statement.  L is always a host pointer and is read before the call
+ * returns.  c, M and R are all host pointers (ptr_space == GBMW_PTR_HOST) or all
+ * device pointers (GBMW_PTR_DEVICE).  Lifetime of the three arrays: the solve
+ * reads them from work enqueued on `stream` (host arrays through asynchronous
+ * copies, device arrays by its first kernel) and nothing reads them after that
+ * work has run; they must stay valid and unchanged until a call that waits for
+ * the solve has returned (gbmw_synchronize or any of the result calls), or until
+ * the caller has itself waited for `stream`, and may be freed or overwritten
+ * then.  Every later call on the context (gbmw_backtrack, gbmw_export_tables,
+ * gbmw_select_forward_budget, gbmw_pipeline_cost) works from copies the context
+ * owns.  Rows of instance b start at off_b = L[0] + ... + L[b-1];
+ * sumL = L[0] + ... + L[B-1].
  */
 typedef struct {
   int32_t B;        /* number of instances, >= 1                               */

@@ -248,19 +248,27 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
     HIP_TRY_B(hipEventCreate(&c->ev1));
   }
 
-  const float *dc, *dR;
-  const int* dM;
+  // c and M always end up in arrays the context owns (the walkers, the export and the later
+  // entry points read them long after this call): uploaded here for host inputs, copied by the
+  // prepare kernel for device inputs.  R is only read by the prepare kernel.
+  TRY(c->d_c.reserve(sizeof(float) * (size_t)sumL * S));
+  TRY(c->d_M.reserve(sizeof(int) * (size_t)sumL * S));
+  const float *src_c, *dR;
+  const int* src_M;
   if (p->ptr_space == GBMW_PTR_HOST) {
-    TRY(c->d_c.reserve(sizeof(float) * (size_t)sumL * S));
-    TRY(c->d_M.reserve(sizeof(int) * (size_t)sumL * S));
     TRY(c->d_R.reserve(sizeof(float) * (size_t)sumL * S * S));
     HIP_TRY_B(hipMemcpyAsync(c->d_c.p, p->c, sizeof(float) * (size_t)sumL * S, hipMemcpyHostToDevice, st));
     HIP_TRY_B(hipMemcpyAsync(c->d_M.p, p->M, sizeof(int) * (size_t)sumL * S, hipMemcpyHostToDevice, st));
     HIP_TRY_B(hipMemcpyAsync(c->d_R.p, p->R, sizeof(float) * (size_t)sumL * S * S, hipMemcpyHostToDevice, st));
-    dc = (const float*)c->d_c.p; dM = (const int*)c->d_M.p; dR = (const float*)c->d_R.p;
+    src_c = (const float*)c->d_c.p; src_M = (const int*)c->d_M.p; dR = (const float*)c->d_R.p;
+    c->h_M.assign(p->M, p->M + (size_t)sumL * S);
+    c->h_M_valid = true;
   } else {
-    dc = p->c; dM = p->M; dR = p->R;
+    src_c = p->c; src_M = p->M; dR = p->R;
+    c->h_M_valid = false;
   }
+  const float* dc = (const float*)c->d_c.p;
+  const int* dM = (const int*)c->d_M.p;
   // The small index arrays come from host vectors owned by the context, which
   // outlive the copies.
   if (!same_layout) {
@@ -295,7 +303,7 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
   TRY(gbmw_detail::ensure_streams(c, G));
 
   HIP_TRY_B(hipEventRecord(c->ev0, st));
-  gbmw::launch_prepare(t, dR, sumL, p->ptr_space == GBMW_PTR_DEVICE, st);
+  gbmw::launch_prepare(t, dR, src_c, src_M, sumL, p->ptr_space == GBMW_PTR_DEVICE, st);
   {
     // Layer 0 goes to memory only where something reads it from there.  Inside a
     // group the instances are ordered by L descending, so the short ones are a suffix.
@@ -361,13 +369,16 @@ gbmw_status gbmw_get_best(gbmw_ctx* c, float* best, uint8_t* best_s) {
   return GBMW_OK;
 }
 
-gbmw_status gbmw_backtrack(gbmw_ctx* c, int32_t nq, const int32_t* q_instance, const int32_t* q_e,
-                           uint8_t* plan, float* cost, int32_t* mem_used) {
-  g_err[0] = 0;
-  gbmw_status st = wait_and_check(c);
-  if (st != GBMW_OK) return st;
-  if (nq < 0) return fail(GBMW_ERR_INVALID_ARG, "nq=%d", nq);
-  if (nq == 0) return GBMW_OK;
+}  // extern "C"
+
+namespace {
+
+// `block` is device memory of at least
+// backtrack_block_bytes(nq, Lmax) bytes, laid out q_inst | q_e | cost | mem | plan.
+size_t backtrack_block_bytes(size_t nq, size_t Lmax) { return nq * (4 * sizeof(int)) + nq * Lmax; }
+
+gbmw_status check_queries(const gbmw_ctx* c, int32_t nq, const int32_t* q_instance, const int32_t* q_e,
+                          const uint8_t* plan, const float* cost, const int32_t* mem_used) {
   if (!q_instance || !q_e || !plan || !cost || !mem_used)
     return fail(GBMW_ERR_INVALID_ARG, "null query or output pointer");
   for (int i = 0; i < nq; ++i) {
@@ -376,12 +387,13 @@ gbmw_status gbmw_backtrack(gbmw_ctx* c, int32_t nq, const int32_t* q_instance, c
     if (q_e[i] < 0 || q_e[i] > c->E)
       return fail(GBMW_ERR_INVALID_ARG, "q_e[%d]=%d not in 0..%d", i, q_e[i], c->E);
   }
+  return GBMW_OK;
+}
+
+gbmw_status backtrack_in_block(gbmw_ctx* c, void* block, int32_t nq, const int32_t* q_instance,
+                               const int32_t* q_e, uint8_t* plan, float* cost, int32_t* mem_used) {
   const size_t n = (size_t)nq, Lm = (size_t)c->Lmax;
-  // one device block: q_inst | q_e | cost | mem | plan
-  const size_t bytes = n * (4 * sizeof(int)) + n * Lm;
-  st = c->d_q.reserve(bytes);
-  if (st != GBMW_OK) return st;
-  int* d_qi = (int*)c->d_q.p;
+  int* d_qi = (int*)block;
   int* d_qe = d_qi + n;
   float* d_cost = (float*)(d_qe + n);
   int* d_mem = (int*)(d_cost + n);
@@ -397,6 +409,24 @@ gbmw_status gbmw_backtrack(gbmw_ctx* c, int32_t nq, const int32_t* q_instance, c
   return GBMW_OK;
 }
 
+}  // namespace
+
+extern "C" {
+
+gbmw_status gbmw_backtrack(gbmw_ctx* c, int32_t nq, const int32_t* q_instance, const int32_t* q_e,
+                           uint8_t* plan, float* cost, int32_t* mem_used) {
+  g_err[0] = 0;
+  gbmw_status st = wait_and_check(c);
+  if (st != GBMW_OK) return st;
+  if (nq < 0) return fail(GBMW_ERR_INVALID_ARG, "nq=%d", nq);
+  if (nq == 0) return GBMW_OK;
+  st = check_queries(c, nq, q_instance, q_e, plan, cost, mem_used);
+  if (st != GBMW_OK) return st;
+  st = c->d_q.reserve(backtrack_block_bytes((size_t)nq, (size_t)c->Lmax));
+  if (st != GBMW_OK) return st;
+  return backtrack_in_block(c, c->d_q.p, nq, q_instance, q_e, plan, cost, mem_used);
+}
+
 gbmw_status gbmw_select_forward_budget(gbmw_ctx* c, const int32_t* O_f, const int32_t* O_b,
                                        const int32_t* O_ms, int32_t* e_opt, float* cost,
                                        uint8_t* plan, int32_t* e_all) {
@@ -406,8 +436,12 @@ gbmw_status gbmw_select_forward_budget(gbmw_ctx* c, const int32_t* O_f, const in
   if (!O_f || !O_b || !O_ms) return fail(GBMW_ERR_INVALID_ARG, "null O_f/O_b/O_ms");
   const size_t n = (size_t)c->sumL * c->S, B = (size_t)c->B, Lm = (size_t)c->Lmax;
   // O_f + O_ms must be the M the tables were filled with
-  std::vector<int> M(n);
-  HIP_TRY(hipMemcpy(M.data(), c->t.M, n * sizeof(int), hipMemcpyDeviceToHost));
+  if (!c->h_M_valid) {                    // device-resident inputs: fetched once per solve
+    c->h_M.resize(n);
+    HIP_TRY(hipMemcpy(c->h_M.data(), c->t.M, n * sizeof(int), hipMemcpyDeviceToHost));
+    c->h_M_valid = true;
+  }
+  const std::vector<int>& M = c->h_M;
   for (size_t i = 0; i < n; ++i) {
     if (O_f[i] < 0 || O_b[i] < 0 || O_ms[i] < 0)
       return fail(GBMW_ERR_INVALID_ARG, "negative O_f/O_b/O_ms at %zu", i);

@@ -65,6 +65,8 @@ struct gbmw_ctx {
   uint32_t flags = 0;
   int B = 0, S = 0, SP = 0, E = 0, EP = 0, sumL = 0, Lmax = 0;
   std::vector<int> L, off, perm;
+  std::vector<int> h_M;                      // host mirror of the solve's M (see h_M_valid)
+  bool h_M_valid = false;                    // filled at the solve for host inputs, on first use else
   gbmw::Tables t{};
   gbmw_detail::DevBuf d_L, d_off, d_perm, d_c, d_M, d_R, d_Rt, d_C, d_sum, d_A, d_best, d_best_s, d_status,
       d_q, d_stage, d_search, d_gather;

@@ -32,8 +32,8 @@ struct Tables {
   const int* L;        // [B]   device
   const int* off;      // [B]   device, first row of each instance
   const int* perm;     // [B]   device, instances ordered by L descending
-  const float* c;      // [sumL][S]
-  const int* M;        // [sumL][S]
+  const float* c;      // [sumL][S]  owned by the context (a copy of the caller's)
+  const int* M;        // [sumL][S]  owned by the context
   const float* Rt;     // [sumL][S][RS]
   float* Cbuf;         // keep_all ? [sumL][S][EP] : [2][B][S][EP]
   uint8_t* A;          // [sumL][S][EP]; null: records are not kept (needs keep_all), the
@@ -110,8 +110,10 @@ __device__ __forceinline__ int pred_strategy_wave(const Tables& t, int row, int 
 }
 #endif
 
-// R -> Rt (transpose + pad) and validation of device-resident inputs.
-void launch_prepare(const Tables& t, const float* R, int sumL, bool validate, hipStream_t st);
+// R -> Rt (transpose + pad), validation of device-resident inputs, and the copy of the
+// caller's c / M (src_c, src_M) into the context's own arrays t.c / t.M where they differ.
+void launch_prepare(const Tables& t, const float* R, const float* src_c, const int* src_M, int sumL,
+                    bool validate, hipStream_t st);
 // C(0, e, s) written to the table for instances perm[first .. first + count).  Needed
 // where something reads layer 0 from memory: instances with L_b <= 2 (final reduce,
 // export), every instance when all layers are kept or S > 64.

@@ -37,12 +37,18 @@ __device__ __forceinline__ float* c_table(const Tables& t, int inst, int row, in
 
 // ---------------------------------------------------------------------------
 // prepare: Rt[row][s][0..SP) = R[row][.][s] (zero padding), Rt[row][s][SP] = c,
-// Rt[row][s][SP+1] = bits of M; + input validation
+// Rt[row][s][SP+1] = bits of M; + input validation.  c and M are read from the caller's
+// arrays (src_c, src_M) and, where those are not the context's own (device-resident inputs),
+// copied into the context's (t.c, t.M), which is what every later kernel and every later call
+// reads: the caller's arrays are not touched again once this kernel has run.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_prepare(Tables t, const float* __restrict__ R, int sumL,
-                                                 int validate, float* __restrict__ Rt) {
+                                                 int validate, float* __restrict__ Rt,
+                                                 const float* __restrict__ src_c,
+                                                 const int* __restrict__ src_M) {
   const int SP = t.SP, S = t.S, RS = t.RS;
   const size_t n = (size_t)sumL * S * RS;
+  const bool copy = src_c != t.c;
   int bad = 0;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
        i += (size_t)gridDim.x * blockDim.x) {
@@ -53,11 +59,13 @@ __global__ __launch_bounds__(256) void k_prepare(Tables t, const float* __restri
     if (sp < S) {
       v = R[(row * S + sp) * S + s];
     } else if (sp == SP) {
-      v = t.c[row * S + s];
+      v = src_c[row * S + s];
       if (validate && !(v >= 0.0f)) bad |= 1;
+      if (copy) const_cast<float*>(t.c)[row * S + s] = v;
     } else if (sp == SP + 1) {
-      const int m = t.M[row * S + s];
+      const int m = src_M[row * S + s];
       if (validate && m < 0) bad |= 2;
+      if (copy) const_cast<int*>(t.M)[row * S + s] = m;
       v = __int_as_float(m);
     }
     Rt[i] = v;
@@ -82,7 +90,8 @@ __global__ __launch_bounds__(256) void k_validate_R(Tables t, const float* __res
 
 __global__ void k_clear_status(int* status) { *status = 0; }
 
-void launch_prepare(const Tables& t, const float* R, int sumL, bool validate, hipStream_t st) {
+void launch_prepare(const Tables& t, const float* R, const float* src_c, const int* src_M, int sumL,
+                    bool validate, hipStream_t st) {
   // a fill kernel rather than a memset node, so that the sequence can be captured
   hipLaunchKernelGGL(k_clear_status, dim3(1), dim3(1), 0, st, t.status);
   const size_t n = (size_t)sumL * t.S * t.RS;
@@ -90,7 +99,7 @@ void launch_prepare(const Tables& t, const float* R, int sumL, bool validate, hi
   if (blocks > 65536) blocks = 65536;
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(k_prepare, dim3(blocks), dim3(256), 0, st, t, R, sumL, validate ? 1 : 0,
-                     const_cast<float*>(t.Rt));
+                     const_cast<float*>(t.Rt), src_c, src_M);
   if (validate) hipLaunchKernelGGL(k_validate_R, dim3(64, t.B), dim3(256), 0, st, t, R);
 }
 
