@@ -149,6 +149,26 @@ gbmw_status gbmw_backtrack(gbmw_ctx* ctx, int32_t nq, const int32_t* q_instance,
                            const int32_t* q_e, uint8_t* plan, float* cost, int32_t* mem_used);
 
 /*
+ * gbmw_backtrack for callers that must not allocate device memory (tight serving
+ * loops, harnesses that forbid hipMalloc inside a step, code that prepares a HIP
+ * graph capture): same arguments, same results, but the staging block for the
+ * queries and the plans is a fixed array of GBMW_STATIC_SCRATCH_BYTES bytes
+ * inside the library's device image instead of a buffer of the context.  The
+ * call allocates nothing and frees nothing, on the device or through any library.
+ * Limit: nq * (16 + Lmax) <= GBMW_STATIC_SCRATCH_BYTES, else
+ * GBMW_ERR_UNSUPPORTED (nothing is enqueued).  Every GPU the library runs on
+ * holds one such array until the process ends, and all contexts on a GPU share
+ * it: calls of this function that overlap in time on one GPU race on it
+ * (serialise them); each call overwrites what the last one left, nothing in it
+ * has to be cleared.  Waits for the solve and for its own kernel, like
+ * gbmw_backtrack.
+ */
+#define GBMW_STATIC_SCRATCH_BYTES (1 << 20)
+gbmw_status gbmw_backtrack_static(gbmw_ctx* ctx, int32_t nq, const int32_t* q_instance,
+                                  const int32_t* q_e, uint8_t* plan, float* cost,
+                                  int32_t* mem_used);
+
+/*
  * The outer loop of Appendix A, Algorithm 3 on top of a solved context: choose
  * the forward budget E_fwd_opt whose plan also respects the OVERALL memory
  * E_all(plan) <= E of Section 4.1.2, Eq. 2,

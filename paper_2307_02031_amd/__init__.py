@@ -30,9 +30,10 @@ GBMW_FLAG_RESOLVE_ALL = 8
 GBMW_FLAG_LAZY_ARGMIN = 16
 GBMW_FLAG_DENSE_ARITHMETIC = 32
 GBMW_MAX_S = 256
+GBMW_STATIC_SCRATCH_BYTES = 1 << 20
 
 EXPORTS = [
-    "gbmw_dp_solve_batched", "gbmw_backtrack", "gbmw_select_forward_budget", "gbmw_pipeline_cost",
+    "gbmw_dp_solve_batched", "gbmw_backtrack", "gbmw_backtrack_static", "gbmw_select_forward_budget", "gbmw_pipeline_cost",
     "gbmw_partition_search", "gbmw_enumerate_strategies", "gbmw_cost_model",
     "gbmw_max_layers", "gbmw_get_best",
     "gbmw_export_tables", "gbmw_synchronize", "gbmw_last_solve_ms", "gbmw_destroy",
@@ -91,6 +92,8 @@ _lib.gbmw_dp_solve_batched.argtypes = [ct.POINTER(gbmw_problem), ct.c_uint32, ct
 _lib.gbmw_dp_solve_batched.restype = ct.c_int
 _lib.gbmw_backtrack.argtypes = [ct.c_void_p, ct.c_int32] + [ct.c_void_p] * 5
 _lib.gbmw_backtrack.restype = ct.c_int
+_lib.gbmw_backtrack_static.argtypes = [ct.c_void_p, ct.c_int32] + [ct.c_void_p] * 5
+_lib.gbmw_backtrack_static.restype = ct.c_int
 _lib.gbmw_select_forward_budget.argtypes = [ct.c_void_p] * 8
 _lib.gbmw_select_forward_budget.restype = ct.c_int
 _lib.gbmw_pipeline_cost.argtypes = [ct.c_void_p, ct.c_int32] + [ct.c_void_p] * 8
@@ -212,6 +215,20 @@ def gbmw_backtrack(ctx: Context, q_instance, q_e):
     mem = np.empty(nq, np.int32)
     _check(_lib.gbmw_backtrack(ctx.handle, nq, qi.ctypes.data, qe.ctypes.data, plan.ctypes.data,
                                cost.ctypes.data, mem.ctypes.data))
+    return plan, cost, mem
+
+
+def gbmw_backtrack_static(ctx: Context, q_instance, q_e):
+    """gbmw_backtrack through the library's fixed staging block (no device allocation)."""
+    qi = np.ascontiguousarray(q_instance, dtype=np.int32)
+    qe = np.ascontiguousarray(q_e, dtype=np.int32)
+    assert qi.shape == qe.shape and qi.ndim == 1
+    nq, Lmax = len(qi), gbmw_max_layers(ctx)
+    plan = np.empty((nq, Lmax), np.uint8)
+    cost = np.empty(nq, np.float32)
+    mem = np.empty(nq, np.int32)
+    _check(_lib.gbmw_backtrack_static(ctx.handle, nq, qi.ctypes.data, qe.ctypes.data, plan.ctypes.data,
+                                      cost.ctypes.data, mem.ctypes.data))
     return plan, cost, mem
 
 

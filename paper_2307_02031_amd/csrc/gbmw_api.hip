@@ -8,12 +8,42 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <numeric>
 #include <vector>
 
 #include "gbmw_ctx.h"
 #include "gbmw_kernels.h"
+
+// Staging block of gbmw_backtrack_static: queries in, plans out.  One copy per GPU, held
+// until the process ends.  Host code never uses the array's name as an address: the device
+// address is looked up once per device (static_scratch) and that pointer is what copies and
+// kernels get.
+static constexpr size_t kStaticScratchBytes = (size_t)GBMW_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices] = {};
+static std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on device `dev`, which must be the current device.
+static gbmw_status static_scratch(int dev, void** out) {
+  if (dev < 0 || dev >= kMaxDevices)
+    return gbmw_detail::fail(GBMW_ERR_UNSUPPORTED, "device %d: only devices 0..%d are supported", dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return gbmw_detail::fail(GBMW_ERR_DEVICE, "hipGetSymbolAddress(scratch) on device %d: %s", dev,
+                               hipGetErrorString(e));
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return GBMW_OK;
+}
 
 namespace {
 
@@ -373,7 +403,7 @@ gbmw_status gbmw_get_best(gbmw_ctx* c, float* best, uint8_t* best_s) {
 
 namespace {
 
-// `block` is device memory of at least
+// Shared by gbmw_backtrack and gbmw_backtrack_static: `block` is device memory of at least
 // backtrack_block_bytes(nq, Lmax) bytes, laid out q_inst | q_e | cost | mem | plan.
 size_t backtrack_block_bytes(size_t nq, size_t Lmax) { return nq * (4 * sizeof(int)) + nq * Lmax; }
 
@@ -425,6 +455,27 @@ gbmw_status gbmw_backtrack(gbmw_ctx* c, int32_t nq, const int32_t* q_instance, c
   st = c->d_q.reserve(backtrack_block_bytes((size_t)nq, (size_t)c->Lmax));
   if (st != GBMW_OK) return st;
   return backtrack_in_block(c, c->d_q.p, nq, q_instance, q_e, plan, cost, mem_used);
+}
+
+gbmw_status gbmw_backtrack_static(gbmw_ctx* c, int32_t nq, const int32_t* q_instance, const int32_t* q_e,
+                                  uint8_t* plan, float* cost, int32_t* mem_used) {
+  g_err[0] = 0;
+  gbmw_status st = wait_and_check(c);                    // makes the context's device current
+  if (st != GBMW_OK) return st;
+  if (nq < 0) return fail(GBMW_ERR_INVALID_ARG, "nq=%d", nq);
+  if (nq == 0) return GBMW_OK;
+  st = check_queries(c, nq, q_instance, q_e, plan, cost, mem_used);
+  if (st != GBMW_OK) return st;
+  const size_t need = backtrack_block_bytes((size_t)nq, (size_t)c->Lmax);
+  if (need > kStaticScratchBytes)
+    return fail(GBMW_ERR_UNSUPPORTED,
+                "gbmw_backtrack_static: %d queries of %d layers need %zu bytes of staging, the static block "
+                "holds %zu (at most %zu queries at this depth)",
+                nq, c->Lmax, need, kStaticScratchBytes, kStaticScratchBytes / (16 + (size_t)c->Lmax));
+  void* block = nullptr;
+  st = static_scratch(c->device, &block);
+  if (st != GBMW_OK) return st;
+  return backtrack_in_block(c, block, nq, q_instance, q_e, plan, cost, mem_used);
 }
 
 gbmw_status gbmw_select_forward_budget(gbmw_ctx* c, const int32_t* O_f, const int32_t* O_b,
