@@ -83,6 +83,97 @@ def cpu_baseline(p, budget_s=12.0):
                       f"OpenMP over budget rows"}
 
 
+def kernel_roofline(g, torch, p, d, args, flags, step_sec):
+    """The dominant kernel (k_minplus: Eq. 3's inner minimum fused with the shift-add), one launch per
+    layer: average duration from HIP event pairs around every launch on the solve's stream (one stream),
+    and the work the launches really did from the library's path counters (a second, untimed solve
+    with GBMW_FLAG_COUNT_WORK: which waves took the run shortcut depends on the inputs alone).
+
+    achieved = executed lane-ops per launch / average launch duration, with 2 lane-ops (one add, one
+    min) per candidate update that a lane or a run really computed; covered / executed updates is
+    the shortcut's gain and is reported separately.  HBM bytes are modelled from the same counters.
+    """
+    dense = bool(flags & g.GBMW_FLAG_DENSE_ARITHMETIC)
+    keep = flags & (g.GBMW_FLAG_DENSE_ARITHMETIC | g.GBMW_FLAG_LAZY_ARGMIN)
+    records = not (flags & g.GBMW_FLAG_LAZY_ARGMIN)
+    reps = max(3, min(args.steps, 10))
+    tctx = None
+    mp_ms = mp_n = tot_ms = 0.0
+    for _ in range(reps + 1):
+        tctx = g.gbmw_dp_solve_batched(p.L, d[0], d[1], d[2], p.S, p.E, flags=g.GBMW_FLAG_TIME_KERNELS | keep, ctx=tctx)
+        a, b, n = g.gbmw_last_solve_ms(tctx)
+        if _ == 0:
+            continue                                                      # warm-up of this mode
+        tot_ms += a; mp_ms += b; mp_n += n
+    # the same launch sequence, untimed, on one stream: the step that the per-kernel times add up to
+    octx, one_sec = solve_steps(g, torch, p, d, max(3, args.steps // 2), 1, flags=g.GBMW_FLAG_ONE_STREAM | keep)
+    g.gbmw_destroy(octx)
+    tctx = g.gbmw_dp_solve_batched(p.L, d[0], d[1], d[2], p.S, p.E, flags=g.GBMW_FLAG_COUNT_WORK | keep, ctx=tctx)
+    n_launch = int(mp_n / reps)
+    work = [g.gbmw_last_solve_work(tctx, i) for i in range(n_launch)]
+    g.gbmw_destroy(tctx)
+    S = p.S
+    tot = [sum(w[k] for w in work) for k in range(4)]
+    upd_runs = (tot[0] + tot[1] + tot[2]) * S * S                          # one column's S x S' updates each
+    upd_dense = tot[3] * 64 * S                                            # a row: 64 lanes x S' candidates
+    upd_exec = upd_runs + upd_dense
+    covered = p.executed_updates()
+    # HBM bytes by path (the R tile of a workgroup, S x (S'+2) floats, is re-read from the L2 and left out):
+    #   dense row (wave, s): 64 x 4 B of the previous table read (not in the layer-1 launch), 64 x 4 B of
+    #     the new table and 64 x 1 B of records written, one summary word
+    #   run wave: per strategy M and two summary words read (12 B), 64 record bytes and one summary word
+    #     written; if it was recognised only from the loaded values it has read its 64 x 4 B per strategy too
+    #   run workgroup (4 waves): 4 x the reads, 256 record bytes and four summary words per strategy
+    rec = 1 if records else 0
+    sumw = 0 if dense else 4
+    read_b = write_b = 0
+    for i, w in enumerate(work):
+        read_b += w[3] * (256 if i > 0 else 0) + (w[1] + w[2] + 4 * w[0]) * 12 * S + (w[2] * 256 * S if i > 0 else 0)
+        write_b += w[3] * (256 + 64 * rec + sumw) + (w[1] + w[2]) * S * (64 * rec + 4) + w[0] * S * (256 * rec + 16)
+    avg_launch_s = mp_ms / mp_n * 1e-3 if mp_n else float("nan")
+    ach = OPS_PER_UPDATE * upd_exec / n_launch / avg_launch_s / 1e12 if mp_n else 0.0
+    hbm_model = (read_b + write_b) / n_launch if n_launch else 0.0
+    traffic, traffic_source = None, None
+    tname = f"k_minplus_cfg{args.config}_hbm_traffic.txt"
+    tpath = os.path.join(ROOT, "profiles", tname)
+    if os.path.exists(tpath):
+        key = "hbm_bytes_per_launch_dense:" if dense else "hbm_bytes_per_launch:"
+        for line in open(tpath):
+            if line.startswith(key):
+                traffic = int(line.split(":")[1])
+                traffic_source = (f"profiles/{tname}: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of "
+                                  f"this benchmark, scaled by a 1 GiB copy (commands in the file); not measured "
+                                  f"in this run")
+    return {
+        "kernel": "k_minplus (fused min-plus + argmin + shift-add), one launch per layer",
+        "mode": "dense arithmetic" if dense else "run shortcut (default)",
+        "bound": "alu", "achieved": ach, "peak": PEAK_PLAIN_FP32_TOPS, "unit": "TFLOP/s",
+        "frac": ach / PEAK_PLAIN_FP32_TOPS,
+        "peak_is": "plain (non-packed, non-FMA) fp32 VALU lane-ops: 256 CU x 64 lanes x 2.4 GHz = 39.3 T/s; "
+                   "the published 157.3 TFLOP/s is this x2 packed x2 FMA",
+        "frac_of_published_fp32_vector_peak": ach / PEAK_PUBLISHED_FP32_TFLOPS,
+        "ops_per_update": OPS_PER_UPDATE,
+        "valu_instr_floor_per_update": 1.5,
+        "frac_of_instr_floor": ach / OPS_PER_UPDATE * 1.5 / PEAK_PLAIN_FP32_TOPS,
+        "note": "achieved = 2 lane-ops (add, min) x candidate updates really computed per launch / average "
+                "launch duration; a three-input min folds two candidates, so the instruction floor is 1.5 per "
+                "update and frac_of_instr_floor is the share of the VALU issue rate that floor would need",
+        "executed_updates_per_launch": upd_exec / n_launch if n_launch else 0,
+        "covered_updates_per_launch": covered / n_launch if n_launch else 0,
+        "shortcut_gain": covered / upd_exec if upd_exec else None,
+        "work_per_solve": {"run_workgroups": tot[0], "run_waves_by_summary": tot[1], "run_waves_by_value": tot[2],
+                           "dense_rows": tot[3]},
+        "hbm": {"modelled_bytes_per_launch": hbm_model, "achieved_GBps": hbm_model / avg_launch_s / 1e9 if mp_n else 0.0,
+                "peak": 8000.0, "frac": hbm_model / avg_launch_s / 8e12 if mp_n else 0.0,
+                "dense_formulation_bytes_per_launch": (8.0 + rec) * covered / S / n_launch if n_launch else 0.0},
+        "traffic": traffic, "traffic_source": traffic_source,
+        "avg_launch_ms": avg_launch_s * 1e3, "launches_per_solve": n_launch,
+        "sum_kernel_ms_per_solve": mp_ms / reps, "timed_solve_ms": tot_ms / reps,
+        "ms_per_step_one_stream": one_sec * 1e3, "ms_per_step": step_sec * 1e3,
+        "kernel_share_of_one_stream_step": (mp_ms / reps) / (one_sec * 1e3) if one_sec else None,
+    }
+
+
 def partition_workload(gi):
     """16 (batch size, PP degree) pairs of a 48-layer, 44-strategy model: batch
     sizes scale the activation memory (x0.5, x1, x2, x4), PP degrees 2, 4, 8, 16."""
@@ -238,58 +329,7 @@ def main():
     ctx, sec = solve_steps(g, torch, p, d, args.steps, args.warmup, flags=base_flags)
     nominal, executed = p.nominal_updates(), p.executed_updates()
 
-    # the dominant kernel, timed live with HIP event pairs on the solve's stream
-    tctx = None
-    mp_ms = mp_n = tot_ms = 0.0
-    reps = max(3, min(args.steps, 10))
-    for _ in range(reps):
-        tctx = g.gbmw_dp_solve_batched(p.L, d[0], d[1], d[2], p.S, p.E, flags=g.GBMW_FLAG_TIME_KERNELS | (base_flags & g.GBMW_FLAG_DENSE_ARITHMETIC), ctx=tctx)
-        a, b, n = g.gbmw_last_solve_ms(tctx)
-        tot_ms += a; mp_ms += b; mp_n += n
-    g.gbmw_destroy(tctx)
-    launches_per_solve = mp_n / reps
-    avg_launch_ms = mp_ms / mp_n if mp_n else float("nan")
-    ops_per_launch = OPS_PER_UPDATE * executed / launches_per_solve if mp_n else 0.0
-    achieved = ops_per_launch / (avg_launch_ms * 1e-3) / 1e12 if mp_n else 0.0
-    # HBM bytes per launch as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by
-    # a copy kernel of known size); the summary file states the commands.
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"k_minplus_cfg{args.config}_hbm_traffic.txt")
-    if os.path.exists(tpath):
-        for line in open(tpath):
-            if line.startswith("hbm_bytes_per_launch:"):
-                traffic = int(line.split(":")[1])
-    hbm_alg = 9.0 * executed / p.S / launches_per_solve if mp_n else 0.0
-    hbm_gbps = hbm_alg / (avg_launch_ms * 1e-3) / 1e9 if mp_n else 0.0
-    alu = {"achieved": achieved, "peak": PEAK_PLAIN_FP32_TOPS, "unit": "TFLOP/s",
-           "frac": achieved / PEAK_PLAIN_FP32_TOPS, "ops_per_update": OPS_PER_UPDATE,
-           "frac_of_published_fp32_vector_peak": achieved / PEAK_PUBLISHED_FP32_TFLOPS,
-           "note": "algorithmic lane-ops (2 per candidate update: one add, one min) of the updates a launch "
-                   "covers / its duration"}
-    common = {"kernel": "k_minplus (fused min-plus + argmin + shift-add)", "traffic": traffic,
-              "updates_per_launch": executed / launches_per_solve if mp_n else 0,
-              "algorithmic_bytes_per_launch": hbm_alg, "avg_launch_ms": avg_launch_ms,
-              "launches_per_solve": launches_per_solve,
-              "kernel_share_of_solve": mp_ms / tot_ms if tot_ms else None}
-    if args.dense_arithmetic:
-        # every lane computes its own cell: the launch is bound by the fp32 VALU
-        roofline = dict(alu, bound="alu", hbm_GBps_algorithmic=hbm_gbps, **common)
-    else:
-        # Default mode: a wave whose 64 budgets share one input column computes it once and
-        # leaves its cells of the fp32 table unwritten (the layer's summary word stands for
-        # them), so both the arithmetic per covered update and the bytes per covered cell drop
-        # far below the method's 2 lane-ops and 9 bytes (4 read, 4 + 1 written).  `achieved` is
-        # the contract's figure, algorithmic bytes / duration, and can pass the peak for that
-        # reason; `measured_GBps` is what the launch really moves (`traffic` / duration).  The ALU
-        # view of the same launch is kept beside it (covered, not executed, updates), and
-        # dense_arithmetic below is the same solve with every cell computed and written, bound
-        # by the VALU.
-        roofline = dict(common, bound="hbm", achieved=hbm_gbps, peak=8000.0, unit="GB/s",
-                        frac=hbm_gbps / 8000.0,
-                        measured_GBps=(traffic / (avg_launch_ms * 1e-3) / 1e9) if traffic and mp_n else None,
-                        note="frac counts the dense formulation's bytes (9 per cell); the run shortcut "
-                             "skips most of them, so it can exceed 1",
-                        alu=alu)
+    roofline = kernel_roofline(g, torch, p, d, args, base_flags, sec)
 
     out = {
         "metric": "DP cell-updates/s (B*L*E*S*S')", "value": nominal / sec, "unit": "cell-updates/s",
@@ -309,32 +349,13 @@ def main():
         dflags = base_flags | g.GBMW_FLAG_DENSE_ARITHMETIC
         dctx, dsec = solve_steps(g, torch, p, d, args.steps, args.warmup, flags=dflags)
         g.gbmw_destroy(dctx)
-        dt_ = None
-        dmp = dmn = 0.0
-        for _ in range(reps):
-            dt_ = g.gbmw_dp_solve_batched(p.L, d[0], d[1], d[2], p.S, p.E,
-                                          flags=g.GBMW_FLAG_TIME_KERNELS | g.GBMW_FLAG_DENSE_ARITHMETIC, ctx=dt_)
-            _, b3, n3 = g.gbmw_last_solve_ms(dt_)
-            dmp += b3; dmn += n3
-        g.gbmw_destroy(dt_)
-        d_launch_ms = dmp / dmn if dmn else float("nan")
-        d_ach = OPS_PER_UPDATE * executed / (dmn / reps) / (d_launch_ms * 1e-3) / 1e12 if dmn else 0.0
-        out["dense_arithmetic"] = {
-            "ms_per_step": dsec * 1e3, "value": nominal / dsec, "value_executed": executed / dsec,
-            "avg_launch_ms": d_launch_ms, "achieved": d_ach, "peak": PEAK_PLAIN_FP32_TOPS,
-            "frac": d_ach / PEAK_PLAIN_FP32_TOPS, "bound": "alu"}
+        dr = kernel_roofline(g, torch, p, d, args, dflags, dsec)
+        out["dense_arithmetic"] = dict(dr, ms_per_step=dsec * 1e3, value=nominal / dsec, value_executed=executed / dsec)
     # The same solve without argmin records (GBMW_FLAG_LAZY_ARGMIN): every layer's fp32 table
     # is kept and the walkers recompute the records they need.  Reported beside the headline,
     # never as it: the headline path materialises every record.
-    lctx, lsec = solve_steps(g, torch, p, d, args.steps, args.warmup, flags=base_flags | g.GBMW_FLAG_LAZY_ARGMIN)
-    g.gbmw_destroy(lctx)
-    lt = None
-    lmp = lmn = 0.0
-    for _ in range(reps):
-        lt = g.gbmw_dp_solve_batched(p.L, d[0], d[1], d[2], p.S, p.E,
-                                     flags=g.GBMW_FLAG_TIME_KERNELS | g.GBMW_FLAG_LAZY_ARGMIN | (base_flags & g.GBMW_FLAG_DENSE_ARITHMETIC), ctx=lt)
-        _, b2, n2 = g.gbmw_last_solve_ms(lt)
-        lmp += b2; lmn += n2
+    lflags = base_flags | g.GBMW_FLAG_LAZY_ARGMIN
+    lt, lsec = solve_steps(g, torch, p, d, args.steps, args.warmup, flags=lflags)
     # plans through the recomputing walker, same query set as the backtrack leg below
     import numpy as np
     window = min(256, p.E + 1)
@@ -345,16 +366,14 @@ def main():
     g.gbmw_backtrack(lt, qi, qe)
     lbt = time.perf_counter() - t0
     g.gbmw_destroy(lt)
-    l_launch_ms = lmp / lmn if lmn else float("nan")
-    l_ach = OPS_PER_UPDATE * executed / (lmn / reps) / (l_launch_ms * 1e-3) / 1e12 if lmn else 0.0
-    out["lazy_argmin"] = {
-        "ms_per_step": lsec * 1e3, "value": nominal / lsec, "value_executed": executed / lsec,
-        "avg_launch_ms": l_launch_ms, "achieved": l_ach, "frac": l_ach / PEAK_PLAIN_FP32_TOPS,
-        "hbm_frac_algorithmic": (8.0 * executed / p.S / (lmn / reps)) / (l_launch_ms * 1e-3) / 8e12 if lmn else 0.0,
-        "table_bytes_per_cell": 4, "backtrack_ms": lbt * 1e3, "backtrack_queries": int(len(qi)),
-        "note": "no argmin records written (8 algorithmic bytes per cell instead of 9, tables of all "
-                "layers kept: 4 B/cell resident instead of 1); frac counts 2 lane-ops per update, the "
-                "three-input min folds two candidates per op, so a value pass can exceed 1.0"}
+    lr = kernel_roofline(g, torch, p, d, args, lflags, lsec)
+    out["lazy_argmin"] = dict(
+        lr, ms_per_step=lsec * 1e3, value=nominal / lsec, value_executed=executed / lsec,
+        table_bytes_per_cell=4, backtrack_ms=lbt * 1e3, backtrack_queries=int(len(qi)),
+        note_lazy="no argmin records written (8 bytes per cell of the dense formulation instead of 9; the "
+                  "tables of all layers are kept, 4 B/cell resident instead of 1); a value pass folds two "
+                  "candidates per three-input min, so its frac at 2 lane-ops per update can pass 1.0 while "
+                  "frac_of_instr_floor cannot")
     # row a4: plans for a window of budgets below E for every instance (the E_fwd window
     # Algorithm 3 inspects), timed end to end through the ABI (upload, walk, download)
     g.gbmw_backtrack(ctx, qi[:64], qe[:64])
@@ -381,24 +400,32 @@ def main():
 
     if not args.no_others:
         others = {}
-        for k in (1, 2, 3, 5):
+        ceiling = PEAK_PLAIN_FP32_TOPS * 1e12 / OPS_PER_UPDATE       # updates/s at 2 plain lane-ops per update
+        wide = gi.random_instance(128, 12, 128, 32768, M_rng=(64, 1024), R_rng=(0.0, 5.0))
+        wide.name = "S=128 (above the register-blocked range): L=12, E=32768, c~U[1,10), M~U{64..1024}, R~U[0,5)"
+        for k in (1, 2, 3, 5, "S128"):
             if k == args.config:
                 continue
-            q = gi.make_config(k)
+            q = wide if k == "S128" else gi.make_config(k)
+            name = k if k == "S128" else f"cfg{k}"
             dq = to_device(torch, q)
-            c2, s2 = solve_steps(g, torch, q, dq, 5 if k == 5 else 20, 2, flags=base_flags)
-            others[f"cfg{k}"] = {"ms_per_step": s2 * 1e3, "value": q.nominal_updates() / s2,
-                                 "value_executed": q.executed_updates() / s2}
+            n_steps = 5 if k in (5, "S128") else 20
+            c2, s2 = solve_steps(g, torch, q, dq, n_steps, 2, flags=base_flags)
+            others[name] = {"workload": q.name, "ms_per_step": s2 * 1e3, "value": q.nominal_updates() / s2,
+                            "value_executed": q.executed_updates() / s2,
+                            "covered_updates_frac_of_alu_ceiling": q.executed_updates() / s2 / ceiling}
             g.gbmw_destroy(c2)
-            c3, s3 = solve_steps(g, torch, q, dq, 5 if k == 5 else 20, 2, flags=base_flags | g.GBMW_FLAG_LAZY_ARGMIN)
-            others[f"cfg{k}"]["lazy_argmin_ms_per_step"] = s3 * 1e3
-            others[f"cfg{k}"]["lazy_argmin_value_executed"] = q.executed_updates() / s3
+            c3, s3 = solve_steps(g, torch, q, dq, n_steps, 2, flags=base_flags | g.GBMW_FLAG_LAZY_ARGMIN)
+            others[name]["lazy_argmin_ms_per_step"] = s3 * 1e3
+            others[name]["lazy_argmin_value_executed"] = q.executed_updates() / s3
             g.gbmw_destroy(c3)
-            if k == 5 and not args.dense_arithmetic:
-                c4, s4 = solve_steps(g, torch, q, dq, 5, 2, flags=base_flags | g.GBMW_FLAG_DENSE_ARITHMETIC)
-                others[f"cfg{k}"]["dense_arithmetic_ms_per_step"] = s4 * 1e3
+            if k in (2, 3, 5, "S128") and not args.dense_arithmetic:
+                c4, s4 = solve_steps(g, torch, q, dq, n_steps, 2, flags=base_flags | g.GBMW_FLAG_DENSE_ARITHMETIC)
+                others[name]["dense_arithmetic_ms_per_step"] = s4 * 1e3
+                others[name]["dense_arithmetic_frac_of_alu_ceiling"] = q.executed_updates() / s4 / ceiling
                 g.gbmw_destroy(c4)
             del dq
+        others["alu_ceiling_updates_per_s"] = ceiling
         out["other_configs"] = others
 
     if not args.no_partition:

@@ -82,7 +82,12 @@ enum {
                                   cells are not written inside the library's own tables
                                   (what gbmw_export_tables and every other call return is
                                   unaffected).  Identical results either way; the flag
-                                  exists to time the dense arithmetic                     */
+                                  exists to time the dense arithmetic                     */,
+  GBMW_FLAG_COUNT_WORK = 64u   /* measurement: the min-plus launches also count the waves
+                                  that took the shortcut above, for gbmw_last_solve_work
+                                  (implies GBMW_FLAG_ONE_STREAM).  The counts depend on the
+                                  inputs alone; the counting costs registers, so time the
+                                  kernels in a solve without this flag                    */
 };
 
 #define GBMW_MAX_S 256
@@ -469,6 +474,24 @@ gbmw_status gbmw_synchronize(gbmw_ctx* ctx);
  */
 gbmw_status gbmw_last_solve_ms(gbmw_ctx* ctx, float* total_ms, float* minplus_ms,
                                int32_t* minplus_launches);
+
+/*
+ * What the min-plus launches of the last solve really computed, for roofline
+ * accounting (all zero unless the solve was given GBMW_FLAG_COUNT_WORK).  launch
+ * selects one min-plus launch of the solve, in the order they were enqueued
+ * (0 is the launch of layer 1, whose input is layer 0's closed form and is not
+ * read from memory), or -1 for the sum over all of them.  With the run shortcut
+ * of Eq. 3's fill (see GBMW_FLAG_DENSE_ARITHMETIC) a group of budgets that reads
+ * one and the same column of the previous table is computed once:
+ *   work[0]  workgroups (256 budgets) computed once:      S * S candidate updates each
+ *   work[1]  waves (64 budgets) computed once, recognised
+ *            from the summaries:                          S * S updates each
+ *   work[2]  the same, recognised from the loaded table:  S * S updates each
+ *   work[3]  (wave, output strategy) rows computed cell
+ *            by cell:                                     64 * S updates each
+ * Waits for the solve.
+ */
+gbmw_status gbmw_last_solve_work(gbmw_ctx* ctx, int32_t launch, uint64_t work[4]);
 
 /* Free the context and its device memory (waits first).  NULL is allowed. */
 void gbmw_destroy(gbmw_ctx* ctx);

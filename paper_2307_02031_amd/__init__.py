@@ -29,6 +29,7 @@ GBMW_FLAG_ONE_STREAM = 4
 GBMW_FLAG_RESOLVE_ALL = 8
 GBMW_FLAG_LAZY_ARGMIN = 16
 GBMW_FLAG_DENSE_ARITHMETIC = 32
+GBMW_FLAG_COUNT_WORK = 64
 GBMW_MAX_S = 256
 GBMW_STATIC_SCRATCH_BYTES = 1 << 20
 
@@ -36,7 +37,7 @@ EXPORTS = [
     "gbmw_dp_solve_batched", "gbmw_backtrack", "gbmw_backtrack_static", "gbmw_select_forward_budget", "gbmw_pipeline_cost",
     "gbmw_partition_search", "gbmw_enumerate_strategies", "gbmw_cost_model",
     "gbmw_max_layers", "gbmw_get_best",
-    "gbmw_export_tables", "gbmw_synchronize", "gbmw_last_solve_ms", "gbmw_destroy",
+    "gbmw_export_tables", "gbmw_synchronize", "gbmw_last_solve_ms", "gbmw_last_solve_work", "gbmw_destroy",
     "gbmw_last_error", "gbmw_version",
 ]
 
@@ -117,6 +118,8 @@ _lib.gbmw_synchronize.restype = ct.c_int
 _lib.gbmw_last_solve_ms.argtypes = [ct.c_void_p, ct.POINTER(ct.c_float), ct.POINTER(ct.c_float),
                                     ct.POINTER(ct.c_int32)]
 _lib.gbmw_last_solve_ms.restype = ct.c_int
+_lib.gbmw_last_solve_work.argtypes = [ct.c_void_p, ct.c_int32, ct.POINTER(ct.c_uint64)]
+_lib.gbmw_last_solve_work.restype = ct.c_int
 _lib.gbmw_destroy.argtypes = [ct.c_void_p]
 _lib.gbmw_destroy.restype = None
 _lib.gbmw_last_error.restype = ct.c_char_p
@@ -370,6 +373,14 @@ def gbmw_last_solve_ms(ctx: Context):
     a, b, n = ct.c_float(), ct.c_float(), ct.c_int32()
     _check(_lib.gbmw_last_solve_ms(ctx.handle, ct.byref(a), ct.byref(b), ct.byref(n)))
     return a.value, b.value, n.value
+
+
+def gbmw_last_solve_work(ctx: Context, launch: int = -1):
+    """(wide workgroups, run waves by summary, run waves by value, dense rows) of the last counted
+    solve: of one min-plus launch, or summed over all (launch = -1)."""
+    w = (ct.c_uint64 * 4)()
+    _check(_lib.gbmw_last_solve_work(ctx.handle, launch, w))
+    return tuple(int(x) for x in w)
 
 
 def gbmw_destroy(ctx: Context) -> None:

@@ -81,7 +81,7 @@ void free_ctx(gbmw_ctx* c) {
   (void)hipStreamSynchronize(c->stream);
   for (DevBuf* b : {&c->d_L, &c->d_off, &c->d_perm, &c->d_c, &c->d_M, &c->d_R, &c->d_Rt, &c->d_C, &c->d_sum,
                     &c->d_A, &c->d_best, &c->d_best_s, &c->d_status, &c->d_q, &c->d_stage,
-                    &c->d_search, &c->d_gather})
+                    &c->d_search, &c->d_gather, &c->d_counts})
     b->release();
   if (c->ev0) (void)hipEventDestroy(c->ev0);
   if (c->ev1) (void)hipEventDestroy(c->ev1);
@@ -176,7 +176,7 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
   if (p->ptr_space != GBMW_PTR_HOST && p->ptr_space != GBMW_PTR_DEVICE)
     return fail(GBMW_ERR_INVALID_ARG, "ptr_space=%d", p->ptr_space);
   if (flags & ~(uint32_t)(GBMW_FLAG_KEEP_ALL_C | GBMW_FLAG_TIME_KERNELS | GBMW_FLAG_ONE_STREAM |
-                          GBMW_FLAG_LAZY_ARGMIN | GBMW_FLAG_DENSE_ARITHMETIC))
+                          GBMW_FLAG_LAZY_ARGMIN | GBMW_FLAG_DENSE_ARITHMETIC | GBMW_FLAG_COUNT_WORK))
     return fail(GBMW_ERR_INVALID_ARG, "unknown flag bits 0x%x", flags);
 
   const int B = p->B, S = p->S, E = p->E;
@@ -203,7 +203,8 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
   // instances are independent, so one group's launch fills the ramp-down of
   // another's.
   const bool timed = (flags & GBMW_FLAG_TIME_KERNELS) != 0;
-  int G = (timed || (flags & GBMW_FLAG_ONE_STREAM)) ? 1 : kGroups;
+  const bool counting = (flags & GBMW_FLAG_COUNT_WORK) != 0;
+  int G = (timed || counting || (flags & GBMW_FLAG_ONE_STREAM)) ? 1 : kGroups;
   if (G > B) G = B;
   std::vector<int> grouped, gfirst(G + 1, 0);
   for (int g = 0; g < G; ++g) {
@@ -322,6 +323,10 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
   t.prev_full = 0;
 
   c->timed_launches = 0;
+  c->counted_launches = 0;
+  c->counted_waves.clear();
+  t.counts = nullptr;
+  if (counting) TRY(c->d_counts.reserve(sizeof(unsigned long long) * 4 * (size_t)Lmax));
   if (timed) {
     while ((int)c->ev_layer.size() < 2 * Lmax) {
       hipEvent_t e;
@@ -332,6 +337,7 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
 
   TRY(gbmw_detail::ensure_streams(c, G));
 
+  if (counting) gbmw::launch_clear_counts((unsigned long long*)c->d_counts.p, 4 * Lmax, st);
   HIP_TRY_B(hipEventRecord(c->ev0, st));
   gbmw::launch_prepare(t, dR, src_c, src_M, sumL, p->ptr_space == GBMW_PTR_DEVICE, st);
   {
@@ -356,6 +362,10 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
       const int na = active_in_group(g, l);
       if (na == 0) break;
       if (timed) HIP_TRY_B(hipEventRecord(c->ev_layer[2 * c->timed_launches], sg));
+      if (counting) {
+        t.counts = (unsigned long long*)c->d_counts.p + 4 * (size_t)c->counted_launches++;
+        c->counted_waves.push_back((unsigned long long)na * (unsigned long long)((E + 64) / 64));
+      }
       gbmw::launch_minplus(t, l, gfirst[g], na, sg, l > 1 ? active_in_group(g, l - 1) : 0);
       if (timed) {
         HIP_TRY_B(hipEventRecord(c->ev_layer[2 * c->timed_launches + 1], sg));
@@ -368,6 +378,7 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
       HIP_TRY_B(hipStreamWaitEvent(st, c->ev_join[g - 1], 0));
     }
   }
+  t.counts = nullptr;
   HIP_TRY_B(hipEventRecord(c->ev1, st));
   HIP_TRY_B(hipGetLastError());
 #undef TRY
@@ -657,6 +668,28 @@ gbmw_status gbmw_last_solve_ms(gbmw_ctx* c, float* total_ms, float* minplus_ms,
   }
   if (minplus_ms) *minplus_ms = sum;
   if (minplus_launches) *minplus_launches = c->timed_launches;
+  return GBMW_OK;
+}
+
+gbmw_status gbmw_last_solve_work(gbmw_ctx* c, int32_t launch, uint64_t work[4]) {
+  g_err[0] = 0;
+  gbmw_status st = wait_and_check(c);
+  if (st != GBMW_OK) return st;
+  if (!work) return fail(GBMW_ERR_INVALID_ARG, "null output pointer");
+  work[0] = work[1] = work[2] = work[3] = 0;
+  if (c->counted_launches == 0) return GBMW_OK;
+  if (launch < -1 || launch >= c->counted_launches)
+    return fail(GBMW_ERR_INVALID_ARG, "launch=%d not in -1..%d", launch, c->counted_launches - 1);
+  std::vector<unsigned long long> h(4 * (size_t)c->counted_launches);
+  HIP_TRY(hipMemcpy(h.data(), c->d_counts.p, h.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost));
+  unsigned long long waves = 0, covered = 0;
+  for (int i = 0; i < c->counted_launches; ++i) {
+    if (launch >= 0 && i != launch) continue;
+    work[0] += h[4 * i]; work[1] += h[4 * i + 1]; work[2] += h[4 * i + 2];
+    covered += h[4 * i + 1] + h[4 * i + 2] + h[4 * i + 3];
+    waves += c->counted_waves[i];
+  }
+  work[3] = (waves - covered) * (uint64_t)c->S;
   return GBMW_OK;
 }
 

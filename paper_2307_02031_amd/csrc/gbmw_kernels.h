@@ -47,6 +47,12 @@ struct Tables {
   float* best;         // [B][EP]
   uint8_t* best_s;     // [B][EP]
   int* status;         // device word; bit 0: bad c, bit 1: bad M, bit 2: bad R
+  unsigned long long* counts;  // null, or four counters of the launch, for measurements: [0] workgroups
+                       // whose four waves shared one column (S * S' updates computed per workgroup)
+                       // and [3] the waves inside the table that those workgroups covered;
+                       // [1] waves recognised as a run from the summaries and [2] from the loaded
+                       // table values (S * S' updates per wave).  Every other wave inside the table
+                       // computed its 64 * S cells one by one
 };
 
 #if defined(__HIPCC__)
@@ -114,6 +120,8 @@ __device__ __forceinline__ int pred_strategy_wave(const Tables& t, int row, int 
 // caller's c / M (src_c, src_M) into the context's own arrays t.c / t.M where they differ.
 void launch_prepare(const Tables& t, const float* R, const float* src_c, const int* src_M, int sumL,
                     bool validate, hipStream_t st);
+// Zeroes n measurement counters (a fill kernel, not a memset node).
+void launch_clear_counts(unsigned long long* counts, int n, hipStream_t st);
 // C(0, e, s) written to the table for instances perm[first .. first + count).  Needed
 // where something reads layer 0 from memory: instances with L_b <= 2 (final reduce,
 // export), every instance when all layers are kept or S > 64.

@@ -90,6 +90,15 @@ __global__ __launch_bounds__(256) void k_validate_R(Tables t, const float* __res
 
 __global__ void k_clear_status(int* status) { *status = 0; }
 
+__global__ void k_clear_counts(unsigned long long* counts, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) counts[i] = 0;
+}
+
+void launch_clear_counts(unsigned long long* counts, int n, hipStream_t st) {
+  if (n > 0) hipLaunchKernelGGL(k_clear_counts, dim3((n + 255) / 256), dim3(256), 0, st, counts, n);
+}
+
 void launch_prepare(const Tables& t, const float* R, const float* src_c, const int* src_M, int sumL,
                     bool validate, hipStream_t st) {
   // a fill kernel rather than a memset node, so that the sequence can be captured
@@ -207,7 +216,7 @@ template <int SP, bool ARG>
 __device__ __forceinline__ void uniform_tile(const float colv, const float4* rt_lds, int s_begin,
                                              int s_end, int lane, int e0, int wbase, float* __restrict__ Cn,
                                              uint8_t* __restrict__ An, float* __restrict__ sum_cur, int E,
-                                             int EP) {
+                                             int EP, unsigned long long* cnt) {
   const int srow = (s_begin + lane < s_end) ? s_begin + lane : s_begin;   // idle lanes redo a valid row
   int outv, a;
   uniform_min<SP>(colv, rt_lds, srow, outv, a);
@@ -221,6 +230,7 @@ __device__ __forceinline__ void uniform_tile(const float colv, const float4* rt_
       __builtin_amdgcn_raw_buffer_store_b8((unsigned char)ar, ba, e0, 0, kStreaming);
     }
   }
+  if (cnt && lane == 0) atomicAdd(cnt, 1ull);             // measurement only, when nothing else is live
 }
 
 // The same for a whole workgroup whose four waves (256 budgets from `base`) all carry that one
@@ -231,7 +241,7 @@ template <int SP, bool ARG>
 __device__ __forceinline__ void wide_tile(const float colv, const float4* rt_lds, int s_begin, int s_end,
                                           int lane, int base, float* __restrict__ Cn,
                                           uint8_t* __restrict__ An, float* __restrict__ sum_cur, int E,
-                                          int EP) {
+                                          int EP, unsigned long long* cnt, int inside) {
   const int srow = (s_begin + lane < s_end) ? s_begin + lane : s_begin;
   int outv, a;
   uniform_min<SP>(colv, rt_lds, srow, outv, a);
@@ -249,14 +259,24 @@ __device__ __forceinline__ void wide_tile(const float colv, const float4* rt_lds
       __builtin_amdgcn_raw_buffer_store_b32(ar * 0x01010101u, ba, base + 4 * lane, 0, kStreaming);
     }
   }
+  if (cnt && threadIdx.x == 0) {                          // measurement only: workgroups, and their waves
+    atomicAdd(cnt, 1ull);
+    atomicAdd(cnt + 3, (unsigned long long)inside);
+  }
 }
 
 // RUNS: waves whose budgets share one input column take uniform_tile (never in split mode:
 // those launches are bound by a wave's own latency, which the test would lengthen).
-template <int SP, int K, int NW, int CH, int MINW, bool FIRST, bool ARG, bool SPLIT, bool RUNS>
+// COUNT: the same kernel with one atomic per run-path wave or workgroup into t.counts, for
+// measurements.  The paths a wave takes depend on the inputs alone, so the counts of this
+// instantiation are those of the plain one, which is the one that is timed (the atomics cost a
+// few registers, and with them occupancy at some sizes).
+template <int SP, int K, int NW, int CH, int MINW, bool FIRST, bool ARG, bool SPLIT, bool RUNS, bool COUNT = false>
 __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int tiles, int first) {
   constexpr bool split = SPLIT;
   static_assert(!(SPLIT && RUNS), "no run shortcut in split mode");
+  static_assert(RUNS || !COUNT, "only the run paths are counted");
+  unsigned long long* const counts = COUNT ? t.counts : nullptr;
   // With the run shortcut the waves that compute every cell are few and sit among waves that
   // hardly use the VALU: nothing hides the latency of their reads of the R tile, so they keep
   // PD quads of R in flight ahead of the fold, across the end of the row into the next one
@@ -417,19 +437,22 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
     __syncthreads();
     const float v0 = x_col[0][lane];
     bool same = true;
+    int inside = 0;
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
       const int st = x_ok[w];
       same = same && (st == 2 || (st == 1 && __float_as_int(x_col[w][lane]) == __float_as_int(v0)));
+      inside += (st != 2) ? 1 : 0;
     }
     if (__builtin_amdgcn_ballot_w64(!same) == 0) {
       wide_tile<SP, ARG>(v0, rt_lds, (wave * S) / NW, ((wave + 1) * S) / NW, lane, tile * NW * 64, Cn, An,
-                         sum_cur, E, EP);
+                         sum_cur, E, EP, counts, inside);
       return;
     }
     if (!present) return;
     if (mine) {
-      uniform_tile<SP, ARG>(v, rt_lds, s_begin, s_end, lane, e0, wbase, Cn, An, sum_cur, E, EP);
+      uniform_tile<SP, ARG>(v, rt_lds, s_begin, s_end, lane, e0, wbase, Cn, An, sum_cur, E, EP,
+                            counts ? counts + 1 : nullptr);
       return;
     }
   }
@@ -561,7 +584,8 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
         const int f = __builtin_amdgcn_readfirstlane(__float_as_int(cp[0][sp]));
         colv = (lane == sp) ? __int_as_float(f) : colv;
       }
-      uniform_tile<SP, ARG>(colv, rt_lds, s_begin, s_end, lane, e0, wbase, Cn, An, sum_cur, E, EP);
+      uniform_tile<SP, ARG>(colv, rt_lds, s_begin, s_end, lane, e0, wbase, Cn, An, sum_cur, E, EP,
+                            counts ? counts + 2 : nullptr);
       return;
     }
   }
@@ -822,6 +846,15 @@ static void launch_minplus_sp(const Tables& t_in, int l, int first, int n_active
   hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, MW, FIRST_, ARG_, SPLIT_, RUNS_>), grid, block, lds, st, t, l, \
                      tiles, first)
   const bool runs = t.runs != 0;
+  if (runs && !split && t.counts) {                      // the counting twin of the unsplit run-shortcut kernels
+#define GBMW_LAUNCH_COUNT(FIRST_, ARG_)                                                                      \
+  hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, 2, FIRST_, ARG_, false, true, true>), grid, block, lds, st, t, l, \
+                     tiles, first)
+    if (t.A == nullptr) { if (l == 1) GBMW_LAUNCH_COUNT(true, false); else GBMW_LAUNCH_COUNT(false, false); }
+    else { if (l == 1) GBMW_LAUNCH_COUNT(true, true); else GBMW_LAUNCH_COUNT(false, true); }
+#undef GBMW_LAUNCH_COUNT
+    return;
+  }
   if (t.A == nullptr) {
     constexpr int MW = Blocking<SP>::MINW_VALUES, MWR = Blocking<SP>::MINW_VALUES_RUNS;
     if (l == 1) {

@@ -646,6 +646,7 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
   t.Cbuf = (float*)c->d_C.p; t.A = lazy ? nullptr : (uint8_t*)c->d_A.p;
   t.best = (float*)c->d_best.p; t.best_s = (uint8_t*)c->d_best_s.p;
   t.status = (int*)c->d_status.p;
+  t.counts = nullptr;
   t.prev_full = 0;
 
   HIP_TRY_B(hipEventCreate(&ev0));

@@ -250,6 +250,44 @@ def test_device_inputs_may_be_overwritten_after_the_solve(g):
         g.gbmw_destroy(ctx)
 
 
+def test_work_counters_match_the_tables(g):
+    """GBMW_FLAG_COUNT_WORK: the number of (wave, strategy) rows that the launches report as
+    computed cell by cell is what the oracle's tables imply: a wave of 64 budgets escapes the
+    dense arithmetic exactly when the 64 columns of the previous layer's table that it reads are
+    the same bits (the kernel finds such waves from its summaries or, failing that, from the
+    loaded values), and the counted solve returns the same tables as the plain one."""
+    S, E = 9, 700 * 256 - 141
+    st = gi.Stream(9300)
+    parts = []
+    for i, L in enumerate([4, 3, 2]):
+        c = st.integers(L * S, 1, 6).astype(np.float32).reshape(L, S)
+        M = (st.integers(L * S, 0, 60) * (97 if i else 64)).reshape(L, S)
+        R = st.integers(L * S * S, 0, 3).astype(np.float32).reshape(L, S, S)
+        parts.append(gi.Problem(1, S, E, np.array([L]), c, M, R))
+    p = gi.stack(parts, "counters")
+    ctx = solve_gpu(p, flags=g.GBMW_FLAG_COUNT_WORK | g.GBMW_FLAG_KEEP_ALL_C, device_inputs=True)
+    wide, u1, u2, dense_rows = g.gbmw_last_solve_work(ctx)
+    waves = uniform = 0
+    nw = (E + 64) // 64
+    for b in range(p.B):
+        ref = check_instance(g, ctx, p, b, full_C=True, q_es=[0, E // 2, E])
+        for l in range(1, int(p.L[b])):
+            prev = ref.C[l - 1].view(np.uint32)                       # [E+1][S]
+            pad = np.concatenate([prev, np.repeat(prev[-1:], nw * 64 - (E + 1), axis=0)])
+            tiles = pad.reshape(nw, 64, S)
+            uniform += int(np.all(tiles == tiles[:, :1, :], axis=(1, 2)).sum())
+            waves += nw
+    assert dense_rows == (waves - uniform) * S, (wide, u1, u2, dense_rows, waves, uniform)
+    assert wide > 0 and u1 > 0 and dense_rows > 0
+    # a solve with dense arithmetic computes every row
+    ctx = solve_gpu(p, flags=g.GBMW_FLAG_COUNT_WORK | g.GBMW_FLAG_DENSE_ARITHMETIC, device_inputs=True, ctx=ctx)
+    assert g.gbmw_last_solve_work(ctx) == (0, 0, 0, waves * S)
+    # and without the flag nothing is counted
+    ctx = solve_gpu(p, flags=0, device_inputs=True, ctx=ctx)
+    assert g.gbmw_last_solve_work(ctx) == (0, 0, 0, 0)
+    g.gbmw_destroy(ctx)
+
+
 MODES = {"records": 0, "lazy-argmin": 16, "records-dense": 32, "lazy-argmin-dense": 48}
 
 
