@@ -87,7 +87,20 @@ enum {
                                   that took the shortcut above, for gbmw_last_solve_work
                                   (implies GBMW_FLAG_ONE_STREAM).  The counts depend on the
                                   inputs alone; the counting costs registers, so time the
-                                  kernels in a solve without this flag                    */
+                                  kernels in a solve without this flag                    */,
+  GBMW_FLAG_LAYER_LAUNCHES = 128u /* one launch per layer even for a small problem.
+                                  Default: a problem with S <= 64 whose tiles of 64 budgets
+                                  (ceil((E+1)/64) per instance) are all resident on the
+                                  device at once is filled by a single launch in which the
+                                  tiles hand their layers to each other through flags in
+                                  device memory.  Its waits are bounded: should one give up
+                                  (the device held by other work for seconds), the calls
+                                  that wait for the solve return GBMW_ERR_DEVICE and the
+                                  context holds no solution.  Identical results either way */,
+  GBMW_FLAG_TEST_WAIT_GIVES_UP = 256u /* testing: the waits of that single launch ask for a
+                                  layer that is never published and give up after 1 ms, so
+                                  that the error path can be exercised; every workgroup
+                                  still ends normally                                     */
 };
 
 #define GBMW_MAX_S 256

@@ -30,6 +30,8 @@ GBMW_FLAG_RESOLVE_ALL = 8
 GBMW_FLAG_LAZY_ARGMIN = 16
 GBMW_FLAG_DENSE_ARITHMETIC = 32
 GBMW_FLAG_COUNT_WORK = 64
+GBMW_FLAG_LAYER_LAUNCHES = 128
+GBMW_FLAG_TEST_WAIT_GIVES_UP = 256
 GBMW_MAX_S = 256
 GBMW_STATIC_SCRATCH_BYTES = 1 << 20
 

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgbmw.so")
-SOURCES = ["gbmw_kernels.hip", "gbmw_api.hip", "gbmw_partition.hip", "gbmw_strategy.hip"]
+SOURCES = ["gbmw_kernels.hip", "gbmw_persistent.hip", "gbmw_api.hip", "gbmw_partition.hip", "gbmw_strategy.hip"]
 HEADERS = ["gbmw_kernels.h", "gbmw_ctx.h", os.path.join("..", "..", "include", "gbmw.h")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -49,6 +49,21 @@ namespace {
 
 thread_local char g_err[512] = "";
 
+// Workgroups of the single-launch kernel that the current device holds at once, per (S, waves
+// per tile, records): asked once per process and variant (one device type per process is assumed).
+int resident_workgroups(int S, int waves, bool records) {
+  static std::mutex mu;
+  static int cache[GBMW_MAX_S + 1][2][2];
+  static bool known[GBMW_MAX_S + 1][2][2];
+  std::lock_guard<std::mutex> lock(mu);
+  const int w = waves == 8 ? 1 : 0, r = records ? 1 : 0;
+  if (!known[S][w][r]) {
+    cache[S][w][r] = gbmw::layers_resident_workgroups(S, waves, records);
+    known[S][w][r] = true;
+  }
+  return cache[S][w][r];
+}
+
 // Instance groups per solve (each on its own stream).  Two is where the gain
 // from overlapping one group's ramp-down with the other's launch saturates.
 constexpr int kGroups = 2;
@@ -81,7 +96,7 @@ void free_ctx(gbmw_ctx* c) {
   (void)hipStreamSynchronize(c->stream);
   for (DevBuf* b : {&c->d_L, &c->d_off, &c->d_perm, &c->d_c, &c->d_M, &c->d_R, &c->d_Rt, &c->d_C, &c->d_sum,
                     &c->d_A, &c->d_best, &c->d_best_s, &c->d_status, &c->d_q, &c->d_stage,
-                    &c->d_search, &c->d_gather, &c->d_counts})
+                    &c->d_search, &c->d_gather, &c->d_counts, &c->d_sync})
     b->release();
   if (c->ev0) (void)hipEventDestroy(c->ev0);
   if (c->ev1) (void)hipEventDestroy(c->ev1);
@@ -140,7 +155,18 @@ gbmw_status wait_and_check(gbmw_ctx* c) {
   HIP_TRY(hipSetDevice(c->device));
   HIP_TRY(hipStreamSynchronize(c->stream));
   int status = 0;
-  HIP_TRY(hipMemcpy(&status, c->d_status.p, sizeof(int), hipMemcpyDeviceToHost));
+  if (c->single_epoch != 0) {                              // the single-launch fill keeps epochs, not bits
+    unsigned long long w[5];
+    HIP_TRY(hipMemcpy(w, c->d_sync.p, sizeof(w), hipMemcpyDeviceToHost));
+    if (w[gbmw::kSyncGaveUp] == c->single_epoch)
+      return fail(GBMW_ERR_DEVICE, "the single-launch fill gave up waiting for a neighbouring tile (its workgroups "
+                                   "were not all running at once, or the device was held by other work for seconds); "
+                                   "the context holds no solution, solve again (GBMW_FLAG_LAYER_LAUNCHES avoids this path)");
+    status = (w[gbmw::kSyncBadC] == c->single_epoch ? 1 : 0) | (w[gbmw::kSyncBadM] == c->single_epoch ? 2 : 0) |
+             (w[gbmw::kSyncBadR] == c->single_epoch ? 4 : 0);
+  } else {
+    HIP_TRY(hipMemcpy(&status, c->d_status.p, sizeof(int), hipMemcpyDeviceToHost));
+  }
   if (status)
     return fail(GBMW_ERR_INVALID_ARG, "device inputs rejected:%s%s%s",
                 (status & 1) ? " c has NaN/negative values;" : "",
@@ -176,7 +202,8 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
   if (p->ptr_space != GBMW_PTR_HOST && p->ptr_space != GBMW_PTR_DEVICE)
     return fail(GBMW_ERR_INVALID_ARG, "ptr_space=%d", p->ptr_space);
   if (flags & ~(uint32_t)(GBMW_FLAG_KEEP_ALL_C | GBMW_FLAG_TIME_KERNELS | GBMW_FLAG_ONE_STREAM |
-                          GBMW_FLAG_LAZY_ARGMIN | GBMW_FLAG_DENSE_ARITHMETIC | GBMW_FLAG_COUNT_WORK))
+                          GBMW_FLAG_LAZY_ARGMIN | GBMW_FLAG_DENSE_ARITHMETIC | GBMW_FLAG_COUNT_WORK |
+                          GBMW_FLAG_LAYER_LAUNCHES | GBMW_FLAG_TEST_WAIT_GIVES_UP))
     return fail(GBMW_ERR_INVALID_ARG, "unknown flag bits 0x%x", flags);
 
   const int B = p->B, S = p->S, E = p->E;
@@ -204,7 +231,22 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
   // another's.
   const bool timed = (flags & GBMW_FLAG_TIME_KERNELS) != 0;
   const bool counting = (flags & GBMW_FLAG_COUNT_WORK) != 0;
-  int G = (timed || counting || (flags & GBMW_FLAG_ONE_STREAM)) ? 1 : kGroups;
+  // A problem whose tiles of 64 budgets are all resident at once is filled by ONE launch in
+  // which every tile walks the layers itself (gbmw_persistent.hip) instead of one launch per
+  // layer: those launches would be bound by their own latency.
+  const int tiles64 = (E + 64) / 64;
+  int single_waves = 0;                                  // waves per tile of the single launch; 0: layer launches
+  if (S <= 64 && Lmax < (1 << 19) && !timed && !counting && (flags & GBMW_FLAG_LAYER_LAUNCHES) == 0) {
+    const bool records = (flags & GBMW_FLAG_LAZY_ARGMIN) == 0;
+    // eight waves per tile where that fits (a wave then has an eighth of the strategies to itself)
+    // (up to 44 strategies: beyond, a wave's registers do not allow two workgroups per compute unit)
+    if (S >= 16 && S <= 44 && (long long)tiles64 * B <= (long long)resident_workgroups(S, 8, records)) single_waves = 8;
+    else if ((long long)tiles64 * B <= (long long)resident_workgroups(S, 4, records)) single_waves = 4;
+  }
+  const bool single = single_waves != 0;
+  if ((flags & GBMW_FLAG_TEST_WAIT_GIVES_UP) && !single)
+    return fail(GBMW_ERR_INVALID_ARG, "GBMW_FLAG_TEST_WAIT_GIVES_UP needs a problem that takes the single-launch path");
+  int G = (timed || counting || single || (flags & GBMW_FLAG_ONE_STREAM)) ? 1 : kGroups;
   if (G > B) G = B;
   std::vector<int> grouped, gfirst(G + 1, 0);
   for (int g = 0; g < G; ++g) {
@@ -269,11 +311,19 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
   TRY(c->d_Rt.reserve(sizeof(float) * (size_t)sumL * S * RS));
   TRY(c->d_C.reserve(sizeof(float) * slab * (keep ? (size_t)sumL : (size_t)2 * B)));
   // the run shortcut and its summaries exist for the register-blocked kernels (S <= 64)
-  const bool runs = (flags & GBMW_FLAG_DENSE_ARITHMETIC) == 0 && gbmw::layer0_in_registers(S);
+  const bool runs = (flags & GBMW_FLAG_DENSE_ARITHMETIC) == 0 && gbmw::layer0_in_registers(S) && !single;
   if (runs) TRY(c->d_sum.reserve(sizeof(float) * ((size_t)S * (EP / 64)) * (keep ? (size_t)sumL : (size_t)2 * B)));
   if (!lazy) TRY(c->d_A.reserve(slab * (size_t)sumL));
   TRY(c->d_best.reserve(sizeof(float) * (size_t)B * EP));
   TRY(c->d_best_s.reserve((size_t)B * EP));
+  if (single) {
+    // the synchronisation words of the single launch; new memory starts at zero, and since epochs
+    // only grow nothing is ever cleared again
+    const size_t words = (size_t)gbmw::kSyncHeader + (size_t)sumL + (size_t)B * tiles64;
+    const size_t before = c->d_sync.cap;
+    TRY(c->d_sync.reserve(words * sizeof(unsigned long long)));
+    if (c->d_sync.cap != before) HIP_TRY_B(hipMemsetAsync(c->d_sync.p, 0, c->d_sync.cap, (hipStream_t)p->stream));
+  }
   if (!c->ev0) {
     HIP_TRY_B(hipEventCreate(&c->ev0));
     HIP_TRY_B(hipEventCreate(&c->ev1));
@@ -338,6 +388,27 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
   TRY(gbmw_detail::ensure_streams(c, G));
 
   if (counting) gbmw::launch_clear_counts((unsigned long long*)c->d_counts.p, 4 * Lmax, st);
+  c->single_epoch = 0;
+  if (single) {
+    gbmw::PersistArgs a{};
+    a.sync = (unsigned long long*)c->d_sync.p;
+    a.epoch = ++c->epoch;
+    a.src_c = src_c; a.src_M = src_M; a.R = dR;
+    const bool give_up = (flags & GBMW_FLAG_TEST_WAIT_GIVES_UP) != 0;
+    a.wait_ticks = give_up ? 100000 : 200000000;         // 1 ms : 2 s at 100 MHz
+    a.wait_polls = give_up ? 2000 : 4000000;
+    a.sumL = sumL; a.validate = p->ptr_space == GBMW_PTR_DEVICE ? 1 : 0;
+    a.tiles = tiles64; a.n_slots = B; a.first = 0;
+    a.extra_wait = give_up ? 1 : 0;
+    HIP_TRY_B(hipEventRecord(c->ev0, st));
+    HIP_TRY_B(gbmw::launch_layers(t, a, single_waves, st));
+    HIP_TRY_B(hipEventRecord(c->ev1, st));
+    HIP_TRY_B(hipGetLastError());
+    c->single_epoch = a.epoch;
+    c->solved = true;
+    *out = c;
+    return GBMW_OK;
+  }
   HIP_TRY_B(hipEventRecord(c->ev0, st));
   gbmw::launch_prepare(t, dR, src_c, src_M, sumL, p->ptr_space == GBMW_PTR_DEVICE, st);
   {

@@ -162,6 +162,28 @@ void launch_export_u8(const uint8_t* src, uint8_t* dst, int n, int S, int E, int
 // The argmin records of one table row, [S][EP] bytes, recomputed from the kept tables.
 void launch_argmin_row(const Tables& t, int row, uint8_t* dst, hipStream_t st);
 
+// ---- the single-launch fill of small problems (gbmw_persistent.hip)
+// Words of the context's synchronisation block (unsigned long long each).  The header words
+// hold the epoch of the solve that set them; then one word per table row (its R tile is
+// transposed: holds the epoch), then one per (instance slot, tile): epoch << 20 | layers done.
+// Epochs only grow, so a word left by an earlier solve never satisfies a later one.
+constexpr int kSyncBadC = 0, kSyncBadM = 1, kSyncBadR = 2, kSyncGaveUp = 3, kSyncLeave = 4, kSyncHeader = 8;
+struct PersistArgs {
+  unsigned long long* sync;     // device, kSyncHeader + sumL + n_slots * tiles words
+  unsigned long long epoch;     // of this solve, >= 1, < 2^43
+  const float* src_c;           // the caller's c / M / R on the device (or the context's uploads)
+  const int* src_M;
+  const float* R;
+  long long wait_ticks;         // bound of every wait, in ticks of the constant 100 MHz clock
+  int wait_polls;               // and in polls
+  int sumL, validate, tiles, n_slots, first;
+  int extra_wait;               // testing: every wait asks for a layer that is never published
+};
+// Workgroups of the single-launch kernel with `waves` (4 or 8) waves per tile that the device
+// holds at once (0: no such kernel).
+int layers_resident_workgroups(int S, int waves, bool records);
+hipError_t launch_layers(const Tables& t, const PersistArgs& a, int waves, hipStream_t st);
+
 const char* minplus_variant(int S);
 
 }  // namespace gbmw

@@ -20,11 +20,14 @@ def _log(msg):
     print(msg, flush=True)
 
 
+@pytest.mark.parametrize("launches", ["single-launch", "layer-launches"])
 @pytest.mark.parametrize("k", [1, 2, 3])
-def test_single_configs_full_tables(g, k):
+def test_single_configs_full_tables(g, k, launches):
+    """cfg1-3 through both ways of filling a small problem: the single launch in which the tiles
+    hand their layers to each other (default), and one launch per layer."""
     p = gi.make_config(k)
-    _log(f"config {k}: {p.name}")
-    ctx = solve_gpu(p, flags=g.GBMW_FLAG_KEEP_ALL_C)
+    _log(f"config {k}: {p.name} {launches}")
+    ctx = solve_gpu(p, flags=g.GBMW_FLAG_KEEP_ALL_C | (g.GBMW_FLAG_LAYER_LAUNCHES if launches == "layer-launches" else 0))
     q = None if k > 1 else list(range(p.E + 1))
     check_instance(g, ctx, p, 0, full_C=True, q_es=q)
     g.gbmw_destroy(ctx)
@@ -73,15 +76,30 @@ SHAPES = [  # (S, E, list of L): ragged tails, tile boundaries, every kernel var
 
 
 @pytest.mark.parametrize("S,E,Ls", SHAPES, ids=[f"S{s}-E{e}" for s, e, _ in SHAPES])
-@pytest.mark.parametrize("device_inputs,lazy", [(False, False), (True, False), (True, True)],
-                         ids=["host", "device", "device-lazy-argmin"])
-def test_ragged_batches_all_shapes(g, S, E, Ls, device_inputs, lazy):
-    _log(f"S={S} E={E} L={Ls} device_inputs={device_inputs} lazy={lazy}")
+@pytest.mark.parametrize("device_inputs,lazy,extra", [(False, False, 0), (True, False, 0), (True, True, 0),
+                                                      (True, False, 128), (True, True, 128), (True, False, "roll")],
+                         ids=["host", "device", "device-lazy-argmin", "device-layer-launches",
+                              "device-lazy-argmin-layer-launches", "device-rolling-tables"])
+def test_ragged_batches_all_shapes(g, S, E, Ls, device_inputs, lazy, extra):
+    """Small batches: by default one launch for the whole fill (S <= 64), with
+    GBMW_FLAG_LAYER_LAUNCHES (128) one launch per layer; with all tables kept and (rolling) with
+    the rolling pair, where a tile also has to wait for the readers of the table it overwrites."""
+    _log(f"S={S} E={E} L={Ls} device_inputs={device_inputs} lazy={lazy} extra={extra}")
+    if extra == "roll":
+        Mhi = max(2, E // 3 + 1)
+        parts = [gi.random_instance(1000 + 17 * S + i, L + 3, S, E, M_rng=(0 if E == 0 else 1, Mhi),
+                                    R_rng=(0.0, 4.0)) for i, L in enumerate(Ls)]
+        p = gi.stack(parts, f"S{S}E{E}roll")
+        ctx = solve_gpu(p, flags=0, device_inputs=True)
+        for b in range(p.B):
+            check_instance(g, ctx, p, b, full_C=False, q_es=list(range(0, E + 1, max(1, E // 40))) + [E])
+        g.gbmw_destroy(ctx)
+        return
     Mhi = max(2, E // 3 + 1)
     parts = [gi.random_instance(1000 + 17 * S + i, L, S, E, M_rng=(0 if E == 0 else 1, Mhi),
                                 R_rng=(0.0, 4.0)) for i, L in enumerate(Ls)]
     p = gi.stack(parts, f"S{S}E{E}")
-    ctx = solve_gpu(p, flags=g.GBMW_FLAG_LAZY_ARGMIN if lazy else g.GBMW_FLAG_KEEP_ALL_C,
+    ctx = solve_gpu(p, flags=(g.GBMW_FLAG_LAZY_ARGMIN if lazy else g.GBMW_FLAG_KEEP_ALL_C) | int(extra),
                     device_inputs=device_inputs)
     for b in range(p.B):
         check_instance(g, ctx, p, b, full_C=True, q_es=list(range(0, E + 1, max(1, E // 40))) + [E])
@@ -285,6 +303,31 @@ def test_work_counters_match_the_tables(g):
     # and without the flag nothing is counted
     ctx = solve_gpu(p, flags=0, device_inputs=True, ctx=ctx)
     assert g.gbmw_last_solve_work(ctx) == (0, 0, 0, 0)
+    g.gbmw_destroy(ctx)
+
+
+def test_single_launch_wait_gives_up_cleanly(g):
+    """The single-launch fill's waits are bounded.  With GBMW_FLAG_TEST_WAIT_GIVES_UP they ask for a
+    layer that no tile ever publishes and give up after a millisecond: every workgroup ends, the
+    solve's waiting calls report GBMW_ERR_DEVICE, and the same context solves correctly afterwards."""
+    import torch
+    p = gi.stack([gi.random_instance(5100 + i, L, 12, 3000, M_rng=(1, 500)) for i, L in enumerate([5, 3])], "give-up")
+    ctx = solve_gpu(p, flags=g.GBMW_FLAG_KEEP_ALL_C, device_inputs=True)
+    check_instance(g, ctx, p, 0, full_C=True)
+    c = torch.from_numpy(p.c).cuda(); M = torch.from_numpy(p.M).cuda(); R = torch.from_numpy(p.R).cuda()
+    ctx = g.gbmw_dp_solve_batched(p.L, c, M, R, p.S, p.E, flags=g.GBMW_FLAG_KEEP_ALL_C | g.GBMW_FLAG_TEST_WAIT_GIVES_UP, ctx=ctx)
+    for call in (lambda: g.gbmw_synchronize(ctx), lambda: g.gbmw_get_best(ctx), lambda: g.gbmw_backtrack(ctx, [0], [p.E])):
+        with pytest.raises(g.GbmwError) as ei:
+            call()
+        assert ei.value.status == g.GBMW_ERR_DEVICE and "gave up" in str(ei.value)
+    ctx = solve_gpu(p, flags=g.GBMW_FLAG_KEEP_ALL_C, device_inputs=True, ctx=ctx)
+    for b in range(p.B):
+        check_instance(g, ctx, p, b, full_C=True)
+    # a problem too large for the single launch refuses the test flag instead of ignoring it
+    big = gi.random_instance(5200, 2, 4, 400000, M_rng=(1, 9))
+    with pytest.raises(g.GbmwError) as ei:
+        g.gbmw_dp_solve_batched(big.L, big.c, big.M, big.R, big.S, big.E, flags=g.GBMW_FLAG_TEST_WAIT_GIVES_UP)
+    assert ei.value.status == g.GBMW_ERR_INVALID_ARG
     g.gbmw_destroy(ctx)
 
 
