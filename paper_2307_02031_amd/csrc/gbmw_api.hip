@@ -300,7 +300,12 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
   c->L = L; c->off = off; c->perm = perm;
   const int SP = c->SP, EP = c->EP;
   const bool lazy = (flags & GBMW_FLAG_LAZY_ARGMIN) != 0;
-  const bool keep = lazy || (flags & GBMW_FLAG_KEEP_ALL_C) != 0;
+  // The single launch keeps every layer's table where that is cheap (a small problem by
+  // definition): with a rolling pair a tile also has to wait for the readers of the table it
+  // overwrites, which ties the tiles to the slowest one.  What gbmw_export_tables hands out
+  // still follows the flags.
+  const bool keep = lazy || (flags & GBMW_FLAG_KEEP_ALL_C) != 0 ||
+                    (single && sizeof(float) * (size_t)S * ((E + 1 + 255) / 256 * 256) * (size_t)sumL <= ((size_t)1 << 30));
   const size_t slab = (size_t)S * EP;
 
   TRY(c->d_L.reserve(sizeof(int) * B));
@@ -694,7 +699,7 @@ gbmw_status gbmw_export_tables(gbmw_ctx* c, int32_t inst, int32_t l0, int32_t l1
   if (st != GBMW_OK) return st;
   for (int l = l0; l < l1; ++l) {
     if (C) {
-      const size_t tab = keep ? (size_t)(row0 + l) : (size_t)(l & 1) * c->B + inst;   // as c_table / sum_table
+      const size_t tab = c->t.keep_all ? (size_t)(row0 + l) : (size_t)(l & 1) * c->B + inst;   // as c_table / sum_table
       const float* src = (const float*)c->d_C.p + tab * slab;
       const float* sum = c->t.Tsum ? c->t.Tsum + tab * (S * (c->EP >> 6)) : nullptr;
       gbmw::launch_export_c(c->t, src, sum, c->t.M + (size_t)(row0 + l) * S, (float*)c->d_stage.p, c->stream);

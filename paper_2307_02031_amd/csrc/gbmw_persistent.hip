@@ -80,17 +80,17 @@ __device__ __forceinline__ int max_shift(const int* __restrict__ Mrow, int S, in
   return m;
 }
 
-// Wave 0 of a workgroup waits until every word prog[lo..hi] has reached `target` and (if
-// prep != null) *prep holds the epoch.  Returns false if it gave up (recorded in the header) or
-// was told to leave.  Bounded by ticks of the constant 100 MHz clock and by polls.
+// Wave 0 of a workgroup waits until every word prog[lo..hi] has reached `target`.  Returns false
+// if it gave up (recorded in the header) or was told to leave.  Bounded by ticks of the constant
+// 100 MHz clock and by polls.  (Two samples in flight half a round trip apart, tried, change
+// nothing: what a tile waits for is its neighbours' stores on their way through the memory side.)
 __device__ bool wait_for(const PersistArgs& a, const unsigned long long* prog, int lo, int hi,
-                         unsigned long long target, const unsigned long long* prep, int lane) {
+                         unsigned long long target, int lane) {
   const long long t0 = (long long)wall_clock64();
   int polls = 0;
   for (;;) {
     bool ok = true;
     for (int k = lo + lane; k <= hi; k += 64) ok = ok && load_word(prog + k) >= target;
-    if (prep) ok = ok && load_word(prep) == a.epoch;
     const bool leave = load_word(a.sync + kSyncLeave) == a.epoch;
     if (__builtin_amdgcn_ballot_w64(!ok) == 0) return true;
     if (__builtin_amdgcn_ballot_w64(leave) != 0) return false;
@@ -146,7 +146,6 @@ template <int SP, int NW, bool ARG>
 __global__ __launch_bounds__(64 * NW, (NW >= 8 && SP <= 44) ? 4 : 2) void k_layers(Tables t, PersistArgs a) {
   constexpr int CH = 3;                                  // candidates per chunk minimum
   constexpr int NC = (SP + CH - 1) / CH;                 // chunks (the last may be short)
-  constexpr int NP = NC / 2 + 1;                         // prefix minima / blocks
   constexpr int RS = (SP + 2 + 3) / 4 * 4;
   constexpr int RQ = RS / 4;
   constexpr int NSTG = (SP * RQ * 2 + 64 * NW - 1) / (64 * NW);   // 8-byte words of the R tile per thread
@@ -179,7 +178,7 @@ __global__ __launch_bounds__(64 * NW, (NW >= 8 && SP <= 44) ? 4 : 2) void k_laye
   // ... and waits until all of them are there (once; the rows are few and done at once)
   if (Lb >= 2) {
     if (wave == 0) {
-      const bool ok = wait_for(a, prep + row0, 1, Lb - 1, a.epoch, nullptr, lane);
+      const bool ok = wait_for(a, prep + row0, 1, Lb - 1, a.epoch, lane);
       if (lane == 0) go = ok ? 1 : 0;
     }
     __syncthreads();
@@ -219,7 +218,7 @@ __global__ __launch_bounds__(64 * NW, (NW >= 8 && SP <= 44) ? 4 : 2) void k_laye
         const int lo = tile - (mprev + 63) / 64;
         const int hi = t.keep_all ? tile : tile + (63 + mcur) / 64;
         const bool ok = wait_for(a, prog, lo < 0 ? 0 : lo, hi > a.tiles - 1 ? a.tiles - 1 : hi,
-                                 base + (unsigned)(l - 1) + never, nullptr, lane);
+                                 base + (unsigned)(l - 1) + never, lane);
         mprev = mcur;
         if (lane == 0) go = ok ? 1 : 0;
       }
@@ -272,7 +271,7 @@ __global__ __launch_bounds__(64 * NW, (NW >= 8 && SP <= 44) ? 4 : 2) void k_laye
     uint8_t* __restrict__ An = ARG ? t.A + (size_t)row * S * EP : nullptr;
 #pragma unroll 1
     for (int s = s_begin; s < s_end; ++s) {
-      float x[SP], P[NP], cm_odd = INFINITY;
+      float x[SP], cm[NC];
 #pragma unroll
       for (int q = 0; q < SP / 4; ++q) {
         const float4 v = rt_lds[s * RQ + q];
@@ -280,20 +279,15 @@ __global__ __launch_bounds__(64 * NW, (NW >= 8 && SP <= 44) ? 4 : 2) void k_laye
         x[4 * q + 2] = cp[4 * q + 2] + v.z; x[4 * q + 3] = cp[4 * q + 3] + v.w;
       }
       const float4 tail = rt_lds[s * RQ + SP / 4];       // c(l,s), bits of M(l,s)
-      // chunk minima of three, prefix minima over pairs of chunks (see k_minplus)
+      // chunk minima of three candidates, then their minimum T: one add and half a min per candidate
 #pragma unroll
       for (int c = 0; c < NC; ++c) {
-        const int lo = c * CH, hi = ((c + 1) * CH < SP) ? (c + 1) * CH : SP, len = hi - lo;
-        const float cmv = len == 3 ? fmin3(x[lo], x[lo + 1], x[lo + 2]) : len == 2 ? __builtin_fminf(x[lo], x[lo + 1]) : x[lo];
-        if (c == 0) P[0] = cmv;
-        else if (c % 2 == 1) {
-          cm_odd = cmv;
-          if (c == NC - 1) P[(c + 1) / 2] = __builtin_fminf(P[(c - 1) / 2], cm_odd);
-        } else {
-          P[c / 2] = fmin3(P[c / 2 - 1], cm_odd, cmv);
-        }
+        const int lo = c * CH, len = ((c + 1) * CH < SP ? (c + 1) * CH : SP) - lo;
+        cm[c] = len == 3 ? fmin3(x[lo], x[lo + 1], x[lo + 2]) : len == 2 ? __builtin_fminf(x[lo], x[lo + 1]) : x[lo];
       }
-      const float T = P[NP - 1];
+      float T = cm[0];
+#pragma unroll
+      for (int c = 1; c < NC; c += 2) T = (c + 1 < NC) ? fmin3(T, cm[c], cm[c + 1]) : __builtin_fminf(T, cm[c]);
       const float cs = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(tail.x)));
       const int m_raw = __builtin_amdgcn_readfirstlane(__float_as_int(tail.y));
       const int m = (m_raw < 0 || m_raw > E + 1) ? E + 1 : m_raw;
@@ -301,29 +295,20 @@ __global__ __launch_bounds__(64 * NW, (NW >= 8 && SP <= 44) ? 4 : 2) void k_laye
       const __amdgpu_buffer_rsrc_t bc = __builtin_amdgcn_make_buffer_rsrc(Cs, 0, (E + 1) * 4, kBufWord3);
       const __amdgpu_buffer_rsrc_t binf = __builtin_amdgcn_make_buffer_rsrc(Cs, 0, m * 4, kBufWord3);
       if (ARG) {
-        // lowest-index minimiser: in the first block whose prefix minimum equals T (P_k == T is
-        // monotone in k); only blocks that some lane first hits are scanned, against the kept sums
-        int arg = 0;
-        bool prev = false;
-        unsigned long long prevm = 0;
+        // Lowest-index minimiser without a branch (a wave is nearly alone on its SIMD here, and a
+        // taken branch costs it more than the selects): going down the chunks, the lowest chunk whose
+        // minimum equals T leaves its index and its first two sums behind; the minimiser is the
+        // first of the chunk's (at most three) sums that equals T.  Same sums, same bits.
+        int cidx = NC - 1;
+        float a0 = x[(NC - 1) * CH], a1 = ((NC - 1) * CH + 1 < SP) ? x[(NC - 1) * CH + 1] : INFINITY;
 #pragma unroll
-        for (int k = 0; k < NP; ++k) {
-          const bool eq = (k == NP - 1) ? true : (P[k] == T);
-          const unsigned long long eqm = (k == NP - 1) ? ~0ull : __builtin_amdgcn_ballot_w64(eq);
-          if ((eqm & ~prevm) != 0) {
-            if (eq && !prev) {
-              const int clo = (k == 0) ? 0 : 2 * k - 1;
-              const int chi = (k == 0) ? 1 : ((2 * k + 1 < NC) ? 2 * k + 1 : NC);
-              const int lo = clo * CH, hi = (chi * CH < SP) ? chi * CH : SP;
-              int av = hi - 1;
-#pragma unroll
-              for (int i = hi - 2; i >= lo; --i) av = (x[i] == T) ? i : av;
-              arg = av;
-            }
-          }
-          prev = eq;
-          prevm = eqm;
+        for (int c = NC - 2; c >= 0; --c) {
+          const bool eq = cm[c] == T;
+          cidx = eq ? c : cidx;
+          a0 = eq ? x[c * CH] : a0;
+          a1 = eq ? x[c * CH + 1] : a1;
         }
+        const int arg = cidx * CH + (a0 == T ? 0 : a1 == T ? 1 : 2);
         const __amdgpu_buffer_rsrc_t ba = __builtin_amdgcn_make_buffer_rsrc(An + (size_t)s * EP, 0, EP, kBufWord3);
         __builtin_amdgcn_raw_buffer_store_b8((unsigned char)arg, ba, e0, 0, 0);
       }
@@ -341,7 +326,7 @@ __global__ __launch_bounds__(64 * NW, (NW >= 8 && SP <= 44) ? 4 : 2) void k_laye
   if (Lb >= 2) {
     if (wave == 0) {
       const int lo = tile - (mprev + 63) / 64;
-      const bool ok = wait_for(a, prog, lo < 0 ? 0 : lo, tile, base + (unsigned)(Lb - 1) + never, nullptr, lane);
+      const bool ok = wait_for(a, prog, lo < 0 ? 0 : lo, tile, base + (unsigned)(Lb - 1) + never, lane);
       if (lane == 0) go = ok ? 1 : 0;
     }
     __syncthreads();

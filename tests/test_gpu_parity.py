@@ -331,6 +331,20 @@ def test_single_launch_wait_gives_up_cleanly(g):
     g.gbmw_destroy(ctx)
 
 
+def test_single_launch_with_a_rolling_pair_of_tables(g):
+    """The single launch keeps every layer's table only up to 1 GiB of them; beyond, it works on a
+    rolling pair and a tile also waits for the tiles above it, whose input it is about to
+    overwrite.  136 layers of 64 strategies over 512 tiles (1.06 GiB of tables): records, last
+    tables, best and plans against the oracle."""
+    E = 512 * 64 - 1
+    p = gi.random_instance(5300, 136, 64, E, M_rng=(1, 480), R_rng=(0.0, 4.0))
+    ctx = solve_gpu(p, flags=0, device_inputs=True)
+    check_instance(g, ctx, p, 0, full_C=False, q_es=[0, 1000, E // 4, E // 2, E - 1, E])
+    with pytest.raises(g.GbmwError):
+        g.gbmw_export_tables(ctx, 0, 0, 5)
+    g.gbmw_destroy(ctx)
+
+
 MODES = {"records": 0, "lazy-argmin": 16, "records-dense": 32, "lazy-argmin-dense": 48}
 
 
