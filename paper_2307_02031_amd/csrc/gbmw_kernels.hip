@@ -1011,9 +1011,53 @@ __global__ __launch_bounds__(64) void k_backtrack(Tables t, int nq, const int* _
   mem_used[q] = mem;
 }
 
+// The same walk without argmin records: every step has to redo the minimum over the S
+// predecessors from the kept table of the layer below, so a whole wave takes one query, its
+// lanes over the predecessors (pred_strategy_wave), and lane 0 writes the plan.
+__global__ __launch_bounds__(256) void k_backtrack_wave(Tables t, int nq, const int* __restrict__ q_inst,
+                                                        const int* __restrict__ q_e, int Lmax,
+                                                        uint8_t* __restrict__ plan, float* __restrict__ cost,
+                                                        int* __restrict__ mem_used) {
+  const int q = blockIdx.x * 4 + (threadIdx.x >> 6);      // wave-uniform
+  const int lane = threadIdx.x & 63;
+  if (q >= nq) return;
+  const int inst = q_inst[q];
+  int e = q_e[q];
+  uint8_t* p = plan + (size_t)q * Lmax;
+  const int Lb = t.L[inst];
+  const float b = t.best[(size_t)inst * t.EP + e];
+  if (b == INFINITY) {
+    for (int l = lane; l < Lmax; l += 64) p[l] = 0xFF;
+    if (lane == 0) { cost[q] = b; mem_used[q] = -1; }
+    return;
+  }
+  for (int l = Lb + lane; l < Lmax; l += 64) p[l] = 0xFF;
+  int s = t.best_s[(size_t)inst * t.EP + e];
+  const int row0 = t.off[inst];
+  int mem = 0;
+  for (int l = Lb - 1; l >= 1; --l) {
+    if (lane == 0) p[l] = (uint8_t)s;
+    const int m = t.M[(size_t)(row0 + l) * t.S + s];
+    mem += m;
+    e -= m;                                              // budget left for layers < l
+    if (m < 0 || e < 0) { mem = -2; break; }             // only reachable with invalid inputs
+    s = pred_strategy_wave(t, row0 + l, s, e, lane);
+  }
+  if (mem != -2) {
+    if (lane == 0) p[0] = (uint8_t)s;
+    mem += t.M[(size_t)row0 * t.S + s];
+  }
+  if (lane == 0) { cost[q] = b; mem_used[q] = mem; }
+}
+
 void launch_backtrack(const Tables& t, int nq, const int* q_inst, const int* q_e, int Lmax,
                       uint8_t* plan, float* cost, int* mem_used, hipStream_t st) {
   if (nq <= 0) return;
+  if (t.A == nullptr) {
+    hipLaunchKernelGGL(k_backtrack_wave, dim3((nq + 3) / 4), dim3(256), 0, st, t, nq, q_inst, q_e, Lmax, plan, cost,
+                       mem_used);
+    return;
+  }
   hipLaunchKernelGGL(k_backtrack, dim3((nq + 63) / 64), dim3(64), 0, st, t, nq, q_inst, q_e, Lmax,
                      plan, cost, mem_used);
 }

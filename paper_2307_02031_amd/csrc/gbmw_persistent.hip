@@ -8,9 +8,9 @@
 // axis: the min-plus product of tile j reads column entries C(l-1, e, .) of its OWN budgets
 // only, and those were written, shifted by M(l-1, s), by the tiles at or below j within
 // max_s M(l-1, s) budgets.  So there is no grid-wide barrier: every tile publishes the number
-// of layers it has finished in a word of its own (plain store with release semantics, single
-// writer), and a tile about to start layer l polls the words of the tiles in its window until
-// all of them show l - 1:
+// of layers it has finished in a word of its own (one store, single writer, once its table
+// stores are acknowledged), and a tile about to start layer l polls the words of the tiles in
+// its window until all of them show l - 1:
 //   - below:  tiles j - ceil(max_s M(l-1,s) / 64) .. j   (their stores make up my input)
 //   - above:  tiles j .. j + (63 + max_s M(l,s)) / 64    (rolling pair of tables only: my
 //             stores of layer l overwrite layer l - 2, which those tiles read in step l - 1)
