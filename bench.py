@@ -401,8 +401,9 @@ def main():
     if not args.no_others:
         others = {}
         ceiling = PEAK_PLAIN_FP32_TOPS * 1e12 / OPS_PER_UPDATE       # updates/s at 2 plain lane-ops per update
-        wide = gi.random_instance(128, 12, 128, 32768, M_rng=(64, 1024), R_rng=(0.0, 5.0))
-        wide.name = "S=128 (above the register-blocked range): L=12, E=32768, c~U[1,10), M~U{64..1024}, R~U[0,5)"
+        wide = gi.stack([gi.random_instance(128 + i, 8, 128, 32768, M_rng=(64, 1024), R_rng=(0.0, 5.0))
+                         for i in range(16)], "S128")
+        wide.name = "S=128 (upper end of the register-blocked range): B=16, L=8, E=32768, c~U[1,10), M~U{64..1024}, R~U[0,5)"
         for k in (1, 2, 3, 5, "S128"):
             if k == args.config:
                 continue

@@ -406,7 +406,7 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
   const bool true_sum = RUNS ? true : (SPLIT ? t.runs == 2 : false);
   float* __restrict__ sum_cur = want_sum ? sum_table(t, inst, row, l) : nullptr;
   if (RUNS) {
-    static_assert(K == 1 && SP <= 64, "one budget per lane, one lane per strategy");
+    static_assert(!RUNS || (K == 1 && SP <= 64), "one budget per lane, one lane per strategy");
     const int e_last = wbase + n_in - 1;
     bool ok = true;
     float v = INFINITY;
@@ -429,7 +429,7 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
     const bool mine = __builtin_amdgcn_ballot_w64(!ok) == 0;
     // Do all waves of the workgroup (those inside the table) carry the same one column?  Each
     // publishes its verdict and its column, and every wave forms the same answer from them.
-    static_assert(NW == 4, "four waves share their columns");
+    static_assert(!RUNS || NW == 4, "four waves share their columns");
     __shared__ float x_col[NW][64];
     __shared__ int x_ok[NW];
     x_col[wave][lane] = v;
@@ -765,7 +765,7 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
     sum_cur[(size_t)(s_begin + lane) * (EP >> 6) + (wbase >> 6)] = __int_as_float(sumv);
 }
 
-// Any S up to 256: the C_{l-1} tile of 64 budgets is staged in LDS as
+// Any S up to 256 (used above 128): the C_{l-1} tile of 64 budgets is staged in LDS as
 // [S][64]; wave w handles output strategies w, w+4, ...
 __global__ __launch_bounds__(256) void k_minplus_generic(Tables t, int l, int tiles, int first) {
   extern __shared__ float lds[];
@@ -804,17 +804,20 @@ __global__ __launch_bounds__(256) void k_minplus_generic(Tables t, int l, int ti
 template <int SP>
 struct Blocking {                       // budgets per lane for a given strategy count
   static constexpr int K = 1;
-  static constexpr int NW = 4;
+  // waves per workgroup.  Beyond 64 strategies the R tile takes 20 to 68 KB of LDS, so that one or
+  // two workgroups fit a compute unit: they are made large enough to bring the waves per SIMD
+  // that the registers allow (4 up to 96 strategies, 3 up to 128)
+  static constexpr int NW = (SP <= 64) ? 4 : (SP <= 96) ? 8 : 12;
   static constexpr int CH = 3;          // candidates per chunk minimum
   // waves per SIMD the register allocation must allow: SP live table values plus about 20
   // working registers out of 512 (the value pass streams the R row and keeps only the
   // prefix minima; the candidate sums are not kept)
-  static constexpr int MINW = (SP <= 44) ? 8 : (SP <= 56) ? 6 : 5;
+  static constexpr int MINW = (SP <= 44) ? 8 : (SP <= 56) ? 6 : (SP <= 64) ? 5 : (SP <= 96) ? 4 : 3;
   static constexpr int MINW_SPLIT = 4;
   // the layer-1 variant builds layer 0 from c and M and needs a few registers more
   static constexpr int MINW_FIRST = (SP > 40 && SP <= 44) ? 7 : MINW;
   // without the argmin pass: the SP table values plus about 16 working registers
-  static constexpr int MINW_VALUES = (SP <= 44) ? 8 : (SP <= 52) ? 7 : (SP <= 60) ? 6 : 5;
+  static constexpr int MINW_VALUES = (SP <= 44) ? 8 : (SP <= 52) ? 7 : (SP <= 60) ? 6 : (SP <= 64) ? 5 : (SP <= 96) ? 4 : 3;
   // with the run shortcut compiled in: the summaries, the exchange, the second look at the
   // loaded columns and (up to 56 strategies) four quads of R in flight ahead of the fold (see
   // PRE in the kernel) take a few registers more; targets found by compiling every size.  The
@@ -881,6 +884,24 @@ static void launch_minplus_sp(const Tables& t_in, int l, int first, int n_active
 #undef GBMW_LAUNCH
 }
 
+// 65 to 128 strategies: the same register-blocked kernel, every lane with its S' table values
+// in registers (148 to 168 of them at 128 strategies: three waves per SIMD), in larger workgroups
+// (see Blocking::NW).  No run shortcut, no split shape, layer 0 read from memory.
+template <int SP>
+static void launch_minplus_big(const Tables& t, int l, int first, int n_active, hipStream_t st) {
+  constexpr int NW = Blocking<SP>::NW, CH = Blocking<SP>::CH;
+  const int tiles = (t.E + 1 + 64 * NW - 1) / (64 * NW);
+  constexpr int RS = (SP + 2 + 3) / 4 * 4;
+  const dim3 grid((unsigned)tiles * n_active), block(64 * NW);
+  const size_t lds = (size_t)t.S * RS * sizeof(float);
+  if (t.A == nullptr)
+    hipLaunchKernelGGL((k_minplus<SP, 1, NW, CH, Blocking<SP>::MINW_VALUES, false, false, false, false>), grid, block, lds,
+                       st, t, l, tiles, first);
+  else
+    hipLaunchKernelGGL((k_minplus<SP, 1, NW, CH, Blocking<SP>::MINW, false, true, false, false>), grid, block, lds, st, t,
+                       l, tiles, first);
+}
+
 void launch_minplus(const Tables& t, int l, int first, int n_active, hipStream_t st, int n_prev) {
   if (n_active <= 0) return;
   switch (t.SP) {
@@ -888,6 +909,13 @@ void launch_minplus(const Tables& t, int l, int first, int n_active, hipStream_t
     GBMW_CASE(4) GBMW_CASE(8) GBMW_CASE(12) GBMW_CASE(16) GBMW_CASE(20) GBMW_CASE(24)
     GBMW_CASE(28) GBMW_CASE(32) GBMW_CASE(36) GBMW_CASE(40) GBMW_CASE(44) GBMW_CASE(48)
     GBMW_CASE(52) GBMW_CASE(56) GBMW_CASE(60) GBMW_CASE(64)
+#undef GBMW_CASE
+  // (a launch of fewer waves than the chip has SIMDs is better off with the generic kernel below,
+  // whose waves divide the output strategies: four times the waves)
+#define GBMW_CASE(N) case N: if ((long long)((t.E + 64) / 64) * n_active < 1024) break; launch_minplus_big<N>(t, l, first, n_active, st); return;
+    GBMW_CASE(68) GBMW_CASE(72) GBMW_CASE(76) GBMW_CASE(80) GBMW_CASE(84) GBMW_CASE(88)
+    GBMW_CASE(92) GBMW_CASE(96) GBMW_CASE(100) GBMW_CASE(104) GBMW_CASE(108) GBMW_CASE(112)
+    GBMW_CASE(116) GBMW_CASE(120) GBMW_CASE(124) GBMW_CASE(128)
 #undef GBMW_CASE
     default: break;
   }
@@ -903,8 +931,8 @@ bool launch_is_split(const Tables& t, int n_active) {
 }
 
 const char* minplus_variant(int S) {
-  return S <= 64 ? "register-blocked, LDS-staged R tile, prefix-min value pass + on-demand argmin rescan"
-                 : "generic LDS-staged (S > 64)";
+  return S <= 128 ? "register-blocked, LDS-staged R tile, prefix-min value pass + on-demand argmin rescan"
+                  : "generic LDS-staged (S > 128)";
 }
 
 // ---------------------------------------------------------------------------

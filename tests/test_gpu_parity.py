@@ -69,8 +69,11 @@ SHAPES = [  # (S, E, list of L): ragged tails, tile boundaries, every kernel var
     (55, 1025, [2, 4]),
     (58, 800, [4, 2]),
     (64, 1500, [4, 6]),
-    (65, 500, [3, 2]),       # above 64: LDS-staged generic kernel
+    (65, 500, [3, 2]),       # 65..128: register-blocked in larger workgroups (8 or 12 waves)
     (100, 300, [3]),
+    (97, 1700, [3, 2]),
+    (128, 2000, [2, 4]),
+    (129, 300, [3]),         # above 128: LDS-staged generic kernel
     (256, 130, [2, 3]),
 ]
 
@@ -127,6 +130,34 @@ def test_wide_launches_every_instantiation(g, S, lazy):
     best, best_s = g.gbmw_get_best(ctx)
     for b in (0, 4, 9):
         check_instance(g, ctx, p, b, full_C=False, q_es=[0, 1, E // 2, E - 1, E], best=best, best_s=best_s)
+    for b in range(p.B):
+        ref = oracle.solve_problem(p, b, keep_C=False, keep_A=False, nthreads=16)
+        pins.assert_same_f32(best[b], ref.best, f"wide-S{S}[{b}] best")
+        assert np.array_equal(best_s[b], ref.best_s)
+    g.gbmw_destroy(ctx)
+
+
+@pytest.mark.parametrize("lazy", [False, True], ids=["records", "lazy-argmin"])
+@pytest.mark.parametrize("S", [65, 68, 83, 96, 97, 113, 128])
+def test_wide_launches_above_64_strategies(g, S, lazy):
+    """65 to 128 strategies in launches of at least 1024 waves take the register-blocked kernel in
+    workgroups of eight or twelve waves (smaller launches and larger S the generic one): seven
+    instances of 2 or 3 layers, a ragged last workgroup, integer costs (ties everywhere), every
+    table cell of three instances and the best rows of all against the oracle."""
+    E = 12000 + S
+    _log(f"wide S={S} lazy={lazy}")
+    st = gi.Stream(6500 + S)
+    parts = []
+    for i, L in enumerate([3, 3, 3, 3, 3, 3, 2]):
+        c = st.integers(L * S, 1, 4).astype(np.float32).reshape(L, S)
+        M = st.integers(L * S, 0, E // 2).reshape(L, S)
+        R = st.integers(L * S * S, 0, 2).astype(np.float32).reshape(L, S, S)
+        parts.append(gi.Problem(1, S, E, np.array([L]), c, M, R))
+    p = gi.stack(parts, f"wide-S{S}")
+    ctx = solve_gpu(p, flags=g.GBMW_FLAG_LAZY_ARGMIN if lazy else g.GBMW_FLAG_KEEP_ALL_C, device_inputs=True)
+    best, best_s = g.gbmw_get_best(ctx)
+    for b in (0, 3, 6):
+        check_instance(g, ctx, p, b, full_C=True, q_es=[0, 1, E // 2, E - 1, E], best=best, best_s=best_s)
     for b in range(p.B):
         ref = oracle.solve_problem(p, b, keep_C=False, keep_A=False, nthreads=16)
         pins.assert_same_f32(best[b], ref.best, f"wide-S{S}[{b}] best")
