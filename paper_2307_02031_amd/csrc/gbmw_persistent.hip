@@ -163,6 +163,8 @@ __global__ __launch_bounds__(64 * NW, (NW >= 8 && SP <= 44) ? 4 : 2) void k_laye
   const int lane = threadIdx.x & 63;
   const int wbase = tile * 64, e0 = wbase + lane;
   const int s_begin = (wave * S) / NW, s_end = ((wave + 1) * S) / NW;
+  const int n_tile = (E - wbase + 1 < 64) ? E - wbase + 1 : 64;   // budgets of the tile inside the table
+  const bool thin = n_tile <= 8;
   unsigned long long* const prep = a.sync + kSyncHeader;                     // [sumL]
   unsigned long long* const prog = prep + a.sumL + (size_t)slot * a.tiles;   // [tiles] of this instance
   const unsigned long long base = a.epoch << 20;
@@ -230,7 +232,7 @@ __global__ __launch_bounds__(64 * NW, (NW >= 8 && SP <= 44) ? 4 : 2) void k_laye
     }
 
     // ---- the tile's table values: every wave fetches a share of the columns for all of them
-    if (l >= 2) {
+    if (l >= 2 && !thin) {
       const float* __restrict__ Cp = c_table(t, inst, row - 1, l - 1);
       float col[NCOL];
 #pragma unroll
@@ -253,6 +255,46 @@ __global__ __launch_bounds__(64 * NW, (NW >= 8 && SP <= 44) ? 4 : 2) void k_laye
       }
     }
     __syncthreads();
+    float* __restrict__ Cn = c_table(t, inst, row, l);
+    uint8_t* __restrict__ An = ARG ? t.A + (size_t)row * S * EP : nullptr;
+    if (thin) {
+      // A last tile of a few budgets (E + 1 just above a multiple of 64) would cost its compute
+      // unit, which it shares with another tile, a whole tile's arithmetic for nearly nothing.
+      // Its budgets are computed one by one instead, with the lanes over the OUTPUT strategies:
+      // lane s folds min_s' (C_{l-1}[e][s'] + R[s'][s]) in index order with a strict compare (the
+      // lowest minimiser, 0 if all are +inf), then adds c(l, s).  Same operands, same bits.
+      const float* __restrict__ Cp = c_table(t, inst, row - 1, l - 1);
+      const int srow = lane < S ? lane : 0;
+      for (int b = wave; b < n_tile; b += NW) {
+        const int e = wbase + b;
+        float colv = INFINITY;                             // lane s': C_{l-1}[e][s']
+        if (lane < S) {
+          if (l == 1) { const int mv = m0[lane]; colv = (mv >= 0 && e >= mv) ? c0[lane] : INFINITY; }
+          else colv = load_shared(&Cp[(size_t)lane * EP + e]);
+        }
+        float best = INFINITY;
+        int arg = 0;
+#pragma unroll
+        for (int q = 0; q < SP / 4; ++q) {
+          const float4 v = rt_lds[srow * RQ + q];
+          const float rq[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+          for (int i4 = 0; i4 < 4; ++i4) {
+            const float f = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(colv), 4 * q + i4));
+            const float x = f + rq[i4];
+            if (x < best) { best = x; arg = 4 * q + i4; }
+          }
+        }
+        const float4 tl = rt_lds[srow * RQ + SP / 4];      // c(l, s) and the bits of M(l, s), per lane
+        if (lane < S) {
+          const int m_raw = __float_as_int(tl.y);
+          const int m = (m_raw < 0 || m_raw > E + 1) ? E + 1 : m_raw;
+          if (ARG) An[(size_t)lane * EP + e] = (uint8_t)arg;
+          if (m <= E - e) store_shared(&Cn[(size_t)lane * EP + e + m], best + tl.x);
+          if (e < m) store_shared(&Cn[(size_t)lane * EP + e], INFINITY);
+        }
+      }
+    } else {
     float cp[SP];
     if (l == 1) {
 #pragma unroll
@@ -267,8 +309,6 @@ __global__ __launch_bounds__(64 * NW, (NW >= 8 && SP <= 44) ? 4 : 2) void k_laye
       for (int sp = 0; sp < SP; ++sp) cp[sp] = cp_lds[sp * 64 + lane];
     }
 
-    float* __restrict__ Cn = c_table(t, inst, row, l);
-    uint8_t* __restrict__ An = ARG ? t.A + (size_t)row * S * EP : nullptr;
 #pragma unroll 1
     for (int s = s_begin; s < s_end; ++s) {
       float x[SP], cm[NC];
@@ -314,6 +354,8 @@ __global__ __launch_bounds__(64 * NW, (NW >= 8 && SP <= 44) ? 4 : 2) void k_laye
       }
       __builtin_amdgcn_raw_buffer_store_b32((unsigned)__float_as_int(T + cs), bc, (e0 + m) * 4, 0, kDeviceScope);
       if (wbase < m) __builtin_amdgcn_raw_buffer_store_b32(0x7f800000u, binf, e0 * 4, 0, kDeviceScope);
+    }
+
     }
 
     // ---- publish: this tile has finished layer l
