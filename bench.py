@@ -137,7 +137,8 @@ def kernel_roofline(g, torch, p, d, args, flags, step_sec):
     tname = f"k_minplus_cfg{args.config}_hbm_traffic.txt"
     tpath = os.path.join(ROOT, "profiles", tname)
     if os.path.exists(tpath):
-        key = "hbm_bytes_per_launch_dense:" if dense else "hbm_bytes_per_launch:"
+        key = ("hbm_bytes_per_launch_dense:" if dense else "hbm_bytes_per_launch:" if records
+               else "hbm_bytes_per_launch_lazy:")
         for line in open(tpath):
             if line.startswith(key):
                 traffic = int(line.split(":")[1])
