@@ -352,6 +352,12 @@ def main():
         g.gbmw_destroy(dctx)
         dr = kernel_roofline(g, torch, p, d, args, dflags, dsec)
         out["dense_arithmetic"] = dict(dr, ms_per_step=dsec * 1e3, value=nominal / dsec, value_executed=executed / dsec)
+        # the VALU fraction of the min-plus kernel when it executes every update of the batched config
+        out["roofline"]["frac_with_every_update_executed"] = dr["frac"]
+        out["roofline"]["frac_with_every_update_executed_is"] = (
+            "roofline.frac of the same solve under GBMW_FLAG_DENSE_ARITHMETIC (object dense_arithmetic): the default "
+            "mode's run shortcut executes one update in shortcut_gain, so its launches are short and bound by "
+            "neither roofline")
     # The same solve without argmin records (GBMW_FLAG_LAZY_ARGMIN): every layer's fp32 table
     # is kept and the walkers recompute the records they need.  Reported beside the headline,
     # never as it: the headline path materialises every record.

@@ -97,6 +97,14 @@ enum {
                                   (the device held by other work for seconds), the calls
                                   that wait for the solve return GBMW_ERR_DEVICE and the
                                   context holds no solution.  Identical results either way */,
+  GBMW_FLAG_COOPERATIVE_LAUNCH = 512u /* that single launch goes through the cooperative
+                                  launch API, which starts a kernel only when all its
+                                  workgroups fit on the device at once (about 15 us more per
+                                  solve).  For callers that run several solves, or other
+                                  kernels, concurrently on one device: with the plain
+                                  launch (default) two such kernels that each hold a part of
+                                  the device would wait for tiles that cannot start, until
+                                  their waits give up                                     */,
   GBMW_FLAG_TEST_WAIT_GIVES_UP = 256u /* testing: the waits of that single launch ask for a
                                   layer that is never published and give up after 1 ms, so
                                   that the error path can be exercised; every workgroup

@@ -32,6 +32,7 @@ GBMW_FLAG_DENSE_ARITHMETIC = 32
 GBMW_FLAG_COUNT_WORK = 64
 GBMW_FLAG_LAYER_LAUNCHES = 128
 GBMW_FLAG_TEST_WAIT_GIVES_UP = 256
+GBMW_FLAG_COOPERATIVE_LAUNCH = 512
 GBMW_MAX_S = 256
 GBMW_STATIC_SCRATCH_BYTES = 1 << 20
 

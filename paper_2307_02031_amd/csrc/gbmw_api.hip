@@ -203,7 +203,7 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
     return fail(GBMW_ERR_INVALID_ARG, "ptr_space=%d", p->ptr_space);
   if (flags & ~(uint32_t)(GBMW_FLAG_KEEP_ALL_C | GBMW_FLAG_TIME_KERNELS | GBMW_FLAG_ONE_STREAM |
                           GBMW_FLAG_LAZY_ARGMIN | GBMW_FLAG_DENSE_ARITHMETIC | GBMW_FLAG_COUNT_WORK |
-                          GBMW_FLAG_LAYER_LAUNCHES | GBMW_FLAG_TEST_WAIT_GIVES_UP))
+                          GBMW_FLAG_LAYER_LAUNCHES | GBMW_FLAG_TEST_WAIT_GIVES_UP | GBMW_FLAG_COOPERATIVE_LAUNCH))
     return fail(GBMW_ERR_INVALID_ARG, "unknown flag bits 0x%x", flags);
 
   const int B = p->B, S = p->S, E = p->E;
@@ -406,7 +406,7 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
     a.tiles = tiles64; a.n_slots = B; a.first = 0;
     a.extra_wait = give_up ? 1 : 0;
     HIP_TRY_B(hipEventRecord(c->ev0, st));
-    HIP_TRY_B(gbmw::launch_layers(t, a, single_waves, st));
+    HIP_TRY_B(gbmw::launch_layers(t, a, single_waves, (flags & GBMW_FLAG_COOPERATIVE_LAUNCH) != 0, st));
     HIP_TRY_B(hipEventRecord(c->ev1, st));
     HIP_TRY_B(hipGetLastError());
     c->single_epoch = a.epoch;

@@ -182,7 +182,7 @@ struct PersistArgs {
 // Workgroups of the single-launch kernel with `waves` (4 or 8) waves per tile that the device
 // holds at once (0: no such kernel).
 int layers_resident_workgroups(int S, int waves, bool records);
-hipError_t launch_layers(const Tables& t, const PersistArgs& a, int waves, hipStream_t st);
+hipError_t launch_layers(const Tables& t, const PersistArgs& a, int waves, bool cooperative, hipStream_t st);
 
 const char* minplus_variant(int S);
 

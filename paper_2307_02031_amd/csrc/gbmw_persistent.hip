@@ -444,12 +444,16 @@ int layers_resident_workgroups(int S, int waves, bool records) {
   return cus * per_cu;
 }
 
-hipError_t launch_layers(const Tables& t, const PersistArgs& a, int waves, hipStream_t st) {
+hipError_t launch_layers(const Tables& t, const PersistArgs& a, int waves, bool cooperative, hipStream_t st) {
   const void* k = layers_kernel(t.SP, waves, t.A != nullptr);
   if (!k || (waves != 4 && waves != 8)) return hipErrorInvalidValue;
   Tables tt = t;
   PersistArgs aa = a;
   void* args[] = {&tt, &aa};
+  // the cooperative launch API starts the kernel only when all its workgroups fit at once
+  if (cooperative)
+    return hipLaunchCooperativeKernel(k, dim3((unsigned)a.tiles * a.n_slots), dim3(64 * waves), args,
+                                      (unsigned)layers_lds_bytes(t.S), st);
   return hipLaunchKernel(k, dim3((unsigned)a.tiles * a.n_slots), dim3(64 * waves), args, layers_lds_bytes(t.S), st);
 }
 

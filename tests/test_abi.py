@@ -68,7 +68,7 @@ def test_argument_errors_are_reported_without_a_device():
     assert status(_problem(g, [2], c, M, R, 3, -1)) == g.GBMW_ERR_INVALID_ARG       # E < 0
     assert status(_problem(g, [0], c, M, R, 3, 10)) == g.GBMW_ERR_INVALID_ARG       # L < 1
     assert status(_problem(g, [2], c, M, R, 3, 10, space=7)) == g.GBMW_ERR_INVALID_ARG
-    assert status(_problem(g, [2], c, M, R, 3, 10), flags=512) == g.GBMW_ERR_INVALID_ARG
+    assert status(_problem(g, [2], c, M, R, 3, 10), flags=2048) == g.GBMW_ERR_INVALID_ARG
     bad = c.copy(); bad[1, 2] = np.nan
     assert status(_problem(g, [2], bad, M, R, 3, 10)) == g.GBMW_ERR_INVALID_ARG
     assert "c[5]" in g.gbmw_last_error()

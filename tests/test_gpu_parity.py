@@ -20,14 +20,16 @@ def _log(msg):
     print(msg, flush=True)
 
 
-@pytest.mark.parametrize("launches", ["single-launch", "layer-launches"])
+@pytest.mark.parametrize("launches", ["single-launch", "single-launch-cooperative", "layer-launches"])
 @pytest.mark.parametrize("k", [1, 2, 3])
 def test_single_configs_full_tables(g, k, launches):
     """cfg1-3 through both ways of filling a small problem: the single launch in which the tiles
     hand their layers to each other (default), and one launch per layer."""
     p = gi.make_config(k)
     _log(f"config {k}: {p.name} {launches}")
-    ctx = solve_gpu(p, flags=g.GBMW_FLAG_KEEP_ALL_C | (g.GBMW_FLAG_LAYER_LAUNCHES if launches == "layer-launches" else 0))
+    extra = {"single-launch": 0, "single-launch-cooperative": g.GBMW_FLAG_COOPERATIVE_LAUNCH,
+             "layer-launches": g.GBMW_FLAG_LAYER_LAUNCHES}[launches]
+    ctx = solve_gpu(p, flags=g.GBMW_FLAG_KEEP_ALL_C | extra)
     q = None if k > 1 else list(range(p.E + 1))
     check_instance(g, ctx, p, 0, full_C=True, q_es=q)
     g.gbmw_destroy(ctx)
