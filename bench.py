@@ -121,15 +121,18 @@ def kernel_roofline(g, torch, p, d, args, flags, step_sec):
     # HBM bytes by path (the R tile of a workgroup, S x (S'+2) floats, is re-read from the L2 and left out):
     #   dense row (wave, s): 64 x 4 B of the previous table read (not in the layer-1 launch), 64 x 4 B of
     #     the new table and 64 x 1 B of records written, one summary word
-    #   run wave: per strategy M and two summary words read (12 B), 64 record bytes and one summary word
-    #     written; if it was recognised only from the loaded values it has read its 64 x 4 B per strategy too
-    #   run workgroup (4 waves): 4 x the reads, 256 record bytes and four summary words per strategy
+    #     (with the run shortcut also the byte that says the group's records are in A)
+    #   run wave: per strategy M and two summary words read (12 B), one summary word and one record byte
+    #     for the group written; if it was recognised only from the loaded values it has read its 64 x 4 B
+    #     per strategy too
+    #   run workgroup (4 waves): 4 x the reads, four summary words and four record bytes per strategy
     rec = 1 if records else 0
     sumw = 0 if dense else 4
+    grp = rec if not dense else 0
     read_b = write_b = 0
     for i, w in enumerate(work):
         read_b += w[3] * (256 if i > 0 else 0) + (w[1] + w[2] + 4 * w[0]) * 12 * S + (w[2] * 256 * S if i > 0 else 0)
-        write_b += w[3] * (256 + 64 * rec + sumw) + (w[1] + w[2]) * S * (64 * rec + 4) + w[0] * S * (256 * rec + 16)
+        write_b += w[3] * (256 + 64 * rec + sumw + grp) + (w[1] + w[2]) * S * (rec + 4) + w[0] * S * (4 * rec + 16)
     avg_launch_s = mp_ms / mp_n * 1e-3 if mp_n else float("nan")
     ach = OPS_PER_UPDATE * upd_exec / n_launch / avg_launch_s / 1e12 if mp_n else 0.0
     hbm_model = (read_b + write_b) / n_launch if n_launch else 0.0

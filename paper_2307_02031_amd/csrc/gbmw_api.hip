@@ -96,7 +96,7 @@ void free_ctx(gbmw_ctx* c) {
   (void)hipStreamSynchronize(c->stream);
   for (DevBuf* b : {&c->d_L, &c->d_off, &c->d_perm, &c->d_c, &c->d_M, &c->d_R, &c->d_Rt, &c->d_C, &c->d_sum,
                     &c->d_A, &c->d_best, &c->d_best_s, &c->d_status, &c->d_q, &c->d_stage,
-                    &c->d_search, &c->d_gather, &c->d_counts, &c->d_sync})
+                    &c->d_search, &c->d_gather, &c->d_counts, &c->d_sync, &c->d_asum})
     b->release();
   if (c->ev0) (void)hipEventDestroy(c->ev0);
   if (c->ev1) (void)hipEventDestroy(c->ev1);
@@ -319,6 +319,8 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
   const bool runs = (flags & GBMW_FLAG_DENSE_ARITHMETIC) == 0 && gbmw::layer0_in_registers(S) && !single;
   if (runs) TRY(c->d_sum.reserve(sizeof(float) * ((size_t)S * (EP / 64)) * (keep ? (size_t)sumL : (size_t)2 * B)));
   if (!lazy) TRY(c->d_A.reserve(slab * (size_t)sumL));
+  // with both, one record per group of 64 budgets where the group's 64 are equal (Tables::Asum)
+  if (!lazy && runs) TRY(c->d_asum.reserve((size_t)S * (EP / 64) * (size_t)sumL));
   TRY(c->d_best.reserve(sizeof(float) * (size_t)B * EP));
   TRY(c->d_best_s.reserve((size_t)B * EP));
   if (single) {
@@ -373,6 +375,7 @@ gbmw_status gbmw_detail::solve_batched(const gbmw_problem* p, uint32_t flags, gb
   t.L = (const int*)c->d_L.p; t.off = (const int*)c->d_off.p; t.perm = (const int*)c->d_perm.p;
   t.c = dc; t.M = dM; t.Rt = (const float*)c->d_Rt.p;
   t.Cbuf = (float*)c->d_C.p; t.A = lazy ? nullptr : (uint8_t*)c->d_A.p;
+  t.Asum = (!lazy && runs) ? (uint8_t*)c->d_asum.p : nullptr;
   t.best = (float*)c->d_best.p; t.best_s = (uint8_t*)c->d_best_s.p;
   t.status = (int*)c->d_status.p;
   t.prev_full = 0;
@@ -714,7 +717,7 @@ gbmw_status gbmw_export_tables(gbmw_ctx* c, int32_t inst, int32_t l0, int32_t l1
         memset(dst, 0, rows * S);
       } else {
         const uint8_t* src = (const uint8_t*)c->d_A.p + (size_t)(row0 + l) * slab;
-        if (lazy) {                                      // the records of this row, recomputed
+        if (lazy || c->t.Asum) {                         // the records of this row, recomputed or put together
           st = c->d_q.reserve(slab);
           if (st != GBMW_OK) return st;
           gbmw::launch_argmin_row(c->t, row0 + l, (uint8_t*)c->d_q.p, c->stream);

@@ -69,7 +69,7 @@ struct gbmw_ctx {
   bool h_M_valid = false;                    // filled at the solve for host inputs, on first use else
   gbmw::Tables t{};
   gbmw_detail::DevBuf d_L, d_off, d_perm, d_c, d_M, d_R, d_Rt, d_C, d_sum, d_A, d_best, d_best_s, d_status,
-      d_q, d_stage, d_search, d_gather, d_counts, d_sync;
+      d_q, d_stage, d_search, d_gather, d_counts, d_sync, d_asum;
   hipEvent_t ev0 = nullptr, ev1 = nullptr, ev_fork = nullptr;
   std::vector<hipStream_t> aux;              // extra streams for instance groups
   std::vector<hipEvent_t> ev_join;

@@ -3,7 +3,8 @@
 //
 // Device data layout ("SoA by strategy", budget axis contiguous):
 //   C table of one (instance, layer):  float  [S][EP]   C[s*EP + e]
-//   A table of one (instance, layer):  uint8  [S][EP]   A[s*EP + e']
+//   A table of one (instance, layer):  uint8  [S][EP]   A[s*EP + e']   (with the run shortcut one byte
+//       per group of 64 budgets stands for the group's 64 records where they are equal: Tables::Asum)
 //   EP = (E + 1) rounded up to a multiple of 256 (row stride in elements)
 //   Rt: transposed, padded transformation cost with the layer's own cost and
 //       memory riding along:  float [sumL][S][RS],  Rt[row][s][s'] = R[row][s'][s]
@@ -44,6 +45,12 @@ struct Tables {
                        // launch when runs != 0; null when runs == 0.  Where the word is a number the
                        // table's cells of that group (at e = e' + M) may be unwritten; where it is
                        // NaN they are written
+  uint8_t* Asum;       // [sumL][S][EP/64], beside A when runs != 0, else null: the record of a whole
+                       // group of 64 budgets e' where one record holds for all of them (the groups whose
+                       // summary word in Tsum is a number: equal input columns give equal minimisers),
+                       // kNoGroupRecord where the group's records are in A.  Every launch that writes
+                       // records writes this byte for every group it covers, and the 64 bytes of A only
+                       // for the groups it marks kNoGroupRecord
   float* best;         // [B][EP]
   uint8_t* best_s;     // [B][EP]
   int* status;         // device word; bit 0: bad c, bit 1: bad M, bit 2: bad R
@@ -73,12 +80,25 @@ __device__ __forceinline__ float table_cell(const Tables& t, const float* __rest
   return is_nan_bits(__float_as_int(w)) ? Ctab[(size_t)s * t.EP + e] : w;
 }
 
+// Marks a group of 64 budgets whose records are in A (strategy indices with the run shortcut
+// stay below 64).
+constexpr int kNoGroupRecord = 0xff;
+
+// The argmin record of table row `row`, strategy s, budget e' = e (t.A != null).  Both bytes are
+// asked for at once (the one in A may never have been written; it is then not used).
+__device__ __forceinline__ int record(const Tables& t, int row, int s, int e) {
+  const int own = t.A[((size_t)row * t.S + s) * t.EP + e];
+  if (t.Asum == nullptr) return own;
+  const int group = t.Asum[((size_t)row * t.S + s) * (t.EP >> 6) + (e >> 6)];
+  return group == kNoGroupRecord ? own : group;
+}
+
 // Predecessor strategy of table row `row` (layer l >= 1 of some instance) under strategy s
 // when e units are left for the layers below: the recorded one, or, where records are not
 // kept, recomputed from the kept table of layer l - 1 with the recurrence's own arithmetic
 // ((C + R), lowest index among equals, 0 if every candidate is +inf).
 __device__ __forceinline__ int pred_strategy(const Tables& t, int row, int s, int e) {
-  if (t.A) return t.A[((size_t)row * t.S + s) * t.EP + e];
+  if (t.A) return record(t, row, s, e);
   const float* __restrict__ Cp = t.Cbuf + (size_t)(row - 1) * t.S * t.EP;
   const float* __restrict__ Tp = t.Tsum ? t.Tsum + (size_t)(row - 1) * t.S * (t.EP >> 6) : nullptr;
   const int* __restrict__ Mp = t.M + (size_t)(row - 1) * t.S;
@@ -96,7 +116,7 @@ __device__ __forceinline__ int pred_strategy(const Tables& t, int row, int s, in
 // the same answer): without records the lanes take the candidates s' = lane, lane + 64, ...
 // and the minimum with its lowest index is found by a butterfly over the wave.
 __device__ __forceinline__ int pred_strategy_wave(const Tables& t, int row, int s, int e, int lane) {
-  if (t.A) return t.A[((size_t)row * t.S + s) * t.EP + e];
+  if (t.A) return record(t, row, s, e);
   const float* __restrict__ Cp = t.Cbuf + (size_t)(row - 1) * t.S * t.EP;
   const float* __restrict__ Tp = t.Tsum ? t.Tsum + (size_t)(row - 1) * t.S * (t.EP >> 6) : nullptr;
   const int* __restrict__ Mp = t.M + (size_t)(row - 1) * t.S;

@@ -29,6 +29,11 @@ __device__ __forceinline__ float* sum_table(const Tables& t, int inst, int row, 
 }
 
 
+// The group records of table row `row`: [S][EP / 64] bytes (null without them).
+__device__ __forceinline__ uint8_t* group_records(const Tables& t, int row) {
+  return t.Asum ? t.Asum + (size_t)row * t.S * (t.EP >> 6) : nullptr;
+}
+
 __device__ __forceinline__ float* c_table(const Tables& t, int inst, int row, int l) {
   const size_t slab = (size_t)t.S * t.EP;
   return t.keep_all ? t.Cbuf + (size_t)row * slab
@@ -181,7 +186,8 @@ __device__ __forceinline__ float fmin3(float a, float b, float c) {
 // order) and adds c.  Same operands and operations per cell as the dense path, hence the same
 // bits.  The value goes into the layer's summary word of that group and strategy and nowhere
 // else: the 64 cells of the fp32 table stay unwritten, every reader takes the word where it is
-// a number (table_cell).  Only the argmin records go out to the 64 budgets.
+// a number (table_cell).  The argmin record, one for the 64 budgets as well, goes into the
+// group's byte of the row's group records (Tables::Asum) and the 64 bytes of A stay unwritten.
 template <int SP>
 __device__ __forceinline__ void uniform_min(const float colv, const float4* rt_lds, int srow, int& outv,
                                             int& a) {
@@ -215,32 +221,26 @@ __device__ __forceinline__ void uniform_min(const float colv, const float4* rt_l
 template <int SP, bool ARG>
 __device__ __forceinline__ void uniform_tile(const float colv, const float4* rt_lds, int s_begin,
                                              int s_end, int lane, int e0, int wbase, float* __restrict__ Cn,
-                                             uint8_t* __restrict__ An, float* __restrict__ sum_cur, int E,
+                                             uint8_t* __restrict__ Ag, float* __restrict__ sum_cur, int E,
                                              int EP, unsigned long long* cnt) {
   const int srow = (s_begin + lane < s_end) ? s_begin + lane : s_begin;   // idle lanes redo a valid row
   int outv, a;
   uniform_min<SP>(colv, rt_lds, srow, outv, a);
   // the layer's own summary: every strategy's 64 cells are equal
   if (s_begin + lane < s_end) sum_cur[(size_t)(s_begin + lane) * (EP >> 6) + (wbase >> 6)] = __int_as_float(outv);
-  // the summary word stands for the 64 cells: only the records are written out
-  if (ARG) {
-    for (int s = s_begin; s < s_end; ++s) {
-      const int ar = __builtin_amdgcn_readlane(a, s - s_begin);
-      const __amdgpu_buffer_rsrc_t ba = __builtin_amdgcn_make_buffer_rsrc(An + (size_t)s * EP, 0, EP, kBufWord3);
-      __builtin_amdgcn_raw_buffer_store_b8((unsigned char)ar, ba, e0, 0, kStreaming);
-    }
-  }
+  // the summary word stands for the 64 cells, and one byte for their 64 records
+  if (ARG && s_begin + lane < s_end) Ag[(size_t)(s_begin + lane) * (EP >> 6) + (wbase >> 6)] = (uint8_t)a;
   if (cnt && lane == 0) atomicAdd(cnt, 1ull);             // measurement only, when nothing else is live
 }
 
 // The same for a whole workgroup whose four waves (256 budgets from `base`) all carry that one
 // column: the waves divide the output strategies instead of the budgets; each writes the four
-// summary words of its strategies and, with records, covers all 256 budgets of a strategy with
-// one store (lane i: one dword of four equal bytes for budgets base + 4 i .. 4 i + 3).
+// summary words of its strategies and, with records, the four group records (one dword: EP is
+// a multiple of 256, so a row of group records is whole dwords and `base >> 6` a multiple of 4).
 template <int SP, bool ARG>
 __device__ __forceinline__ void wide_tile(const float colv, const float4* rt_lds, int s_begin, int s_end,
                                           int lane, int base, float* __restrict__ Cn,
-                                          uint8_t* __restrict__ An, float* __restrict__ sum_cur, int E,
+                                          uint8_t* __restrict__ Ag, float* __restrict__ sum_cur, int E,
                                           int EP, unsigned long long* cnt, int inside) {
   const int srow = (s_begin + lane < s_end) ? s_begin + lane : s_begin;
   int outv, a;
@@ -252,13 +252,8 @@ __device__ __forceinline__ void wide_tile(const float colv, const float4* rt_lds
     for (int k = 0; k < 4; ++k)
       if ((base >> 6) + k <= last_group) sp_[k] = __int_as_float(outv);
   }
-  if (ARG) {
-    for (int s = s_begin; s < s_end; ++s) {
-      const unsigned ar = (unsigned)__builtin_amdgcn_readlane(a, s - s_begin);
-      const __amdgpu_buffer_rsrc_t ba = __builtin_amdgcn_make_buffer_rsrc(An + (size_t)s * EP, 0, EP, kBufWord3);
-      __builtin_amdgcn_raw_buffer_store_b32(ar * 0x01010101u, ba, base + 4 * lane, 0, kStreaming);
-    }
-  }
+  if (ARG && s_begin + lane < s_end)
+    *reinterpret_cast<uint32_t*>(Ag + (size_t)(s_begin + lane) * (EP >> 6) + (base >> 6)) = (unsigned)a * 0x01010101u;
   if (cnt && threadIdx.x == 0) {                          // measurement only: workgroups, and their waves
     atomicAdd(cnt, 1ull);
     atomicAdd(cnt + 3, (unsigned long long)inside);
@@ -389,6 +384,9 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
   const float* __restrict__ Cp = c_table(t, inst, row - 1, l - 1);
   float* __restrict__ Cn = c_table(t, inst, row, l);
   uint8_t* __restrict__ An = ARG ? t.A + (size_t)row * S * EP : nullptr;
+  // group records: kept beside A whenever the context uses the run shortcut, by split launches
+  // too (the pointer is formed where it is used: it would stay live across the row loop)
+  constexpr bool GROUPS = ARG && (RUNS || SPLIT);
   const int e0 = wbase + lane;
 
   // Summaries: besides its table every layer leaves, per strategy and per group of 64 budgets
@@ -445,14 +443,14 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
       inside += (st != 2) ? 1 : 0;
     }
     if (__builtin_amdgcn_ballot_w64(!same) == 0) {
-      wide_tile<SP, ARG>(v0, rt_lds, (wave * S) / NW, ((wave + 1) * S) / NW, lane, tile * NW * 64, Cn, An,
-                         sum_cur, E, EP, counts, inside);
+      wide_tile<SP, ARG>(v0, rt_lds, (wave * S) / NW, ((wave + 1) * S) / NW, lane, tile * NW * 64, Cn,
+                         GROUPS ? group_records(t, row) : nullptr, sum_cur, E, EP, counts, inside);
       return;
     }
     if (!present) return;
     if (mine) {
-      uniform_tile<SP, ARG>(v, rt_lds, s_begin, s_end, lane, e0, wbase, Cn, An, sum_cur, E, EP,
-                            counts ? counts + 1 : nullptr);
+      uniform_tile<SP, ARG>(v, rt_lds, s_begin, s_end, lane, e0, wbase, Cn,
+                            GROUPS ? group_records(t, row) : nullptr, sum_cur, E, EP, counts ? counts + 1 : nullptr);
       return;
     }
   }
@@ -584,10 +582,17 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
         const int f = __builtin_amdgcn_readfirstlane(__float_as_int(cp[0][sp]));
         colv = (lane == sp) ? __int_as_float(f) : colv;
       }
-      uniform_tile<SP, ARG>(colv, rt_lds, s_begin, s_end, lane, e0, wbase, Cn, An, sum_cur, E, EP,
-                            counts ? counts + 2 : nullptr);
+      uniform_tile<SP, ARG>(colv, rt_lds, s_begin, s_end, lane, e0, wbase, Cn,
+                            GROUPS ? group_records(t, row) : nullptr, sum_cur, E, EP, counts ? counts + 2 : nullptr);
       return;
     }
+  }
+
+  // this wave's records will be in A, whatever its summary words say (said here, before the row
+  // loop, where registers are free)
+  if (GROUPS) {
+    uint8_t* __restrict__ Ag = group_records(t, row);
+    if (Ag && s_begin + lane < s_end) Ag[(size_t)(s_begin + lane) * (EP >> 6) + (wbase >> 6)] = (uint8_t)kNoGroupRecord;
   }
 
   if (!ARG) {
@@ -823,7 +828,7 @@ struct Blocking {                       // budgets per lane for a given strategy
   // PRE in the kernel) take a few registers more; targets found by compiling every size.  The
   // values-only kernels would fit one wave more at some sizes; measured, that is no gain
   // (S=44: 7 waves 1.80 ms per solve, 5 or 4 waves 1.76).
-  static constexpr int MINW_RUNS = (SP <= 24) ? 8 : (SP <= 36) ? 7 : (SP <= 40) ? 6 : 5;
+  static constexpr int MINW_RUNS = (SP <= 24) ? 8 : (SP == 32) ? 6 : (SP <= 36) ? 7 : (SP <= 40) ? 6 : 5;   // (32: 7 spills four registers)
   static constexpr int MINW_VALUES_RUNS = (SP <= 24) ? 8 : (SP <= 28) ? 7 : (SP <= 32) ? 6 : (SP <= 40) ? 5
                                           : (SP <= 52) ? 4 : (SP <= 56) ? 3 : 5;
 };

@@ -630,6 +630,7 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
   } else {
     TRY(c->d_C.reserve(sizeof(float) * slab * 2 * B));
     TRY(c->d_A.reserve(slab * rows));
+    if (runs) TRY(c->d_asum.reserve((size_t)S * (EP / 64) * rows));
   }
   TRY(c->d_best.reserve(sizeof(float) * (size_t)B * EP));
   TRY(c->d_best_s.reserve((size_t)B * EP));
@@ -644,6 +645,7 @@ extern "C" gbmw_status gbmw_partition_search(const gbmw_partition_problem* q, ui
   t.L = (const int*)c->d_L.p; t.off = (const int*)c->d_off.p; t.perm = (const int*)c->d_perm.p;
   t.c = gc; t.M = gM; t.Rt = (const float*)c->d_Rt.p;
   t.Cbuf = (float*)c->d_C.p; t.A = lazy ? nullptr : (uint8_t*)c->d_A.p;
+  t.Asum = (!lazy && runs) ? (uint8_t*)c->d_asum.p : nullptr;
   t.best = (float*)c->d_best.p; t.best_s = (uint8_t*)c->d_best_s.p;
   t.status = (int*)c->d_status.p;
   t.counts = nullptr;
