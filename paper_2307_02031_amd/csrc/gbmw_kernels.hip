@@ -234,9 +234,9 @@ __device__ __forceinline__ void uniform_tile(const float colv, const float4* rt_
 }
 
 // The same for a whole workgroup whose four waves (256 budgets from `base`) all carry that one
-// column: the waves divide the output strategies instead of the budgets; each writes the four
-// summary words of its strategies and, with records, the four group records (one dword: EP is
-// a multiple of 256, so a row of group records is whole dwords and `base >> 6` a multiple of 4).
+// column: lane j writes the four summary words of strategy s_begin + j and, with records, the
+// four group records (one dword: EP is a multiple of 256, so a row of group records is whole
+// dwords and `base >> 6` a multiple of 4).
 template <int SP, bool ARG>
 __device__ __forceinline__ void wide_tile(const float colv, const float4* rt_lds, int s_begin, int s_end,
                                           int lane, int base, float* __restrict__ Cn,
@@ -443,8 +443,12 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
       inside += (st != 2) ? 1 : 0;
     }
     if (__builtin_amdgcn_ballot_w64(!same) == 0) {
-      wide_tile<SP, ARG>(v0, rt_lds, (wave * S) / NW, ((wave + 1) * S) / NW, lane, tile * NW * 64, Cn,
-                         GROUPS ? group_records(t, row) : nullptr, sum_cur, E, EP, counts, inside);
+      // one wave does it, a lane per output strategy: the loop over the candidates is as long
+      // for eleven lanes as for all of them, and the other three leave their issue slots to
+      // the waves that compute cell by cell
+      if (wave == 0)
+        wide_tile<SP, ARG>(v0, rt_lds, 0, S, lane, tile * NW * 64, Cn,
+                           GROUPS ? group_records(t, row) : nullptr, sum_cur, E, EP, counts, inside);
       return;
     }
     if (!present) return;
