@@ -260,6 +260,35 @@ __device__ __forceinline__ void wide_tile(const float colv, const float4* rt_lds
   }
 }
 
+// How a launch's workgroups map to (instance, tile): the divisors of that mapping come with
+// floor(2^32 / d) from the host, so that a workgroup finds its place with a multiply, a
+// subtract and one correction per division (the quotient estimate is never more than one
+// short) instead of the thirty-instruction sequence of a division by a run-time value: every
+// wave pays for them before it can ask for its first byte.
+constexpr int kDealChunk = 4;                            // consecutive tiles of one instance per XCD
+struct Deal {
+  int n;                                                 // instances in the launch
+  unsigned inv_tiles, inv_rowlen, inv_cl, inv_n;         // of tiles, n * kDealChunk, tiles % kDealChunk, n
+};
+
+__device__ __forceinline__ void divmod(unsigned p, unsigned d, unsigned inv, int& q, int& r) {
+  unsigned qq = __umulhi(p, inv), rr = p - qq * d;
+  if (rr >= d) { ++qq; rr -= d; }
+  q = (int)qq; r = (int)rr;
+}
+
+static unsigned inv_of(unsigned d) { return d <= 1 ? 0xffffffffu : (unsigned)((1ull << 32) / d); }
+
+static Deal make_deal(int tiles, int n) {
+  Deal d;
+  d.n = n;
+  d.inv_tiles = inv_of((unsigned)tiles);
+  d.inv_rowlen = inv_of((unsigned)(n * kDealChunk));
+  d.inv_cl = inv_of((unsigned)(tiles % kDealChunk));
+  d.inv_n = inv_of((unsigned)n);
+  return d;
+}
+
 // RUNS: waves whose budgets share one input column take uniform_tile (never in split mode:
 // those launches are bound by a wave's own latency, which the test would lengthen).
 // COUNT: the same kernel with one atomic per run-path wave or workgroup into t.counts, for
@@ -267,7 +296,7 @@ __device__ __forceinline__ void wide_tile(const float colv, const float4* rt_lds
 // instantiation are those of the plain one, which is the one that is timed (the atomics cost a
 // few registers, and with them occupancy at some sizes).
 template <int SP, int K, int NW, int CH, int MINW, bool FIRST, bool ARG, bool SPLIT, bool RUNS, bool COUNT = false>
-__global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int tiles, int first) {
+__global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int tiles, int first, Deal deal) {
   constexpr bool split = SPLIT;
   static_assert(!(SPLIT && RUNS), "no run shortcut in split mode");
   static_assert(RUNS || !COUNT, "only the run paths are counted");
@@ -303,8 +332,8 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
   // With dense arithmetic every tile costs the same and the plain order is kept.
   int slot, tile;
   if (RUNS) {
-    constexpr int kChunk = 16, kRound = 8 * kChunk;        // one round: a chunk for each XCD
-    const int b = blockIdx.x, nb = gridDim.x, n = nb / tiles;
+    constexpr int kChunk = kDealChunk, kRound = 8 * kChunk;   // one round: a chunk for each XCD
+    const int b = blockIdx.x, nb = gridDim.x, n = deal.n;
     int p = b;                                            // place in the dealt order (the ragged end keeps its own)
     if (b < nb / kRound * kRound) {
       const int w = b % kRound;                           // b = 8 * (round * kChunk + r) + xcd
@@ -313,18 +342,19 @@ __global__ __launch_bounds__(64 * NW, MINW) void k_minplus(Tables t, int l, int 
     const int full = tiles / kChunk, rowlen = n * kChunk;
     int c, k, r;
     if (p < full * rowlen) {
-      c = p / rowlen;
-      const int rem = p - c * rowlen;
+      int rem;
+      divmod((unsigned)p, (unsigned)rowlen, deal.inv_rowlen, c, rem);
       k = rem / kChunk; r = rem % kChunk;
     } else {                                              // the short last chunk of every instance
       const int cl = tiles - full * kChunk, pp = p - full * rowlen;
-      c = full; k = pp / cl; r = pp - k * cl;
+      c = full;
+      divmod((unsigned)pp, (unsigned)cl, deal.inv_cl, k, r);
     }
-    slot = (k + c) % n;
+    int turns;
+    divmod((unsigned)(k + c), (unsigned)n, deal.inv_n, turns, slot);
     tile = c * kChunk + r;
   } else {
-    slot = blockIdx.x / tiles;
-    tile = blockIdx.x % tiles;
+    divmod(blockIdx.x, (unsigned)tiles, deal.inv_tiles, slot, tile);
   }
   const int inst = t.perm[first + slot];
   const int S = t.S, E = t.E, EP = t.EP;
@@ -856,12 +886,12 @@ static void launch_minplus_sp(const Tables& t_in, int l, int first, int n_active
   constexpr int MS = Blocking<SP>::MINW_SPLIT;
 #define GBMW_LAUNCH(MW, FIRST_, ARG_, SPLIT_, RUNS_)                                                        \
   hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, MW, FIRST_, ARG_, SPLIT_, RUNS_>), grid, block, lds, st, t, l, \
-                     tiles, first)
+                     tiles, first, make_deal(tiles, n_active))
   const bool runs = t.runs != 0;
   if (runs && !split && t.counts) {                      // the counting twin of the unsplit run-shortcut kernels
 #define GBMW_LAUNCH_COUNT(FIRST_, ARG_)                                                                      \
   hipLaunchKernelGGL((k_minplus<SP, K, NW, CH, 2, FIRST_, ARG_, false, true, true>), grid, block, lds, st, t, l, \
-                     tiles, first)
+                     tiles, first, make_deal(tiles, n_active))
     if (t.A == nullptr) { if (l == 1) GBMW_LAUNCH_COUNT(true, false); else GBMW_LAUNCH_COUNT(false, false); }
     else { if (l == 1) GBMW_LAUNCH_COUNT(true, true); else GBMW_LAUNCH_COUNT(false, true); }
 #undef GBMW_LAUNCH_COUNT
@@ -905,10 +935,10 @@ static void launch_minplus_big(const Tables& t, int l, int first, int n_active, 
   const size_t lds = (size_t)t.S * RS * sizeof(float);
   if (t.A == nullptr)
     hipLaunchKernelGGL((k_minplus<SP, 1, NW, CH, Blocking<SP>::MINW_VALUES, false, false, false, false>), grid, block, lds,
-                       st, t, l, tiles, first);
+                       st, t, l, tiles, first, make_deal(tiles, n_active));
   else
     hipLaunchKernelGGL((k_minplus<SP, 1, NW, CH, Blocking<SP>::MINW, false, true, false, false>), grid, block, lds, st, t,
-                       l, tiles, first);
+                       l, tiles, first, make_deal(tiles, n_active));
 }
 
 void launch_minplus(const Tables& t, int l, int first, int n_active, hipStream_t st, int n_prev) {
