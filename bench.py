@@ -118,7 +118,8 @@ def kernel_roofline(g, torch, p, d, args, flags, step_sec):
     upd_dense = tot[3] * 64 * S                                            # a row: 64 lanes x S' candidates
     upd_exec = upd_runs + upd_dense
     covered = p.executed_updates()
-    # HBM bytes by path (the R tile of a workgroup, S x (S'+2) floats, is re-read from the L2 and left out):
+    # HBM bytes by path (the R tile of an instance's layer, S x (S'+2) floats padded to quads, comes from
+    # HBM once per XCD, whose L2 then serves the workgroups):
     #   dense row (wave, s): 64 x 4 B of the previous table read (not in the layer-1 launch), 64 x 4 B of
     #     the new table and 64 x 1 B of records written, one summary word
     #     (with the run shortcut also the byte that says the group's records are in A)
@@ -130,7 +131,9 @@ def kernel_roofline(g, torch, p, d, args, flags, step_sec):
     sumw = 0 if dense else 4
     grp = rec if not dense else 0
     read_b = write_b = 0
+    RS = (S + 3) // 4 * 4 + 4                                              # a row of the R tile in floats
     for i, w in enumerate(work):
+        read_b += int((p.L > i + 1).sum()) * 8 * S * RS * 4                # launch i is layer i + 1 (one stream)
         read_b += w[3] * (256 if i > 0 else 0) + (w[1] + w[2] + 4 * w[0]) * 12 * S + (w[2] * 256 * S if i > 0 else 0)
         write_b += w[3] * (256 + 64 * rec + sumw + grp) + (w[1] + w[2]) * S * (rec + 4) + w[0] * S * (4 * rec + 16)
     avg_launch_s = mp_ms / mp_n * 1e-3 if mp_n else float("nan")
