@@ -374,10 +374,12 @@ def main():
     window = min(256, p.E + 1)
     qi = np.repeat(np.arange(p.B, dtype=np.int32), window)
     qe = np.tile(np.arange(p.E - window + 1, p.E + 1, dtype=np.int32), p.B)
-    g.gbmw_backtrack(lt, qi[:64], qe[:64])
-    t0 = time.perf_counter()
-    g.gbmw_backtrack(lt, qi, qe)
-    lbt = time.perf_counter() - t0
+    g.gbmw_backtrack(lt, qi, qe)                            # first call: the staging block is allocated
+    lbt = float("inf")
+    for _ in range(3):
+        t0 = time.perf_counter()
+        g.gbmw_backtrack(lt, qi, qe)
+        lbt = min(lbt, time.perf_counter() - t0)
     g.gbmw_destroy(lt)
     lr = kernel_roofline(g, torch, p, d, args, lflags, lsec)
     out["lazy_argmin"] = dict(
@@ -389,13 +391,16 @@ def main():
                   "frac_of_instr_floor cannot")
     # row a4: plans for a window of budgets below E for every instance (the E_fwd window
     # Algorithm 3 inspects), timed end to end through the ABI (upload, walk, download)
-    g.gbmw_backtrack(ctx, qi[:64], qe[:64])
-    t0 = time.perf_counter()
-    plan, cost, mem = g.gbmw_backtrack(ctx, qi, qe)
-    bt = time.perf_counter() - t0
+    g.gbmw_backtrack(ctx, qi, qe)                           # first call: the staging block is allocated
+    bt = float("inf")
+    for _ in range(3):
+        t0 = time.perf_counter()
+        plan, cost, mem = g.gbmw_backtrack(ctx, qi, qe)
+        bt = min(bt, time.perf_counter() - t0)
     out["backtrack"] = {"queries": int(len(qi)), "ms": bt * 1e3, "plans_per_s": len(qi) / bt,
-                        "note": "host-to-host through gbmw_backtrack: query upload, one lane per "
-                                "query walking L_b argmin records, plan download"}
+                        "note": "host-to-host through gbmw_backtrack, best of 3 after a first call that "
+                                "allocates the staging block: query upload, one lane per query walking "
+                                "L_b argmin records, plan download"}
     # Algorithm 3's outer loop (overall-memory check over the b_up window, largest valid
     # E_fwd and its plan per instance) on synthetic O_f / O_b / O_ms with O_f + O_ms == M
     Of, Ob, Oms = gi.split_memory(p, 4)
