@@ -998,11 +998,15 @@ __global__ __launch_bounds__(256) void k_final(Tables t, int first) {
         const int m = Ml[s + i];
         idx[i] = (m < 0) ? -1 : e - m;
         w[i] = Ts[(size_t)(s + i) * (t.EP >> 6) + ((idx[i] > 0 ? idx[i] : 0) >> 6)];
-        x[i] = C[(size_t)(s + i) * t.EP + e];
       }
+      // the cell is asked for only where its group's word does not stand for it (most groups
+      // of a step-function table are runs: their cells were never written and need not be read)
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        x[i] = (idx[i] >= 0 && is_nan_bits(__float_as_int(w[i]))) ? C[(size_t)(s + i) * t.EP + e] : w[i];
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        const float v = idx[i] < 0 ? INFINITY : is_nan_bits(__float_as_int(w[i])) ? x[i] : w[i];
+        const float v = idx[i] < 0 ? INFINITY : x[i];
         if (v < b) { b = v; a = s + i; }
       }
     }
